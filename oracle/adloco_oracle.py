@@ -1,0 +1,240 @@
+"""CPU oracle for the AdLoCo data-parallel hot path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this
+module.  The HIP library never calls it and shares no code, table or constant with it.
+
+Everything is written as the plain definition, in fp64 (numpy), with no blocking, fusion
+or reordering: per-sample gradients are materialised explicitly as d_out x d_in matrices
+(one library matmul per sample, `delta_i.T @ a_i`), norms are sums of squared entries,
+the variance is the two-pass mean-of-squared-deviations, and the outer step and the merge
+are element-wise formulas.  The Gram identity that the GPU path uses is deliberately NOT
+used here.
+
+Notation (paper, Section 2.1 and Section 3.3.1): a batch B_k of b_k samples; per-sample
+gradient grad f(x_k; xi_i) =: g_i; mini-batch gradient g_k = (1/b_k) sum_i g_i (eq. 1).
+For one linear layer with weight W [d_out, d_in], sample i with activations
+a_i [T, d_in] and output gradients delta_i [T, d_out] has g_i = delta_i^T a_i.
+
+Pins (tests/test_oracle_pins.py): hand closed forms for T = 1, 2; orthonormal / constant
+token rows; permutation and rotation invariance; element-by-element brute force; torch
+autograd of a bias-free linear layer; numpy's var(ddof=1) over the stacked per-sample
+gradients; iid-noise expectation B/eta^2; LocalSGD averaging (Section 3.1) and
+torch.optim.SGD(nesterov=True) for the outer step; convexity / identity cases for the
+merge; Algorithm 1's branches enumerated by hand.
+
+Parity unpinned (the paper fixes none of these; they are readings documented in the
+design notes): the 1/(B-1) normalisation of the variance, the B = 1 convention, the
+monotone clamp b_req >= b_cur and the optional ceiling b_cap.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+INT64_MAX = (1 << 63) - 1
+
+
+# --------------------------------------------------------------------------------------
+# Input widening (exact; the oracle sees the very bits the GPU sees)
+# --------------------------------------------------------------------------------------
+
+def widen(x) -> np.ndarray:
+    """fp32 array, or uint16 array of bf16 bit patterns  ->  fp64, exactly."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if x.dtype in (np.float32, np.float64):
+        return x.astype(np.float64)
+    raise TypeError(f"unsupported input dtype {x.dtype}")
+
+
+# --------------------------------------------------------------------------------------
+# Gradient statistics (eq. 1; variance of Section 3.3.1)
+# --------------------------------------------------------------------------------------
+
+def per_sample_gradient(a_i, delta_i) -> np.ndarray:
+    """g_i = sum_t delta_{i,t} a_{i,t}^T  as an explicit [d_out, d_in] fp64 matrix."""
+    a_i = widen(a_i)
+    delta_i = widen(delta_i)
+    assert a_i.ndim == 2 and delta_i.ndim == 2 and a_i.shape[0] == delta_i.shape[0]
+    return delta_i.T @ a_i
+
+
+def grad_stats(layers, two_pass: bool = True) -> dict:
+    """Statistics of the per-sample gradients of a list of linear layers.
+
+    layers: list of (a [B,T,d_in], delta [B,T,d_out]) sharing B and T.
+    Returns
+      n_layer_sample [L,B]  ||g_i^l||_F^2
+      n_sample       [B]    ||g_i||^2 = sum_l ||g_i^l||^2   (g_i = concatenation over layers)
+      S1                    sum_i ||g_i||^2
+      G              list   sum_i g_i^l   (B times the mini-batch gradient of eq. 1)
+      S2                    ||sum_i g_i||^2
+      batch_grad_sqnorm     ||g_k||^2 = S2 / B^2            (eq. 1)
+      V                     sum_i ||g_i - g_k||^2, by a second explicit pass (two_pass only)
+    """
+    L = len(layers)
+    B = int(np.asarray(layers[0][0]).shape[0])
+    n_ls = np.zeros((L, B), dtype=np.float64)
+    G = []
+    for l, (a, delta) in enumerate(layers):
+        a = np.asarray(a)
+        delta = np.asarray(delta)
+        assert a.shape[0] == B and delta.shape[0] == B and a.shape[1] == delta.shape[1]
+        Gl = np.zeros((delta.shape[2], a.shape[2]), dtype=np.float64)
+        for i in range(B):
+            g = per_sample_gradient(a[i], delta[i])
+            n_ls[l, i] = np.sum(g * g)
+            Gl += g
+        G.append(Gl)
+    n_s = n_ls.sum(axis=0)
+    S1 = float(n_s.sum())
+    S2 = float(sum(np.sum(Gl * Gl) for Gl in G))
+    out = dict(n_layer_sample=n_ls, n_sample=n_s, S1=S1, G=G, S2=S2, B=B,
+               batch_grad_sqnorm=S2 / (B * B) if B > 0 else float("nan"))
+    if two_pass:
+        V = 0.0
+        for l, (a, delta) in enumerate(layers):
+            gbar = G[l] / B
+            for i in range(B):
+                dev = per_sample_gradient(np.asarray(a)[i], np.asarray(delta)[i]) - gbar
+                V += float(np.sum(dev * dev))
+        out["V"] = V
+    return out
+
+
+def concat_micro_batches(micro_batches):
+    """Switch mode (Algorithm 3, accumulate branch): the effective batch is the union of the
+    micro-batches.  micro_batches: list over micro-batches of layer lists [(a, delta), ...].
+    Returns one layer list over the concatenated samples."""
+    L = len(micro_batches[0])
+    out = []
+    for l in range(L):
+        a = np.concatenate([np.asarray(mb[l][0]) for mb in micro_batches], axis=0)
+        d = np.concatenate([np.asarray(mb[l][1]) for mb in micro_batches], axis=0)
+        out.append((a, d))
+    return out
+
+
+# --------------------------------------------------------------------------------------
+# Norm test, batch rule, switch mode (Section 3.3.1; Section 4.2; Algorithm 3)
+# --------------------------------------------------------------------------------------
+
+def variance(V: float, B: int, biased: bool = False) -> float:
+    """sigma^2_{B_k}: trace of the sample covariance of the per-sample gradients.
+    V = sum_i ||g_i - g_k||^2.  Unbiased 1/(B-1) by default (a reading; parity unpinned)."""
+    if biased:
+        return V / B
+    return V / (B - 1)
+
+
+def switch_mode(b_req: int, b_max: int, n_switch: int = 2) -> dict:
+    """SwitchMode (Section 4.2; Algorithm 3): gradient accumulation only when the requested
+    batch exceeds n * max_batch; then accum = ceil(b_req / b_max) micro-batches of b_max;
+    otherwise a single micro-batch of min(b_req, b_max)."""
+    if b_req > n_switch * b_max:
+        return dict(accumulate=1, accum_steps=-(-b_req // b_max), b_micro=b_max)
+    return dict(accumulate=0, accum_steps=1, b_micro=min(b_req, b_max))
+
+
+def norm_test(S1: float, S2: float, B: int, eta: float, b_cur: int, b_max: int,
+              n_switch: int = 2, b_cap: int = 0, biased_var: bool = False,
+              allow_shrink: bool = False, V: float | None = None) -> dict:
+    """Approximate norm test (eq. 4) and the batch rule b_{k+1} = ceil(sigma^2 /
+    (eta^2 ||grad F_B||^2)) of Section 3.3.1, followed by SwitchMode.
+
+    If V (two-pass sum of squared deviations) is given it defines sigma^2; otherwise
+    sigma^2 comes from S1 - S2/B.  The test passes when b_cur >= sigma^2/(eta^2 ||g_k||^2),
+    the rearranged form of eq. 4.
+    """
+    res = dict(S1=S1, S2=S2, b_cur=int(b_cur), stat_undefined=0)
+    gnorm2 = S2 / (float(B) * float(B)) if B > 0 else float("nan")
+    res["batch_grad_sqnorm"] = gnorm2
+    ceiling = b_cap if b_cap > 0 else INT64_MAX
+    if B < 2 and not biased_var or B < 1:
+        # one sample: the sample variance is 0/0 -> ask for two samples so it becomes defined
+        res.update(variance=float("nan"), stat=float("nan"), stat_undefined=1, test_passed=0)
+        b_req = min(ceiling, max(int(b_cur), 2))
+    else:
+        dev = V if V is not None else max(S1 - S2 / B, 0.0)
+        sigma2 = variance(dev, B, biased_var)
+        res["variance"] = sigma2
+        if gnorm2 > 0.0:
+            stat = sigma2 / (eta * eta * gnorm2)
+        else:
+            stat = float("inf") if sigma2 > 0.0 else 0.0
+        res["stat"] = stat
+        res["test_passed"] = 1 if stat <= b_cur else 0
+        if math.isinf(stat) or stat >= float(ceiling):
+            b_raw = ceiling
+        else:
+            b_raw = int(math.ceil(stat))
+        b_req = b_raw if allow_shrink else max(int(b_cur), b_raw)
+        b_req = min(ceiling, max(b_req, 1))
+    res["b_req"] = int(b_req)
+    res.update(switch_mode(int(b_req), int(b_max), int(n_switch)))
+    return res
+
+
+# --------------------------------------------------------------------------------------
+# Outer step (Algorithm 3, pseudo-gradient and OuterOpt lines; worker reset line)
+# --------------------------------------------------------------------------------------
+
+def outer_step(theta_outer, thetas, momentum, lr: float, mu: float, nesterov: bool = True,
+               broadcast: bool = False) -> dict:
+    """Delta = (1/M) sum_m (x^{(t-1)} - x_m^{(t,H)});  x <- OuterOpt(x, Delta) with OuterOpt
+    = SGD with (Nesterov) momentum:  buf <- mu*buf + Delta;  step = Delta + mu*buf (Nesterov)
+    or buf (heavy ball);  x <- x - lr*step.  mu = 0 is plain SGD.  fp64 arithmetic on the
+    fp32 inputs, rounded to fp32 once at the end.  broadcast: every instance is reset to the
+    new outer parameters (start of the next round)."""
+    x = widen(theta_outer)
+    M = len(thetas)
+    delta = np.zeros_like(x)
+    for th in thetas:
+        delta += x - widen(th)
+    delta /= M
+    buf = widen(momentum) if momentum is not None else np.zeros_like(x)
+    buf = mu * buf + delta
+    step = delta + mu * buf if nesterov else buf
+    x_new = x - lr * step
+    out = dict(theta_outer=x_new.astype(np.float32), momentum=buf.astype(np.float32),
+               pseudo_grad=delta.astype(np.float32), theta_outer_f64=x_new,
+               momentum_f64=buf, pseudo_grad_f64=delta)
+    if broadcast:
+        out["thetas"] = [x_new.astype(np.float32) for _ in range(M)]
+    return out
+
+
+# --------------------------------------------------------------------------------------
+# Trainer merge (Section 4.1.1; Algorithms 1 and 2)
+# --------------------------------------------------------------------------------------
+
+def check_merge(b_req, w: int):
+    """CheckMerge (Algorithm 1): nothing when w = 0 or at most one trainer; otherwise the w
+    trainers with the smallest requested batch when w <= k, else nothing.  Ties keep the
+    lower index first (stable sort)."""
+    k = len(b_req)
+    if w == 0 or k <= 1:
+        return []
+    order = sorted(range(k), key=lambda i: b_req[i])
+    if w <= k:
+        return order[:w]
+    return []
+
+
+def merge(xs, weights, rep: int = -1) -> dict:
+    """DoMerge (Algorithm 2): x_merge = sum_j b_j x_j / sum_j b_j; the representative
+    r = argmax b_j (lowest index on ties) receives x_merge; the others are left as they are
+    (the caller drops them)."""
+    S = len(xs)
+    assert S == len(weights) and S >= 1
+    w = np.asarray(weights, dtype=np.float64)
+    wsum = float(w.sum())
+    acc = np.zeros_like(widen(xs[0]))
+    for j in range(S):
+        acc += w[j] * widen(xs[j])
+    acc /= wsum
+    if rep < 0:
+        rep = int(np.argmax(w))        # first maximal element
+    return dict(rep=rep, x_merge=acc.astype(np.float32), x_merge_f64=acc)

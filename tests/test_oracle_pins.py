@@ -1,0 +1,456 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, independent of the
+oracle's own formulas (hand-worked fixtures, closed forms, brute force, library routines
+reached by another route).  CPU only."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+import adloco_synth as synth
+from oracle import adloco_oracle as orc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _lines(name):
+    with open(os.path.join(GOLD, name)) as f:
+        for ln in f:
+            ln = ln.rstrip("\n")
+            if ln.strip() and not ln.lstrip().startswith("#"):
+                yield ln
+
+
+def _ints(s):
+    s = s.strip()
+    return [int(v) for v in s.split(",")] if s else []
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+# ------------------------------------------------------------------ per-sample norms
+
+def test_gram_hand_cases():
+    # g = sum_t delta_t a_t^T, norms worked by hand (tests/golden/gram_hand_cases.txt)
+    n = 0
+    for ln in _lines("gram_hand_cases.txt"):
+        lhs, want = ln.split("->")
+        dims, a, d = lhs.split(";")
+        T, di, do = [int(v) for v in dims.split()]
+        a = np.array([float(v) for v in a.split(",")], dtype=np.float32).reshape(1, T, di)
+        d = np.array([float(v) for v in d.split(",")], dtype=np.float32).reshape(1, T, do)
+        st = orc.grad_stats([(a, d)])
+        assert st["n_sample"][0] == pytest.approx(float(want), abs=1e-12)
+        n += 1
+    assert n >= 6
+
+
+def test_T1_closed_form():
+    # one token: g = delta a^T  =>  ||g||^2 = ||a||^2 ||delta||^2
+    r = _rng(1)
+    a = r.standard_normal((5, 1, 7)).astype(np.float32)
+    d = r.standard_normal((5, 1, 3)).astype(np.float32)
+    st = orc.grad_stats([(a, d)])
+    want = (a.astype(np.float64) ** 2).sum(axis=(1, 2)) * (d.astype(np.float64) ** 2).sum(axis=(1, 2))
+    np.testing.assert_allclose(st["n_sample"], want, rtol=1e-13)
+
+
+def test_T2_closed_form():
+    # two tokens: ||a1||^2||d1||^2 + ||a2||^2||d2||^2 + 2 (a1.a2)(d1.d2)
+    r = _rng(2)
+    a = r.standard_normal((4, 2, 6))
+    d = r.standard_normal((4, 2, 5))
+    st = orc.grad_stats([(a, d)])
+    for i in range(4):
+        a1, a2, d1, d2 = a[i, 0], a[i, 1], d[i, 0], d[i, 1]
+        want = (a1 @ a1) * (d1 @ d1) + (a2 @ a2) * (d2 @ d2) + 2 * (a1 @ a2) * (d1 @ d2)
+        assert st["n_sample"][i] == pytest.approx(want, rel=1e-12)
+
+
+def test_orthonormal_tokens():
+    # orthonormal activation rows: ||sum_t delta_t a_t^T||^2 = sum_t ||delta_t||^2
+    r = _rng(3)
+    T, di, do = 6, 9, 4
+    q, _ = np.linalg.qr(r.standard_normal((di, di)))
+    a = q[:T][None]                       # [1,T,di] orthonormal rows
+    d = r.standard_normal((1, T, do))
+    st = orc.grad_stats([(a, d)])
+    assert st["n_sample"][0] == pytest.approx((d ** 2).sum(), rel=1e-12)
+
+
+def test_constant_tokens():
+    # every token has the same activation: g = (sum_t delta_t) a^T
+    r = _rng(4)
+    T, di, do = 5, 8, 3
+    a0 = r.standard_normal(di)
+    a = np.broadcast_to(a0, (1, T, di)).copy()
+    d = r.standard_normal((1, T, do))
+    st = orc.grad_stats([(a, d)])
+    want = (a0 @ a0) * (d[0].sum(axis=0) ** 2).sum()
+    assert st["n_sample"][0] == pytest.approx(want, rel=1e-12)
+
+
+def test_token_permutation_and_rotation_invariance():
+    r = _rng(5)
+    B, T, di, do = 3, 7, 6, 5
+    a = r.standard_normal((B, T, di))
+    d = r.standard_normal((B, T, do))
+    base = orc.grad_stats([(a, d)])
+    perm = r.permutation(T)
+    st = orc.grad_stats([(a[:, perm], d[:, perm])])
+    np.testing.assert_allclose(st["n_sample"], base["n_sample"], rtol=1e-12)
+    assert st["S2"] == pytest.approx(base["S2"], rel=1e-12)
+    Q, _ = np.linalg.qr(r.standard_normal((di, di)))
+    R, _ = np.linalg.qr(r.standard_normal((do, do)))
+    st = orc.grad_stats([(a @ Q, d @ R)])
+    np.testing.assert_allclose(st["n_sample"], base["n_sample"], rtol=1e-11)
+    assert st["S2"] == pytest.approx(base["S2"], rel=1e-11)
+    # permuting tokens of a only (not delta) must change the result: guards a dropped pairing
+    st = orc.grad_stats([(a[:, perm], d)])
+    assert not np.allclose(st["n_sample"], base["n_sample"], rtol=1e-6)
+
+
+def test_brute_force_tiny_config():
+    # Config 1 element by element with python loops, no matmul: G[e][c] = sum_t delta[t][e]*a[t][c]
+    inp = synth.grad_stats_inputs(1)[0]
+    a, d = inp["a"], inp["delta"]
+    B, T, di = a.shape
+    do = d.shape[2]
+    st = orc.grad_stats([(a, d)])
+    tot = [[0.0] * di for _ in range(do)]
+    for i in range(B):
+        n = 0.0
+        for e in range(do):
+            for c in range(di):
+                s = 0.0
+                for t in range(T):
+                    s += float(d[i, t, e]) * float(a[i, t, c])
+                n += s * s
+                tot[e][c] += s
+        assert st["n_sample"][i] == pytest.approx(n, rel=1e-12)
+    S2 = sum(v * v for row in tot for v in row)
+    assert st["S2"] == pytest.approx(S2, rel=1e-12)
+    assert st["batch_grad_sqnorm"] == pytest.approx(S2 / B ** 2, rel=1e-12)
+    np.testing.assert_allclose(st["G"][0], np.array(tot), rtol=1e-11, atol=1e-12)
+
+
+def test_autograd_linear_layer():
+    # library route: per-sample weight gradient of a bias-free linear layer y = a W^T with
+    # loss sum <delta, y> is delta^T a
+    import torch
+    r = _rng(6)
+    B, T, di, do = 4, 5, 6, 3
+    a = r.standard_normal((B, T, di))
+    d = r.standard_normal((B, T, do))
+    st = orc.grad_stats([(a, d)])
+    W = torch.zeros(do, di, dtype=torch.float64, requires_grad=True)
+    tot = torch.zeros(do, di, dtype=torch.float64)
+    for i in range(B):
+        y = torch.from_numpy(a[i]) @ W.T
+        (g,) = torch.autograd.grad((torch.from_numpy(d[i]) * y).sum(), W)
+        assert st["n_sample"][i] == pytest.approx(float((g ** 2).sum()), rel=1e-12)
+        np.testing.assert_allclose(orc.per_sample_gradient(a[i], d[i]), g.numpy(), rtol=1e-12,
+                                   atol=1e-14)
+        tot += g
+    assert st["S2"] == pytest.approx(float((tot ** 2).sum()), rel=1e-12)
+
+
+def test_transposed_operand_detected():
+    # d_in != d_out: the gradient is [d_out, d_in]; its sum over samples must match einsum
+    r = _rng(7)
+    a = r.standard_normal((3, 4, 5))
+    d = r.standard_normal((3, 4, 2))
+    st = orc.grad_stats([(a, d)])
+    G = np.einsum("ite,itc->ec", d, a)
+    assert st["G"][0].shape == (2, 5)
+    np.testing.assert_allclose(st["G"][0], G, rtol=1e-12, atol=1e-14)
+
+
+def test_layers_concatenate():
+    # g_i is the concatenation over layers: norms add across layers
+    r = _rng(8)
+    l1 = (r.standard_normal((3, 4, 5)), r.standard_normal((3, 4, 2)))
+    l2 = (r.standard_normal((3, 4, 3)), r.standard_normal((3, 4, 6)))
+    s1, s2, s12 = orc.grad_stats([l1]), orc.grad_stats([l2]), orc.grad_stats([l1, l2])
+    np.testing.assert_allclose(s12["n_sample"], s1["n_sample"] + s2["n_sample"], rtol=1e-13)
+    assert s12["S2"] == pytest.approx(s1["S2"] + s2["S2"], rel=1e-13)
+    assert s12["V"] == pytest.approx(s1["V"] + s2["V"], rel=1e-12)
+    np.testing.assert_allclose(s12["n_layer_sample"][1], s2["n_sample"], rtol=1e-13)
+
+
+def test_bf16_widening_is_exact():
+    x = synth.normal_f32(11, (1000,), 1.0)
+    bits = synth.f32_to_bf16_bits(x)
+    import torch
+    t = torch.from_numpy(x).to(torch.bfloat16)
+    np.testing.assert_array_equal(bits, t.view(torch.int16).numpy().view(np.uint16))
+    np.testing.assert_array_equal(orc.widen(bits), t.to(torch.float64).numpy())
+
+
+# ------------------------------------------------------------------ S2, variance, identity
+
+def test_identical_samples():
+    r = _rng(9)
+    a1 = r.standard_normal((1, 4, 5))
+    d1 = r.standard_normal((1, 4, 3))
+    B = 6
+    a, d = np.repeat(a1, B, axis=0), np.repeat(d1, B, axis=0)
+    st = orc.grad_stats([(a, d)])
+    n1 = orc.grad_stats([(a1, d1)])["n_sample"][0]
+    assert st["S2"] == pytest.approx(B * B * n1, rel=1e-12)
+    assert st["V"] == pytest.approx(0.0, abs=1e-20 * n1 + 1e-22)
+    res = orc.norm_test(st["S1"], st["S2"], B, 0.3, b_cur=B, b_max=32, V=st["V"])
+    assert res["stat"] == pytest.approx(0.0, abs=1e-12) and res["b_req"] == B
+
+
+def test_sample_permutation_invariance():
+    r = _rng(10)
+    a = r.standard_normal((5, 3, 4))
+    d = r.standard_normal((5, 3, 2))
+    p = r.permutation(5)
+    s0, s1 = orc.grad_stats([(a, d)]), orc.grad_stats([(a[p], d[p])])
+    assert s1["S1"] == pytest.approx(s0["S1"], rel=1e-13)
+    assert s1["S2"] == pytest.approx(s0["S2"], rel=1e-12)
+    assert s1["V"] == pytest.approx(s0["V"], rel=1e-12)
+    np.testing.assert_allclose(s1["n_sample"], s0["n_sample"][p], rtol=1e-13)
+
+
+@pytest.mark.parametrize("seed,rho", [(20, 0.0), (21, 0.6), (22, 0.95)])
+def test_variance_identity_and_numpy_var(seed, rho):
+    # sum ||g_i - gbar||^2 = sum ||g_i||^2 - B ||gbar||^2, and the two-pass value equals numpy's
+    # var(ddof=1) summed over coordinates of the stacked per-sample gradients
+    layers = synth.custom_grad_stats_inputs(seed, [(6, 4), (5, 7)], B=7, T=5, dtype="f32",
+                                            std_a=1.0, std_delta=1.0, rho=rho)
+    lay = [(l["a"], l["delta"]) for l in layers]
+    st = orc.grad_stats(lay)
+    B = 7
+    assert st["V"] == pytest.approx(st["S1"] - st["S2"] / B, rel=1e-10)
+    assert st["V"] == pytest.approx(st["S1"] - B * st["batch_grad_sqnorm"], rel=1e-10)
+    flat = np.stack([np.concatenate([orc.per_sample_gradient(a[i], d[i]).ravel() for a, d in lay])
+                     for i in range(B)])
+    assert orc.variance(st["V"], B) == pytest.approx(flat.var(axis=0, ddof=1).sum(), rel=1e-11)
+    assert orc.variance(st["V"], B, biased=True) == pytest.approx(flat.var(axis=0).sum(), rel=1e-11)
+    assert st["batch_grad_sqnorm"] == pytest.approx((flat.mean(axis=0) ** 2).sum(), rel=1e-11)
+
+
+def test_iid_noise_expectation():
+    # iid zero-mean inputs: E||g_i||^2 = T d_in d_out s_a^2 s_d^2 and stat -> B/eta^2
+    B, T, di, do = 16, 12, 48, 40
+    layers = synth.custom_grad_stats_inputs(30, [(di, do)], B=B, T=T, dtype="f32",
+                                            std_a=1.0, std_delta=0.5)
+    st = orc.grad_stats([(layers[0]["a"], layers[0]["delta"])])
+    assert st["S1"] / B == pytest.approx(T * di * do * 0.25, rel=0.1)
+    res = orc.norm_test(st["S1"], st["S2"], B, 0.5, b_cur=B, b_max=8, V=st["V"])
+    assert res["stat"] == pytest.approx(B / 0.25, rel=0.25)
+    assert res["test_passed"] == 0 and res["accumulate"] == 1
+
+
+def test_micro_batch_concatenation():
+    layers = synth.custom_grad_stats_inputs(40, [(6, 4)], B=6, T=3, dtype="f32", std_delta=1.0,
+                                            rho=0.5)
+    a, d = layers[0]["a"], layers[0]["delta"]
+    whole = orc.grad_stats([(a, d)])
+    cat = orc.concat_micro_batches([[(a[:2], d[:2])], [(a[2:4], d[2:4])], [(a[4:], d[4:])]])
+    st = orc.grad_stats(cat)
+    assert st["S1"] == whole["S1"] and st["S2"] == whole["S2"] and st["B"] == 6
+
+
+# ------------------------------------------------------------------ decisions
+
+def test_norm_test_hand_cases():
+    n = 0
+    for ln in _lines("norm_test_hand_cases.txt"):
+        lhs, rhs = ln.split("->")
+        S1, S2, B, eta, b_cur, biased, shrink, cap = lhs.split()
+        var, stat, b_req, passed = rhs.split()
+        res = orc.norm_test(float(S1), float(S2), int(B), float(eta), int(b_cur), b_max=1 << 40,
+                            b_cap=int(cap), biased_var=bool(int(biased)),
+                            allow_shrink=bool(int(shrink)))
+        assert res["variance"] == pytest.approx(float(var), rel=1e-12)
+        if math.isinf(float(stat)):
+            assert math.isinf(res["stat"])
+        else:
+            assert res["stat"] == pytest.approx(float(stat), rel=1e-12)
+        assert res["b_req"] == int(b_req), ln
+        assert res["test_passed"] == int(passed), ln
+        n += 1
+    assert n >= 10
+
+
+def test_norm_test_explicit_vectors():
+    # the hand case again, but through explicit gradients realised as a T=1 linear layer
+    # with d_in = 1: g_i = delta_i * a_i with a_i = 1  ->  g_i = delta_i in R^2
+    g = np.array([[1, 0], [0, 1], [1, 1], [2, 2]], dtype=np.float64)
+    a = np.ones((4, 1, 1))
+    d = g.reshape(4, 1, 2)
+    st = orc.grad_stats([(a, d)])
+    assert (st["S1"], st["S2"], st["V"]) == (12.0, 32.0, 4.0)
+    res = orc.norm_test(st["S1"], st["S2"], 4, 0.5, b_cur=2, b_max=64, V=st["V"])
+    assert res["variance"] == pytest.approx(4 / 3) and res["b_req"] == 3
+    assert res["test_passed"] == 0
+
+
+def test_eq4_equivalence_and_monotone():
+    # eq. 4 rearranged: pass <=> b_cur >= sigma^2/(eta^2 ||g||^2); requested batch never shrinks
+    r = _rng(50)
+    for _ in range(200):
+        B = int(r.integers(2, 40))
+        S2 = float(r.uniform(0.1, 10.0)) * B
+        S1 = S2 / B + float(r.uniform(0.0, 50.0))
+        eta = float(r.uniform(0.05, 0.95))
+        b_cur = int(r.integers(1, 300))
+        res = orc.norm_test(S1, S2, B, eta, b_cur, b_max=32)
+        sigma2 = (S1 - S2 / B) / (B - 1)
+        g2 = S2 / B ** 2
+        # E||g_k - grad F||^2 ~ sigma^2 / b  <= eta^2 ||grad F||^2
+        assert res["test_passed"] == int(sigma2 / b_cur <= eta * eta * g2 * (1 + 1e-15))
+        assert res["b_req"] >= b_cur
+        assert res["b_req"] >= math.ceil(res["stat"]) or res["b_req"] == b_cur
+        raw = orc.norm_test(S1, S2, B, eta, b_cur, b_max=32, allow_shrink=True)
+        assert raw["b_req"] == max(1, math.ceil(sigma2 / (eta * eta * g2)))
+
+
+def test_single_sample_and_zero_gradient_conventions():
+    res = orc.norm_test(5.0, 5.0, 1, 0.3, b_cur=1, b_max=32)
+    assert res["stat_undefined"] == 1 and res["b_req"] == 2 and res["test_passed"] == 0
+    res = orc.norm_test(2.0, 0.0, 2, 0.3, b_cur=2, b_max=32, b_cap=0)
+    assert math.isinf(res["stat"]) and res["b_req"] == orc.INT64_MAX and res["accumulate"] == 1
+    res = orc.norm_test(0.0, 0.0, 4, 0.3, b_cur=4, b_max=32)
+    assert res["stat"] == 0.0 and res["b_req"] == 4 and res["test_passed"] == 1
+
+
+def test_switch_mode_cases():
+    n = 0
+    for ln in _lines("switch_mode_cases.txt"):
+        lhs, rhs = ln.split("->")
+        b_req, b_max, nsw = [int(v) for v in lhs.split()]
+        acc, steps, micro = [int(v) for v in rhs.split()]
+        got = orc.switch_mode(b_req, b_max, nsw)
+        assert (got["accumulate"], got["accum_steps"], got["b_micro"]) == (acc, steps, micro), ln
+        # the micro-batches always cover the requested batch when accumulating
+        if acc:
+            assert steps * micro >= b_req > (steps - 1) * micro
+        n += 1
+    assert n >= 12
+
+
+def test_check_merge_cases():
+    n = 0
+    for ln in _lines("check_merge_cases.txt"):
+        b, w, want = ln.split(";")
+        assert orc.check_merge(_ints(b), int(w)) == _ints(want), ln
+        n += 1
+    assert n >= 12
+
+
+# ------------------------------------------------------------------ outer step
+
+def _outer_case(seed=60, N=257, M=3):
+    r = _rng(seed)
+    th = (0.02 * r.standard_normal(N)).astype(np.float32)
+    ins = [(th - (1e-3 * r.standard_normal(N)).astype(np.float32)) for _ in range(M)]
+    mom = (1e-4 * r.standard_normal(N)).astype(np.float32)
+    return th, ins, mom
+
+
+def test_outer_m1_lr1_mu0_returns_inner_model():
+    th, ins, _ = _outer_case(M=1)
+    out = orc.outer_step(th, ins, None, lr=1.0, mu=0.0)
+    np.testing.assert_array_equal(out["theta_outer"], ins[0])
+
+
+def test_outer_mu0_lr1_is_localsgd_average():
+    # Section 3.1 (LocalSGD): synchronisation replaces the model by the mean over workers
+    th, ins, mom = _outer_case(M=4)
+    out = orc.outer_step(th, ins, mom, lr=1.0, mu=0.0, nesterov=False)
+    want = np.mean(np.stack([i.astype(np.float64) for i in ins]), axis=0)
+    np.testing.assert_allclose(out["theta_outer_f64"], want, rtol=1e-13, atol=1e-18)
+    out2 = orc.outer_step(th, ins, mom, lr=1.0, mu=0.0, nesterov=True)
+    np.testing.assert_allclose(out2["theta_outer_f64"], want, rtol=1e-13, atol=1e-18)
+
+
+def test_outer_fixed_points():
+    th, ins, mom = _outer_case(M=3)
+    same = [th.copy() for _ in range(3)]
+    out = orc.outer_step(th, same, np.zeros_like(th), lr=0.7, mu=0.9)
+    np.testing.assert_array_equal(out["theta_outer"], th)
+    np.testing.assert_array_equal(out["momentum"], np.zeros_like(th))
+    out = orc.outer_step(th, same, mom, lr=0.7, mu=0.9)
+    want = th.astype(np.float64) - 0.7 * 0.81 * mom.astype(np.float64)
+    np.testing.assert_allclose(out["theta_outer_f64"], want, rtol=1e-13)
+    out = orc.outer_step(th, same, mom, lr=0.7, mu=0.9, nesterov=False)
+    want = th.astype(np.float64) - 0.7 * 0.9 * mom.astype(np.float64)
+    np.testing.assert_allclose(out["theta_outer_f64"], want, rtol=1e-13)
+
+
+def test_outer_instance_order_invariance():
+    th, ins, mom = _outer_case(M=4)
+    base = orc.outer_step(th, ins, mom, lr=0.7, mu=0.9)
+    for perm in itertools.permutations(range(4)):
+        out = orc.outer_step(th, [ins[p] for p in perm], mom, lr=0.7, mu=0.9)
+        np.testing.assert_allclose(out["theta_outer_f64"], base["theta_outer_f64"], rtol=1e-13,
+                                   atol=1e-18)
+        np.testing.assert_allclose(out["momentum_f64"], base["momentum_f64"], rtol=1e-12, atol=1e-20)
+
+
+def test_outer_sign_and_scale():
+    # instances moved by -d from theta (theta_k = theta - d): the outer model must move the same way
+    th = np.zeros(4, dtype=np.float32)
+    d = np.array([1.0, -2.0, 0.5, 0.0], dtype=np.float32)
+    out = orc.outer_step(th, [th - d, th - d], np.zeros(4, np.float32), lr=0.5, mu=0.0)
+    np.testing.assert_allclose(out["pseudo_grad"], d)
+    np.testing.assert_allclose(out["theta_outer"], -0.5 * d)
+
+
+@pytest.mark.parametrize("nesterov", [True, False])
+def test_outer_matches_torch_sgd(nesterov):
+    # library route: torch.optim.SGD fed grad = Delta, two consecutive steps so that the second
+    # starts from a non-zero momentum buffer
+    import torch
+    th, ins, _ = _outer_case(seed=61, N=100, M=3)
+    p = torch.nn.Parameter(torch.from_numpy(th.astype(np.float64)))
+    opt = torch.optim.SGD([p], lr=0.7, momentum=0.9, nesterov=nesterov)
+    x = th.astype(np.float64)
+    buf = np.zeros_like(x)
+    r = _rng(62)
+    for step in range(2):
+        cur = [x - 1e-3 * r.standard_normal(100) for _ in range(3)]
+        p.grad = torch.from_numpy(np.mean([x - c for c in cur], axis=0))
+        opt.step()
+        out = orc.outer_step(x, cur, buf, lr=0.7, mu=0.9, nesterov=nesterov)
+        x, buf = out["theta_outer_f64"], out["momentum_f64"]
+        np.testing.assert_allclose(x, p.detach().numpy(), rtol=1e-12, atol=1e-16)
+
+
+def test_outer_broadcast():
+    th, ins, mom = _outer_case(M=2)
+    out = orc.outer_step(th, ins, mom, lr=0.7, mu=0.9, broadcast=True)
+    for t in out["thetas"]:
+        np.testing.assert_array_equal(t, out["theta_outer"])
+
+
+# ------------------------------------------------------------------ merge
+
+def test_merge_properties():
+    r = _rng(70)
+    xs = [r.standard_normal(101).astype(np.float32) for _ in range(4)]
+    eq = orc.merge(xs, [5, 5, 5, 5])
+    np.testing.assert_allclose(eq["x_merge_f64"], np.mean([x.astype(np.float64) for x in xs], axis=0),
+                               rtol=1e-13, atol=1e-17)
+    assert eq["rep"] == 0                                   # ties -> lowest index
+    one = orc.merge(xs[:1], [7])
+    np.testing.assert_array_equal(one["x_merge"], xs[0])    # singleton = identity
+    w = [3, 9, 1, 9]
+    m = orc.merge(xs, w)
+    assert m["rep"] == 1                                    # argmax, first of the ties
+    m2 = orc.merge(xs, [10 * v for v in w])
+    np.testing.assert_allclose(m2["x_merge_f64"], m["x_merge_f64"], rtol=1e-13, atol=1e-17)
+    lo, hi = np.min(xs, axis=0), np.max(xs, axis=0)
+    assert np.all(m["x_merge_f64"] >= lo - 1e-12) and np.all(m["x_merge_f64"] <= hi + 1e-12)
+    # hand value: weights 1 and 3 on values 0 and 4 -> 3
+    h = orc.merge([np.zeros(2, np.float32), np.full(2, 4, np.float32)], [1, 3])
+    np.testing.assert_array_equal(h["x_merge"], np.full(2, 3, np.float32))
+    assert h["rep"] == 1
