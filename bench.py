@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdLoCo hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input:
+  adloco_grad_stats   GPT-2-small-shaped workload: 12 blocks x {768->2304, 768->768, 768->3072,
+                      3072->768}, B = 32, T = 512, bf16 a ~ N(0,1), delta ~ N(0,1e-2):
+                      Gram kernel (per-sample norms), gradient-sum GEMM, reductions
+  adloco_norm_test    ||sum_i g_i||^2, norm test, batch rule, SwitchMode (eta = 0.3)
+  adloco_check_merge  host
+  adloco_outer_step   M = 4 instances x 124M fp32 parameters, Nesterov (lr 0.7, mu 0.9), in place
+  adloco_merge        S = 4 instances, weights = requested batches, in place
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2.5e15     # dense bf16 MFMA flop/s, MI355X
+PEAK_HBM = 8.0e12           # bytes/s
+TILE = 128                  # T-tile edge of the Gram kernel (executed-flop accounting)
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=3)
+    p.add_argument("--gram-variant", type=int, default=None)
+    p.add_argument("--wgrad-variant", type=int, default=None)
+    p.add_argument("--stream-blocks-per-cu", type=int, default=None)
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--grad-provided", action="store_true",
+                   help="caller supplies the gradient sum (skips the gradient-sum GEMM)")
+    p.add_argument("--only", default="all", choices=["all", "stats", "outer"],
+                   help="time only one half (diagnostics; the JSON line says so)")
+    return p.parse_args()
+
+
+def gram_flops(shapes, B, T):
+    """(symmetric-half algorithmic, full, executed by the tile-pair kernel) flops per launch."""
+    dsum = sum(di + do for _, di, do in shapes)
+    nt = -(-T // TILE)
+    pairs = nt * (nt + 1) // 2
+    sym = B * T * (T + 1) * dsum
+    full = 2 * B * T * T * dsum
+    executed = 0
+    for _, di, do in shapes:
+        kp = -(-di // 64) * 64 + -(-do // 64) * 64      # k-chunks of 64 are zero padded
+        executed += B * pairs * 2 * TILE * TILE * kp
+    return sym, full, executed
+
+
+def cpu_baseline(synth, orc, shapes, B, T, N, M):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    # sample: the 4 linears of one of the 12 blocks, all B samples; outer step + merge on N/8
+    layers = synth.grad_stats_inputs(2, linears=range(4), B=B, T=T)
+    t0 = time.perf_counter()
+    st = orc.grad_stats([(l["a"], l["delta"]) for l in layers], two_pass=False)
+    orc.norm_test(st["S1"], st["S2"], B, 0.3, B, 32)
+    t_block = time.perf_counter() - t0
+    n_s = N // 8
+    theta, insts, mom = synth.outer_inputs(3, N=n_s, M=M)
+    t0 = time.perf_counter()
+    orc.outer_step(theta, insts, mom, 0.7, 0.9, True)
+    orc.merge(insts, [32.0 + k for k in range(M)])
+    t_outer = time.perf_counter() - t0
+    n_blocks = len(shapes) // 4
+    t_est = n_blocks * t_block + 8 * t_outer
+    return dict(value=B * T / t_est, unit="tokens/s", cores=int(cores), kind="oracle",
+                sample=(f"1 of {n_blocks} blocks (4 linears, all {B} samples, T={T}) took "
+                        f"{t_block:.2f} s; outer step + merge on N/8 = {n_s} params took "
+                        f"{t_outer:.2f} s; step time extrapolated linearly to "
+                        f"{n_blocks} blocks and N params: {t_est:.1f} s"),
+                grad_stats_tokens_per_s=B * T / (n_blocks * t_block),
+                outer_merge_GBps=((4 * (M + 2) + 8 + 4 * (M + 1)) * n_s) / t_outer / 1e9)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures the one-GPU hot path only: --gpus must be 1 "
+              "(this build has no multi-GPU path)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import adloco_synth as synth
+    import paper_2508_18182_amd as A
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    ctx = A.Context(0)
+    if args.gram_variant is not None:
+        ctx.set_tuning("gram_variant", args.gram_variant)
+    if args.wgrad_variant is not None:
+        ctx.set_tuning("wgrad_variant", args.wgrad_variant)
+    if args.stream_blocks_per_cu is not None:
+        ctx.set_tuning("stream_blocks_per_cu", args.stream_blocks_per_cu)
+    ctx.set_tuning("profile", 1)
+
+    cfg = synth.CONFIGS[2]
+    B, T, eta = cfg["B"], cfg["T"], cfg["eta"]
+    shapes = synth.linear_shapes(2)
+    ocfg = synth.CONFIGS[3]["outer"]
+    N, M = ocfg["N"], ocfg["M"]
+
+    # ---- inputs, resident in HBM
+    layers = synth.device_grad_stats_inputs(2, dev)
+    for l in layers:
+        l["grad_sum"] = torch.zeros(l["d_out"], l["d_in"], dtype=torch.float32, device=dev)
+        l["provided"] = bool(args.grad_provided)
+    descs = A.binding.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
+    per_sample = torch.zeros(B, dtype=torch.float32, device=dev)
+    per_layer = torch.zeros(len(layers), B, dtype=torch.float32, device=dev)
+    acc = torch.zeros(2, dtype=torch.float64, device=dev)
+    theta, insts, mom = synth.device_outer_inputs(3, dev)
+    if args.grad_provided:
+        # the caller's own weight gradient: any values do; computed once, outside the timed region
+        for l in layers:
+            l["provided"] = False
+        d2 = A.binding.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
+        A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, per_sample, per_layer, acc, 0,
+                            descs=d2)
+        for l in layers:
+            l["provided"] = True
+    torch.cuda.synchronize()
+
+    b_req = [B, B, B, B]
+    last = {}
+
+    def step():
+        if args.only in ("all", "stats"):
+            A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, per_sample, per_layer, acc, 0,
+                                descs=descs)
+            res = A.adloco_norm_test(ctx, None, acc, eta, B, 32, 2, 256, descs=descs)
+            last.update(res)
+            b_req[0] = res["b_req"]
+        if args.only in ("all", "outer"):
+            A.adloco_check_merge(b_req, M)
+            A.adloco_outer_step(ctx, theta, insts, mom, ocfg["lr"], ocfg["mu"], True)
+            A.adloco_merge(ctx, insts, [float(b + k) for k, b in enumerate(b_req)])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    for k in ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge"):
+        ctx.profile_read(k)                      # drop warm-up events
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    kern = {}
+    for k in ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge"):
+        ms, n = ctx.profile_read(k)
+        kern[k] = dict(avg_ms=(ms / n) if n else None, launches=n)
+
+    sym, full, executed = gram_flops(shapes, B, T)
+    wgrad_flops = sum(2 * B * T * di * do for _, di, do in shapes)
+    outer_bytes = (4 * (M + 2) + 8) * N
+    merge_bytes = 4 * (M + 1) * N
+    sq_bytes = 4 * sum(di * do for _, di, do in shapes)
+
+    def roof(bound, work, ms, peak, unit, scale, **extra):
+        if not ms:
+            return None
+        a = work / (ms * 1e-3) / scale
+        return dict(bound=bound, achieved=a, peak=peak / scale, unit=unit, frac=a / (peak / scale),
+                    traffic=None, avg_kernel_ms=ms, **extra)
+
+    r_gram = roof("mfma", sym, kern["gram"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
+                  kernel="gram_bf16_kernel", flops_algorithmic_symmetric=sym, flops_full=full,
+                  flops_executed=executed,
+                  frac_executed=(executed / (kern["gram"]["avg_ms"] * 1e-3) / PEAK_BF16_MFMA)
+                  if kern["gram"]["avg_ms"] else None)
+    r_wgrad = roof("mfma", wgrad_flops, kern["wgrad"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
+                   kernel="wgrad_bf16_kernel", flops_algorithmic=wgrad_flops)
+    r_outer = roof("hbm", outer_bytes, kern["outer_step"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+                   kernel="outer_step_vec_kernel", bytes_algorithmic=outer_bytes)
+    r_merge = roof("hbm", merge_bytes, kern["merge"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+                   kernel="merge_vec_kernel", bytes_algorithmic=merge_bytes)
+    r_sq = roof("hbm", sq_bytes, kern["sqnorm"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+                kernel="sqnorm_partial_kernel", bytes_algorithmic=sq_bytes)
+    roofs = dict(gram=r_gram, wgrad=r_wgrad, outer_step=r_outer, merge=r_merge, sqnorm=r_sq)
+    timed = {k: v["avg_ms"] for k, v in kern.items() if v["avg_ms"]}
+    dominant = max(timed, key=timed.get) if timed else None
+    stats_ms = sum(kern[k]["avg_ms"] or 0.0 for k in ("gram", "wgrad", "finalize", "sqnorm"))
+
+    out = {
+        "metric": "grad-stats tokens/s (MFMA util) + outer-step GB/s (frac HBM peak), 1 GPU",
+        "value": B * T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "GPT-2-small-shaped grad stats (48 linears, B=32, T=512, bf16) + "
+                               "norm test + outer step and merge (M=4 x 124M fp32)",
+                   "B": B, "T": T, "n_linears": len(shapes), "M": M, "N": N, "eta": eta,
+                   "grad_sum": "caller-provided" if args.grad_provided else "computed by the library",
+                   "timed_part": args.only},
+        "roofline": (dict(roofs[dominant], dominant_kernel=dominant)
+                     if dominant in roofs and roofs[dominant] else None),
+        "kernels": {"avg_ms": {k: v["avg_ms"] for k, v in kern.items()},
+                    "gram": r_gram, "wgrad": r_wgrad, "outer_step": r_outer, "merge": r_merge,
+                    "sqnorm": r_sq},
+        "grad_stats_tokens_per_s": (B * T / (stats_ms * 1e-3)) if stats_ms else None,
+        "outer_step_GBps": r_outer["achieved"] if r_outer else None,
+        "merge_GBps": r_merge["achieved"] if r_merge else None,
+        "norm_test": {k: last.get(k) for k in ("stat", "b_req", "test_passed", "accumulate")},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import adloco_oracle as orc
+        out["cpu_baseline"] = cpu_baseline(synth, orc, shapes, B, T, N, M)
+    else:
+        out["cpu_baseline"] = None
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

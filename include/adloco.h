@@ -1,0 +1,208 @@
+/*
+ * adloco.h -- C ABI of the AdLoCo data-parallel hot path on one MI355X (gfx950).
+ *
+ * Two halves:
+ *   1. adaptive-batch statistics: per-sample gradient squared norms of linear layers, the
+ *      batch-gradient norm, the norm test / batch rule and the SwitchMode decision;
+ *   2. the multi-instance DiLoCo outer step (averaged pseudo-gradient, Nesterov outer
+ *      update, optional worker reset) and the batch-weighted trainer merge.
+ *
+ * Conventions (all entry points)
+ *   - Return value: 0 = ADLOCO_OK, otherwise one of the ADLOCO_E* codes below.  No exception
+ *     crosses this boundary.  adloco_last_error() gives a human-readable reason for the last
+ *     failing call on that context (valid until the next call on it).
+ *   - "device" pointers are device (HBM) addresses owned by the caller (PyTorch-ROCm
+ *     allocations in the Python binding); the library never frees, reallocates or keeps
+ *     them.  They must stay alive until the work enqueued on `stream` has completed.
+ *     "host" pointers are ordinary host memory, read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All device work
+ *     is enqueued on it.  Only adloco_norm_test waits for the stream (it returns scalars to
+ *     the host); every other call returns as soon as its kernels are enqueued.
+ *   - A context owns only scratch memory (partial sums, descriptor tables, two pinned
+ *     doubles).  One context must not be used from two host threads at once, nor on two
+ *     streams whose work may overlap.
+ *   - Buffers must not alias unless the argument is documented "in/out".
+ */
+#ifndef ADLOCO_H
+#define ADLOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------------------- */
+#define ADLOCO_OK            0
+#define ADLOCO_EINVAL        1  /* NULL / negative / inconsistent / misaligned argument        */
+#define ADLOCO_EUNSUPPORTED  2  /* dtype, size or count outside what the kernels handle       */
+#define ADLOCO_ENOMEM        3  /* scratch allocation failed                                  */
+#define ADLOCO_EHIP          4  /* a HIP runtime call failed (text in adloco_last_error)      */
+#define ADLOCO_ESTATE        5  /* accumulate requested on an accumulator that holds no batch */
+
+/* ---- element types of a and delta --------------------------------------------------- */
+#define ADLOCO_F32   0
+#define ADLOCO_BF16  1
+
+/* ---- flags -------------------------------------------------------------------------- */
+#define ADLOCO_ACCUMULATE       0x1u  /* grad_stats: continue a batch (switch mode micro-batch) */
+#define ADLOCO_GRAD_PROVIDED    0x1u  /* linear_desc.flags: caller maintains grad_sum itself     */
+#define ADLOCO_BROADCAST        0x1u  /* outer_step: also write the new outer model into theta_k */
+#define ADLOCO_BIASED_VAR       0x1u  /* norm_test: variance normalised by 1/B instead of 1/(B-1)*/
+#define ADLOCO_ALLOW_SHRINK     0x2u  /* norm_test: raw ceil rule, requested batch may decrease   */
+
+#define ADLOCO_MAX_INSTANCES   16     /* largest M of adloco_outer_step and S of adloco_merge    */
+
+typedef struct adloco_ctx adloco_ctx;
+
+/* Create / destroy a context on HIP device `device`.  adloco_create makes that device
+ * current for the calling thread.  adloco_destroy frees the scratch memory (it waits for
+ * the device).  adloco_last_error(NULL) returns the reason adloco_create itself failed. */
+int adloco_create(adloco_ctx** out, int device);
+int adloco_destroy(adloco_ctx* ctx);
+const char* adloco_last_error(const adloco_ctx* ctx);
+
+/* Tuning knob for benchmarking kernel variants ("gram_variant", "wgrad_variant",
+ * "stream_blocks_per_cu", ...).  Unknown names give ADLOCO_EINVAL.  Results never depend on
+ * a knob beyond floating-point summation order. */
+int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
+
+/* Measurement aid.  After adloco_set_tuning(ctx, "profile", 1) every launch of the named
+ * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge") is bracketed by HIP
+ * events on the call's stream.  adloco_profile_read waits for the recorded events of that
+ * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
+int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
+
+/* ------------------------------------------------------------------------------------ *
+ * Gradient statistics.
+ *
+ * One linear layer l with weight W [d_out, d_in].  Sample i of the batch has activations
+ * a_i [T, d_in] (the layer's input) and output gradients delta_i [T, d_out] (per sample,
+ * NOT averaged over the batch).  Its per-sample gradient is g_i^l = sum_t delta_{i,t}
+ * a_{i,t}^T, the term that the mini-batch gradient g_k = (1/b_k) sum_i grad f(x_k; xi_i)
+ * of eq. 1 (Section 2.1) averages; the variance of Section 3.3.1 needs ||g_i||^2.
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  const void* a;          /* device [B, T, d_in], token rows a_row_stride elements apart      */
+  const void* delta;      /* device [B, T, d_out], token rows delta_row_stride apart          */
+  int32_t d_in, d_out;    /* >= 1                                                             */
+  int64_t a_row_stride;   /* elements between consecutive tokens; 0 means d_in (contiguous)   */
+  int64_t delta_row_stride; /* likewise; 0 means d_out                                        */
+  float* grad_sum;        /* device [d_out, d_in] fp32, contiguous, in/out: running sum_i g_i^l
+                             over the (accumulated) batch.  Written by adloco_grad_stats
+                             unless ADLOCO_GRAD_PROVIDED; read by adloco_norm_test.  May be
+                             NULL in adloco_grad_stats with ADLOCO_GRAD_PROVIDED.             */
+  uint32_t flags;         /* 0 or ADLOCO_GRAD_PROVIDED                                        */
+  uint32_t reserved;      /* must be 0                                                        */
+} adloco_linear_desc;
+
+/* Running accumulator of one (possibly accumulated) batch; lives in device memory, owned by
+ * the caller (16 bytes, 8-byte aligned). */
+typedef struct {
+  double  sum_sample_sqnorm;  /* S1 = sum_i ||g_i||^2 over all samples seen so far           */
+  int64_t n_samples;          /* number of samples seen so far                               */
+} adloco_stats_acc;
+
+/* adloco_grad_stats: per-sample squared gradient norms of one (micro-)batch by the Gram
+ * identity  ||sum_t delta_t a_t^T||_F^2 = sum_{t,t'} (a_t . a_t')(delta_t . delta_t'),
+ * plus, for every layer without ADLOCO_GRAD_PROVIDED, grad_sum (+)= sum_i delta_i^T a_i
+ * (eq. 1 times b_k; Algorithm 3's "g <- g + grad L" in the accumulate branch).
+ *
+ *   layers   host array of n_layers descriptors (read before return), 1 <= n_layers <= 4096
+ *   B, T     samples in this micro-batch and tokens per sample, >= 1 (all layers share them)
+ *   dtype    ADLOCO_F32 or ADLOCO_BF16: element type of every a and delta
+ *   per_sample_sqnorm        device [B] fp32, overwritten: sum_l ||g_i^l||^2 of this micro-batch
+ *   per_layer_sample_sqnorm  device [n_layers, B] fp32, overwritten; or NULL
+ *   acc      device accumulator.  Without ADLOCO_ACCUMULATE it is reset first (and grad_sum
+ *            is overwritten); with it, S1, n_samples and grad_sum continue from their values
+ *            (ADLOCO_ESTATE is NOT detected on the device: the flag is the caller's promise
+ *            that acc and grad_sum hold the earlier micro-batches of the same batch).
+ *   flags    0 or ADLOCO_ACCUMULATE
+ * bf16 inputs are multiplied exactly and accumulated in fp32 (MFMA); fp32 inputs in fp32.
+ * bf16 rows must be 2-byte aligned; 16-byte aligned rows with d % 8 == 0 take the fast
+ * path, anything else a slower guarded path (same results). */
+int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
+                      int B, int T, int dtype,
+                      float* per_sample_sqnorm, float* per_layer_sample_sqnorm,
+                      adloco_stats_acc* acc, uint32_t flags, void* stream);
+
+/* Result of the norm test, batch rule and SwitchMode for one trainer. */
+typedef struct {
+  double  S1;                 /* sum_i ||g_i||^2                                               */
+  double  S2;                 /* ||sum_i g_i||^2                                               */
+  double  batch_grad_sqnorm;  /* ||g_k||^2 = S2 / B^2 (eq. 1)                                  */
+  double  variance;           /* sigma^2_{B_k} = (S1 - S2/B)/(B-1)   (or /B if BIASED_VAR)     */
+  double  stat;               /* sigma^2 / (eta^2 ||g_k||^2); NaN if undefined, +inf if g_k=0  */
+  int64_t n_samples;          /* B, read from the accumulator                                  */
+  int64_t b_cur;              /* echoed                                                        */
+  int64_t b_req;              /* requested batch for the next outer step                       */
+  int64_t b_micro;            /* micro-batch size to run with                                  */
+  int64_t accum_steps;        /* ceil(b_req / b_max) when accumulating, else 1                 */
+  int32_t test_passed;        /* 1 iff stat <= b_cur (eq. 4 rearranged)                        */
+  int32_t accumulate;         /* 1 iff b_req > n_switch * b_max (SwitchMode)                   */
+  int32_t stat_undefined;     /* 1 iff B < 2 with the unbiased variance (0/0)                  */
+  int32_t reserved;           /* 0                                                             */
+} adloco_norm_test_result;
+
+/* adloco_norm_test: S2 = sum_l ||grad_sum_l||_F^2 on the device, then on the host in fp64:
+ * the approximate norm test (eq. 4), the batch rule b_{k+1} = ceil(sigma^2 / (eta^2
+ * ||grad F_B||^2)) (Section 3.3.1) and SwitchMode (Section 4.2; Algorithm 3).
+ *   b_req = min(b_cap, max(b_cur, ceil(stat), 1))   (b_cur dropped with ADLOCO_ALLOW_SHRINK;
+ *   b_cap = 0 means no ceiling);  B = 1: stat undefined, b_req = max(b_cur, 2).
+ *   layers   host array; only grad_sum, d_in, d_out are used
+ *   acc      device accumulator filled by adloco_grad_stats
+ *   eta > 0; b_cur >= 1; b_max >= 1; n_switch >= 1; b_cap >= 0
+ *   out      host, written before return.  This call waits for `stream`. */
+int adloco_norm_test(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
+                     const adloco_stats_acc* acc, double eta, int64_t b_cur, int64_t b_max,
+                     int32_t n_switch, int64_t b_cap, uint32_t flags,
+                     adloco_norm_test_result* out, void* stream);
+
+/* Host-only halves of adloco_norm_test (no device, no context): the decision from given
+ * S1, S2, B, and SwitchMode alone.  Same formulas, same edge conventions. */
+int adloco_norm_test_decide(double S1, double S2, int64_t n_samples, double eta,
+                            int64_t b_cur, int64_t b_max, int32_t n_switch, int64_t b_cap,
+                            uint32_t flags, adloco_norm_test_result* out);
+int adloco_switch_mode(int64_t b_req, int64_t b_max, int32_t n_switch,
+                       int32_t* accumulate, int64_t* accum_steps, int64_t* b_micro);
+
+/* ------------------------------------------------------------------------------------ *
+ * adloco_outer_step: Algorithm 3's pseudo-gradient and outer update for one trainer,
+ *   Delta = (1/M) sum_m (theta_outer - theta_m);   buf <- mu*buf + Delta;
+ *   theta_outer <- theta_outer - lr * (nesterov ? Delta + mu*buf : buf)
+ * with OuterOpt = SGD with (Nesterov) momentum (mu = 0: plain SGD, the theorems' setting),
+ * and, with ADLOCO_BROADCAST, Algorithm 3's worker reset theta_m <- theta_outer.
+ *   theta_outer      device [N] fp32, in/out
+ *   theta_inst       HOST array of M device pointers, each [N] fp32 (written only with
+ *                    ADLOCO_BROADCAST); 1 <= M <= ADLOCO_MAX_INSTANCES; no aliasing
+ *   momentum         device [N] fp32 in/out; may be NULL iff mu == 0
+ *   pseudo_grad_out  device [N] fp32 or NULL: receives Delta
+ * N = 0 is a successful no-op.  16-byte aligned pointers take the vector path, others a
+ * scalar path with the same results.  Arithmetic is fp64 in registers, rounded once. */
+int adloco_outer_step(adloco_ctx* ctx, float* theta_outer, float* const* theta_inst, int M,
+                      size_t N, float* momentum, double lr, double mu, int nesterov,
+                      uint32_t flags, float* pseudo_grad_out, void* stream);
+
+/* adloco_merge: DoMerge (Algorithm 2; Section 4.1.1): x_r <- sum_j b_j x_j / sum_j b_j for
+ * the representative r = argmax b_j (lowest index on ties) or the given `rep`; the other
+ * S-1 vectors are left untouched (the caller drops them and keeps r's optimizer state).
+ *   x        HOST array of S device pointers, each [N] fp32; 1 <= S <= ADLOCO_MAX_INSTANCES
+ *   weights  HOST [S], the requested batches b_j, all > 0
+ *   rep      index to overwrite, or -1 for argmax
+ *   rep_out  host, receives r; may be NULL */
+int adloco_merge(adloco_ctx* ctx, float* const* x, const double* weights, int S, size_t N,
+                 int rep, int* rep_out, void* stream);
+
+/* adloco_check_merge: CheckMerge (Algorithm 1), host only: nothing when w = 0 or k <= 1;
+ * else the w trainers with the smallest requested batch (ascending, ties by index) when
+ * w <= k; else nothing.  sel_out: host [max(w,1)]; n_sel receives the count (0 or w). */
+int adloco_check_merge(const int64_t* b_req, int k, int w, int* sel_out, int* n_sel);
+
+/* Library version (major*10000 + minor*100 + patch). */
+int adloco_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADLOCO_H */

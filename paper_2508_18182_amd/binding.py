@@ -1,0 +1,308 @@
+"""ctypes binding of libadloco.so: argument marshalling only.
+
+Function names and argument order follow include/adloco.h.  Tensors are torch tensors on
+the GPU (PyTorch-ROCm owns device memory and streams); nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libadloco.so")
+
+ADLOCO_F32, ADLOCO_BF16 = 0, 1
+ADLOCO_ACCUMULATE = 0x1
+ADLOCO_GRAD_PROVIDED = 0x1
+ADLOCO_BROADCAST = 0x1
+ADLOCO_BIASED_VAR = 0x1
+ADLOCO_ALLOW_SHRINK = 0x2
+ADLOCO_MAX_INSTANCES = 16
+
+_ERR_NAMES = {1: "ADLOCO_EINVAL", 2: "ADLOCO_EUNSUPPORTED", 3: "ADLOCO_ENOMEM", 4: "ADLOCO_EHIP",
+              5: "ADLOCO_ESTATE"}
+
+
+class AdlocoError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{_ERR_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+class LinearDesc(C.Structure):
+    _fields_ = [("a", C.c_void_p), ("delta", C.c_void_p), ("d_in", C.c_int32),
+                ("d_out", C.c_int32), ("a_row_stride", C.c_int64),
+                ("delta_row_stride", C.c_int64), ("grad_sum", C.c_void_p),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class StatsAcc(C.Structure):
+    _fields_ = [("sum_sample_sqnorm", C.c_double), ("n_samples", C.c_int64)]
+
+
+class NormTestResult(C.Structure):
+    _fields_ = [("S1", C.c_double), ("S2", C.c_double), ("batch_grad_sqnorm", C.c_double),
+                ("variance", C.c_double), ("stat", C.c_double), ("n_samples", C.c_int64),
+                ("b_cur", C.c_int64), ("b_req", C.c_int64), ("b_micro", C.c_int64),
+                ("accum_steps", C.c_int64), ("test_passed", C.c_int32),
+                ("accumulate", C.c_int32), ("stat_undefined", C.c_int32),
+                ("reserved", C.c_int32)]
+
+    def as_dict(self) -> dict:
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libadloco.so; there is no fallback path: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2508_18182_amd.build` "
+            "(or __graft_entry__.build()); the HIP library is the only implementation")
+    # PyTorch ships its own HIP runtime (same soname as the system one).  It has to be the one
+    # already loaded when libadloco.so resolves libamdhip64, otherwise the process ends up with
+    # two runtimes and the second one to initialise sees no GPU.
+    import torch  # noqa: F401
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, u32, dbl, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_double, C.c_size_t
+    lib.adloco_version.restype = C.c_int
+    lib.adloco_create.argtypes = [C.POINTER(vp), C.c_int]
+    lib.adloco_destroy.argtypes = [vp]
+    lib.adloco_last_error.argtypes = [vp]
+    lib.adloco_last_error.restype = C.c_char_p
+    lib.adloco_set_tuning.argtypes = [vp, C.c_char_p, C.c_int]
+    lib.adloco_profile_read.argtypes = [vp, C.c_char_p, C.POINTER(dbl), C.POINTER(C.c_int)]
+    lib.adloco_profile_read.restype = C.c_int
+    lib.adloco_grad_stats.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, C.c_int, C.c_int, C.c_int,
+                                      vp, vp, vp, u32, vp]
+    lib.adloco_norm_test.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, vp, dbl, i64, i64, i32,
+                                     i64, u32, C.POINTER(NormTestResult), vp]
+    lib.adloco_norm_test_decide.argtypes = [dbl, dbl, i64, dbl, i64, i64, i32, i64, u32,
+                                            C.POINTER(NormTestResult)]
+    lib.adloco_switch_mode.argtypes = [i64, i64, i32, C.POINTER(i32), C.POINTER(i64),
+                                       C.POINTER(i64)]
+    lib.adloco_outer_step.argtypes = [vp, vp, C.POINTER(vp), C.c_int, sz, vp, dbl, dbl,
+                                      C.c_int, u32, vp, vp]
+    lib.adloco_merge.argtypes = [vp, C.POINTER(vp), C.POINTER(dbl), C.c_int, sz, C.c_int,
+                                 C.POINTER(C.c_int), vp]
+    lib.adloco_check_merge.argtypes = [C.POINTER(i64), C.c_int, C.c_int, C.POINTER(C.c_int),
+                                       C.POINTER(C.c_int)]
+    for name in ("adloco_create", "adloco_destroy", "adloco_set_tuning", "adloco_grad_stats",
+                 "adloco_norm_test", "adloco_norm_test_decide", "adloco_switch_mode",
+                 "adloco_outer_step", "adloco_merge", "adloco_check_merge"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def adloco_version() -> int:
+    return load_library().adloco_version()
+
+
+class Context:
+    """Owner of an adloco_ctx (scratch memory on one device)."""
+
+    def __init__(self, device: int = 0):
+        lib = load_library()
+        h = C.c_void_p()
+        rc = lib.adloco_create(C.byref(h), int(device))
+        if rc != 0:
+            raise AdlocoError(rc, lib.adloco_last_error(None).decode())
+        self._h = h
+        self.device = int(device)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().adloco_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def set_tuning(self, name: str, value: int):
+        self._check(load_library().adloco_set_tuning(self._h, name.encode(), int(value)))
+
+    def profile_read(self, kernel: str):
+        """(total milliseconds, launches) of the named kernel since the last read."""
+        ms, n = C.c_double(0.0), C.c_int(0)
+        self._check(load_library().adloco_profile_read(self._h, kernel.encode(), C.byref(ms),
+                                                       C.byref(n)))
+        return ms.value, n.value
+
+    def _check(self, rc: int):
+        if rc != 0:
+            raise AdlocoError(rc, load_library().adloco_last_error(self._h).decode())
+
+
+def _stream_ptr(stream) -> C.c_void_p:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dev_ptr(t, dtype=None, numel=None, name="tensor") -> C.c_void_p:
+    """Device address of a contiguous CUDA/HIP tensor after shape and dtype checks."""
+    if t is None:
+        return C.c_void_p(None)
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} has dtype {t.dtype}, expected {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name} has {t.numel()} elements, needs {numel}")
+    return C.c_void_p(t.data_ptr())
+
+
+def make_layer_descs(layers: Sequence[dict], B: int, T: int, dtype: int):
+    """layers: dicts with a [B,T,d_in], delta [B,T,d_out], optional grad_sum [d_out,d_in] fp32,
+    optional provided=True.  Token rows may be strided views (last dim contiguous)."""
+    import torch
+    tdt = torch.bfloat16 if dtype == ADLOCO_BF16 else torch.float32
+    arr = (LinearDesc * len(layers))()
+    for i, l in enumerate(layers):
+        a, d = l["a"], l["delta"]
+        for nm, t in (("a", a), ("delta", d)):
+            if not t.is_cuda or t.dtype != tdt or t.dim() != 3 or t.shape[0] != B or t.shape[1] != T:
+                raise ValueError(f"layer {i}: {nm} must be a GPU {tdt} tensor [B={B},T={T},d], got "
+                                 f"{tuple(t.shape)} {t.dtype}")
+            if t.stride(2) != 1 or t.stride(0) != T * t.stride(1):
+                raise ValueError(f"layer {i}: {nm} needs unit stride in d and samples T rows apart")
+        g = l.get("grad_sum")
+        if g is not None:
+            if (not g.is_cuda or g.dtype != torch.float32 or not g.is_contiguous()
+                    or tuple(g.shape) != (d.shape[2], a.shape[2])):
+                raise ValueError(f"layer {i}: grad_sum must be contiguous fp32 [d_out, d_in] on the GPU")
+        arr[i].a = a.data_ptr()
+        arr[i].delta = d.data_ptr()
+        arr[i].d_in = a.shape[2]
+        arr[i].d_out = d.shape[2]
+        arr[i].a_row_stride = a.stride(1)
+        arr[i].delta_row_stride = d.stride(1)
+        arr[i].grad_sum = g.data_ptr() if g is not None else None
+        arr[i].flags = ADLOCO_GRAD_PROVIDED if l.get("provided") else 0
+        arr[i].reserved = 0
+    return arr
+
+
+def adloco_grad_stats(ctx: Context, layers: Sequence[dict], B: int, T: int, dtype: int,
+                      per_sample_sqnorm, per_layer_sample_sqnorm, acc, flags: int = 0,
+                      stream=None, descs=None):
+    """acc: GPU tensor of 16 bytes (e.g. torch.zeros(2, dtype=torch.float64)) holding an
+    adloco_stats_acc.  descs: a LinearDesc array from make_layer_descs to skip re-marshalling."""
+    import torch
+    arr = descs if descs is not None else make_layer_descs(layers, B, T, dtype)
+    n = len(arr)
+    ps = _dev_ptr(per_sample_sqnorm, torch.float32, B, "per_sample_sqnorm")
+    pl = _dev_ptr(per_layer_sample_sqnorm, torch.float32, n * B, "per_layer_sample_sqnorm")
+    if acc is None or not acc.is_cuda or acc.numel() * acc.element_size() < 16:
+        raise ValueError("acc must be a GPU tensor of at least 16 bytes")
+    ctx._check(load_library().adloco_grad_stats(ctx._h, arr, n, B, T, dtype, ps, pl,
+                                                C.c_void_p(acc.data_ptr()), flags,
+                                                _stream_ptr(stream)))
+
+
+def adloco_norm_test(ctx: Context, layers, acc, eta: float, b_cur: int, b_max: int,
+                     n_switch: int = 2, b_cap: int = 0, flags: int = 0, stream=None,
+                     descs=None) -> dict:
+    """layers: dicts with grad_sum (and d_in/d_out taken from its shape), or descs."""
+    if descs is None:
+        arr = (LinearDesc * len(layers))()
+        for i, l in enumerate(layers):
+            g = l["grad_sum"]
+            _dev_ptr(g, None, None, f"layer {i} grad_sum")
+            arr[i].grad_sum = g.data_ptr()
+            arr[i].d_out, arr[i].d_in = g.shape
+    else:
+        arr = descs
+    res = NormTestResult()
+    ctx._check(load_library().adloco_norm_test(ctx._h, arr, len(arr), C.c_void_p(acc.data_ptr()),
+                                               eta, b_cur, b_max, n_switch, b_cap, flags,
+                                               C.byref(res), _stream_ptr(stream)))
+    return res.as_dict()
+
+
+def adloco_norm_test_decide(S1: float, S2: float, n_samples: int, eta: float, b_cur: int,
+                            b_max: int, n_switch: int = 2, b_cap: int = 0, flags: int = 0) -> dict:
+    res = NormTestResult()
+    rc = load_library().adloco_norm_test_decide(S1, S2, n_samples, eta, b_cur, b_max, n_switch,
+                                                b_cap, flags, C.byref(res))
+    if rc != 0:
+        raise AdlocoError(rc, "adloco_norm_test_decide rejected its arguments")
+    return res.as_dict()
+
+
+def adloco_switch_mode(b_req: int, b_max: int, n_switch: int = 2) -> dict:
+    acc, steps, micro = C.c_int32(), C.c_int64(), C.c_int64()
+    rc = load_library().adloco_switch_mode(b_req, b_max, n_switch, C.byref(acc), C.byref(steps),
+                                           C.byref(micro))
+    if rc != 0:
+        raise AdlocoError(rc, "adloco_switch_mode rejected its arguments")
+    return dict(accumulate=acc.value, accum_steps=steps.value, b_micro=micro.value)
+
+
+def _ptr_array(tensors, N: int, name: str):
+    import torch
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = _dev_ptr(t, torch.float32, N, f"{name}[{i}]").value
+    return arr
+
+
+def adloco_outer_step(ctx: Context, theta_outer, theta_inst, momentum, lr: float, mu: float,
+                      nesterov: bool = True, flags: int = 0, pseudo_grad_out=None, stream=None,
+                      N: Optional[int] = None):
+    import torch
+    N = theta_outer.numel() if N is None else N
+    th = _dev_ptr(theta_outer, torch.float32, N, "theta_outer")
+    mom = _dev_ptr(momentum, torch.float32, N, "momentum")
+    pg = _dev_ptr(pseudo_grad_out, torch.float32, N, "pseudo_grad_out")
+    arr = _ptr_array(theta_inst, N, "theta_inst")
+    ctx._check(load_library().adloco_outer_step(ctx._h, th, arr, len(theta_inst), N, mom, lr, mu,
+                                                1 if nesterov else 0, flags, pg,
+                                                _stream_ptr(stream)))
+
+
+def adloco_merge(ctx: Context, x, weights, rep: int = -1, stream=None,
+                 N: Optional[int] = None) -> int:
+    N = x[0].numel() if N is None else N
+    arr = _ptr_array(x, N, "x")
+    w = (C.c_double * len(weights))(*[float(v) for v in weights])
+    if len(weights) != len(x):
+        raise ValueError("one weight per vector")
+    r = C.c_int(-1)
+    ctx._check(load_library().adloco_merge(ctx._h, arr, w, len(x), N, rep, C.byref(r),
+                                           _stream_ptr(stream)))
+    return r.value
+
+
+def adloco_check_merge(b_req: Sequence[int], w: int):
+    k = len(b_req)
+    arr = (C.c_int64 * max(k, 1))(*[int(v) for v in b_req])
+    sel = (C.c_int * max(w, 1))()
+    n = C.c_int(0)
+    rc = load_library().adloco_check_merge(arr, k, w, sel, C.byref(n))
+    if rc != 0:
+        raise AdlocoError(rc, "adloco_check_merge rejected its arguments")
+    return [sel[i] for i in range(n.value)]

@@ -1,0 +1,124 @@
+// Internal definitions shared by the translation units of libadloco (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "adloco.h"
+
+namespace adloco {
+
+// MI355X: 256 compute units in 8 XCDs; consecutive workgroup ids are dealt round-robin to
+// the XCDs, each of which has its own L2.
+constexpr int kNumXcd = 8;
+constexpr int kNumCu = 256;
+
+// Device-side view of one linear layer (built on the host, uploaded once per change).
+struct LayerDev {
+  const void* a;
+  const void* delta;
+  float* grad_sum;
+  long long a_stride;      // elements between token rows
+  long long delta_stride;
+  int d_in;
+  int d_out;
+  int fast;                // 1: rows 16-byte aligned and d % 8 == 0 for both operands
+  int provided;            // 1: caller maintains grad_sum (no wgrad for this layer)
+  int wg_blk_start;        // first workgroup of this layer in the wgrad launch
+  int sq_blk_start;        // first workgroup of this layer in the squared-norm launch
+};
+
+struct Scratch {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+
+}  // namespace adloco
+
+struct adloco_ctx {
+  int device = 0;
+  std::string err;
+  // scratch
+  adloco::Scratch partials;    // float  [n_units * pairs] Gram partial sums
+  adloco::Scratch layer_tab;   // LayerDev[n_layers]
+  adloco::Scratch red_f64;     // double partial sums of the streaming reductions
+  adloco::Scratch sample_f64;  // double [B] per-sample totals
+  adloco::Scratch order_tab;   // int [n_layers] launch order (heaviest first)
+  std::vector<adloco::LayerDev> layer_tab_host;  // last uploaded copy
+  std::vector<int> order_host;
+  int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
+  int table_dtype = -1;        // dtype the uploaded table was built for
+  double* pinned = nullptr;    // 4 doubles of pinned host memory (norm-test read-back)
+  double* dev_scalars = nullptr;  // 4 doubles on the device (S2, ...)
+  // optional per-kernel event timing ("profile" knob)
+  struct ProfRec { int kernel; hipEvent_t start, stop; };
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> prof_free;
+  int profile = 0;
+  // tuning
+  int gram_variant = 0;
+  int wgrad_variant = 0;
+  int stream_blocks_per_cu = 8;
+  int stream_variant = 0;
+};
+
+namespace adloco {
+
+inline int fail(adloco_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf;
+  return code;
+}
+
+#define ADLOCO_HIP_CHECK(ctx, expr)                                                      \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess)                                                                \
+      return adloco::fail((ctx), ADLOCO_EHIP, "%s failed: %s (%s:%d)", #expr,            \
+                          hipGetErrorString(e_), __FILE__, __LINE__);                    \
+  } while (0)
+
+// Event timing of one kernel launch when ctx->profile is set (no-ops otherwise).
+enum ProfKernel { kProfGram = 0, kProfWgrad, kProfFinalize, kProfSqnorm, kProfOuter, kProfMerge,
+                  kProfCount };
+hipEvent_t prof_begin(adloco_ctx* ctx, hipStream_t st);
+void prof_end(adloco_ctx* ctx, int kernel, hipEvent_t start, hipStream_t st);
+
+// Grow-only scratch buffer.  Growing frees the old block, which waits for the device.
+int ensure_scratch(adloco_ctx* ctx, Scratch& s, size_t bytes);
+
+// Kernel launchers (defined next to their kernels).  All return a hipError_t from the launch.
+struct GramLaunch {
+  const LayerDev* layers;   // device table
+  const int* order;         // device: launch order of layer indices, heaviest first
+  int n_layers, B, T;
+  float* partials;          // [n_layers][B][n_pairs]
+  int n_pairs;              // tile pairs per (layer, sample)
+  int tile;                 // T-tile edge used by the kernel
+};
+int gram_tile_edge(int dtype, int variant);
+hipError_t launch_gram_bf16(const GramLaunch& g, int variant, hipStream_t st);
+hipError_t launch_gram_f32(const GramLaunch& g, hipStream_t st);
+int wgrad_tile_edge(int dtype);
+hipError_t launch_wgrad(const LayerDev* layers, int n_layers, int n_blocks, long long rows,
+                        int dtype, int accumulate, int variant, hipStream_t st);
+hipError_t launch_finalize_stats(const float* partials, int n_layers, int B, int n_pairs,
+                                 float* per_sample, float* per_layer_sample, double* sample_f64,
+                                 adloco_stats_acc* acc, int accumulate, hipStream_t st);
+// sum_l ||grad_sum_l||^2 -> *out (device double); partial buffer sized by sqnorm_partials().
+int sqnorm_chunk();
+size_t sqnorm_partials(const std::vector<LayerDev>& host_layers);
+hipError_t launch_sqnorm(const LayerDev* layers, const std::vector<LayerDev>& host_layers,
+                         double* partial, double* out, hipStream_t st);
+
+}  // namespace adloco

@@ -1,0 +1,206 @@
+// Entry points of the statistics half: adloco_grad_stats (per-sample norms by the Gram
+// identity, gradient sum, S1 accumulation) and adloco_norm_test (S2 on the device, then the
+// decision on the host).
+#include <algorithm>
+#include <numeric>
+
+#include "common.h"
+
+using namespace adloco;
+
+namespace {
+
+constexpr int kMaxLayers = 4096;
+
+// Build the device view of the layer list and upload it when it differs from the cached copy.
+int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers, int dtype,
+                   bool need_inputs, hipStream_t st) {
+  const size_t esize = dtype == ADLOCO_BF16 ? 2 : 4;
+  std::vector<LayerDev> tab(n_layers);
+  const int wt = wgrad_tile_edge(dtype);
+  const int chunk = sqnorm_chunk();
+  long long wg = 0, sq = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    const adloco_linear_desc& d = layers[l];
+    if (d.d_in < 1 || d.d_out < 1)
+      return fail(ctx, ADLOCO_EINVAL, "layer %d: d_in = %d, d_out = %d must be >= 1", l, d.d_in, d.d_out);
+    if (d.reserved != 0 || (d.flags & ~ADLOCO_GRAD_PROVIDED))
+      return fail(ctx, ADLOCO_EINVAL, "layer %d: unknown flags or non-zero reserved field", l);
+    const bool provided = d.flags & ADLOCO_GRAD_PROVIDED;
+    LayerDev L{};
+    L.a = d.a;
+    L.delta = d.delta;
+    L.grad_sum = d.grad_sum;
+    L.a_stride = d.a_row_stride ? d.a_row_stride : d.d_in;
+    L.delta_stride = d.delta_row_stride ? d.delta_row_stride : d.d_out;
+    L.d_in = d.d_in;
+    L.d_out = d.d_out;
+    L.provided = provided ? 1 : 0;
+    if (need_inputs) {
+      if (!d.a || !d.delta) return fail(ctx, ADLOCO_EINVAL, "layer %d: a or delta is NULL", l);
+      if (L.a_stride < d.d_in || L.delta_stride < d.d_out)
+        return fail(ctx, ADLOCO_EINVAL, "layer %d: row stride smaller than the row", l);
+      if ((reinterpret_cast<uintptr_t>(d.a) % esize) || (reinterpret_cast<uintptr_t>(d.delta) % esize))
+        return fail(ctx, ADLOCO_EINVAL, "layer %d: a or delta not aligned to its element size", l);
+      if (!provided && !d.grad_sum)
+        return fail(ctx, ADLOCO_EINVAL, "layer %d: grad_sum is NULL without ADLOCO_GRAD_PROVIDED", l);
+      L.fast = (reinterpret_cast<uintptr_t>(d.a) % 16 == 0) &&
+               (reinterpret_cast<uintptr_t>(d.delta) % 16 == 0) && (d.d_in % 8 == 0) &&
+               (d.d_out % 8 == 0) && (L.a_stride % 8 == 0) && (L.delta_stride % 8 == 0);
+    } else if (!d.grad_sum) {
+      return fail(ctx, ADLOCO_EINVAL, "layer %d: grad_sum is NULL", l);
+    }
+    if (d.grad_sum && (reinterpret_cast<uintptr_t>(d.grad_sum) % 4))
+      return fail(ctx, ADLOCO_EINVAL, "layer %d: grad_sum not 4-byte aligned", l);
+    L.wg_blk_start = int(wg);
+    L.sq_blk_start = int(sq);
+    if (!provided)
+      wg += (long long)((d.d_out + wt - 1) / wt) * ((d.d_in + wt - 1) / wt);
+    sq += ((long long)d.d_in * d.d_out + chunk - 1) / chunk;
+    if (wg > 0x7fffffffLL || sq > 0x7fffffffLL)
+      return fail(ctx, ADLOCO_EUNSUPPORTED, "layer list too large for one launch");
+    tab[l] = L;
+  }
+  const bool same = ctx->table_dtype == dtype && tab.size() == ctx->layer_tab_host.size() &&
+                    std::memcmp(tab.data(), ctx->layer_tab_host.data(),
+                                tab.size() * sizeof(LayerDev)) == 0;
+  if (same) return ADLOCO_OK;
+  // heaviest layers first, so that the tail of the Gram launch is made of cheap workgroups
+  std::vector<int> order(n_layers);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+    return (long long)tab[x].d_in + tab[x].d_out > (long long)tab[y].d_in + tab[y].d_out;
+  });
+  int rc = ensure_scratch(ctx, ctx->layer_tab, tab.size() * sizeof(LayerDev));
+  if (rc) return rc;
+  rc = ensure_scratch(ctx, ctx->order_tab, order.size() * sizeof(int));
+  if (rc) return rc;
+  ctx->layer_tab_host.clear();          // invalid until both copies are enqueued
+  ctx->table_dtype = -1;
+  ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->layer_tab.ptr, tab.data(), tab.size() * sizeof(LayerDev),
+                                       hipMemcpyHostToDevice, st));
+  ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->order_tab.ptr, order.data(), order.size() * sizeof(int),
+                                       hipMemcpyHostToDevice, st));
+  // pageable sources: make sure the runtime has consumed them before they go out of scope
+  ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+  ctx->layer_tab_host = std::move(tab);
+  ctx->order_host = std::move(order);
+  ctx->wgrad_blocks = int(wg);
+  ctx->table_dtype = dtype;
+  return ADLOCO_OK;
+}
+
+}  // namespace
+
+extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
+                                 int B, int T, int dtype, float* per_sample_sqnorm,
+                                 float* per_layer_sample_sqnorm, adloco_stats_acc* acc,
+                                 uint32_t flags, void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (!layers || n_layers < 1) return fail(ctx, ADLOCO_EINVAL, "grad_stats: no layers");
+  if (n_layers > kMaxLayers)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: n_layers = %d exceeds %d", n_layers, kMaxLayers);
+  if (B < 1 || T < 1) return fail(ctx, ADLOCO_EINVAL, "grad_stats: B = %d, T = %d must be >= 1", B, T);
+  if (dtype != ADLOCO_F32 && dtype != ADLOCO_BF16)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: dtype %d not supported", dtype);
+  if (!per_sample_sqnorm || !acc) return fail(ctx, ADLOCO_EINVAL, "grad_stats: NULL output");
+  if (reinterpret_cast<uintptr_t>(acc) % 8)
+    return fail(ctx, ADLOCO_EINVAL, "grad_stats: acc not 8-byte aligned");
+  if (flags & ~ADLOCO_ACCUMULATE) return fail(ctx, ADLOCO_EINVAL, "grad_stats: unknown flags");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int accumulate = (flags & ADLOCO_ACCUMULATE) ? 1 : 0;
+
+  int rc = prepare_tables(ctx, layers, n_layers, dtype, true, st);
+  if (rc) return rc;
+
+  const int tile = gram_tile_edge(dtype, ctx->gram_variant);
+  const long long nt = (T + tile - 1) / tile;
+  const long long n_pairs = nt * (nt + 1) / 2;
+  const long long n_part = (long long)n_layers * B * n_pairs;
+  if (n_pairs > 0x7fffffffLL || n_part > (1LL << 40))
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: T = %d gives too many tile pairs", T);
+  rc = ensure_scratch(ctx, ctx->partials, size_t(n_part) * sizeof(float));
+  if (rc) return rc;
+  rc = ensure_scratch(ctx, ctx->sample_f64, size_t(B) * sizeof(double));
+  if (rc) return rc;
+
+  GramLaunch g;
+  g.layers = static_cast<const LayerDev*>(ctx->layer_tab.ptr);
+  g.order = static_cast<const int*>(ctx->order_tab.ptr);
+  g.n_layers = n_layers;
+  g.B = B;
+  g.T = T;
+  g.partials = static_cast<float*>(ctx->partials.ptr);
+  g.n_pairs = int(n_pairs);
+  g.tile = tile;
+  hipEvent_t ev = prof_begin(ctx, st);
+  hipError_t e = dtype == ADLOCO_BF16 ? launch_gram_bf16(g, ctx->gram_variant, st)
+                                      : launch_gram_f32(g, st);
+  prof_end(ctx, kProfGram, ev, st);
+  if (e != hipSuccess)
+    return fail(ctx, ADLOCO_EHIP, "grad_stats: Gram launch failed: %s", hipGetErrorString(e));
+  ev = ctx->wgrad_blocks > 0 ? prof_begin(ctx, st) : nullptr;
+  e = launch_wgrad(g.layers, n_layers, ctx->wgrad_blocks, (long long)B * T, dtype, accumulate,
+                   ctx->wgrad_variant, st);
+  prof_end(ctx, kProfWgrad, ev, st);
+  if (e != hipSuccess)
+    return fail(ctx, ADLOCO_EHIP, "grad_stats: gradient-sum launch failed: %s", hipGetErrorString(e));
+  e = launch_finalize_stats(g.partials, n_layers, B, int(n_pairs), per_sample_sqnorm,
+                            per_layer_sample_sqnorm, static_cast<double*>(ctx->sample_f64.ptr),
+                            acc, accumulate, st);
+  if (e != hipSuccess)
+    return fail(ctx, ADLOCO_EHIP, "grad_stats: reduction launch failed: %s", hipGetErrorString(e));
+  return ADLOCO_OK;
+}
+
+extern "C" int adloco_norm_test(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
+                                const adloco_stats_acc* acc, double eta, int64_t b_cur,
+                                int64_t b_max, int32_t n_switch, int64_t b_cap, uint32_t flags,
+                                adloco_norm_test_result* out, void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (!layers || n_layers < 1) return fail(ctx, ADLOCO_EINVAL, "norm_test: no layers");
+  if (n_layers > kMaxLayers)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "norm_test: n_layers = %d exceeds %d", n_layers, kMaxLayers);
+  if (!acc || !out) return fail(ctx, ADLOCO_EINVAL, "norm_test: NULL acc or out");
+  if (!(eta > 0.0) || b_cur < 1 || b_max < 1 || n_switch < 1 || b_cap < 0 ||
+      (flags & ~(ADLOCO_BIASED_VAR | ADLOCO_ALLOW_SHRINK)))
+    return fail(ctx, ADLOCO_EINVAL, "norm_test: bad eta, b_cur, b_max, n_switch, b_cap or flags");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // the table is shared with grad_stats: same layer list -> no upload
+  const int dtype = ctx->table_dtype >= 0 ? ctx->table_dtype : ADLOCO_BF16;
+  bool cached = ctx->layer_tab_host.size() == size_t(n_layers);
+  if (cached)
+    for (int l = 0; l < n_layers && cached; ++l) {
+      const LayerDev& L = ctx->layer_tab_host[l];
+      cached = L.grad_sum == layers[l].grad_sum && L.d_in == layers[l].d_in &&
+               L.d_out == layers[l].d_out && layers[l].grad_sum != nullptr;
+    }
+  if (!cached) {
+    int rc = prepare_tables(ctx, layers, n_layers, dtype, false, st);
+    if (rc) return rc;
+  }
+  const size_t nblk = sqnorm_partials(ctx->layer_tab_host);
+  int rc = ensure_scratch(ctx, ctx->red_f64, nblk * sizeof(double));
+  if (rc) return rc;
+  hipEvent_t ev = prof_begin(ctx, st);
+  hipError_t e = launch_sqnorm(static_cast<const LayerDev*>(ctx->layer_tab.ptr), ctx->layer_tab_host,
+                               static_cast<double*>(ctx->red_f64.ptr), ctx->dev_scalars, st);
+  prof_end(ctx, kProfSqnorm, ev, st);
+  if (e != hipSuccess)
+    return fail(ctx, ADLOCO_EHIP, "norm_test: reduction launch failed: %s", hipGetErrorString(e));
+  ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->pinned, ctx->dev_scalars, sizeof(double),
+                                       hipMemcpyDeviceToHost, st));
+  ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->pinned + 2, acc, sizeof(adloco_stats_acc),
+                                       hipMemcpyDeviceToHost, st));
+  ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+  const double S2 = ctx->pinned[0];
+  adloco_stats_acc h;
+  std::memcpy(&h, ctx->pinned + 2, sizeof h);
+  if (h.n_samples < 1)
+    return fail(ctx, ADLOCO_ESTATE, "norm_test: accumulator holds no samples (n_samples = %lld)",
+                (long long)h.n_samples);
+  rc = adloco_norm_test_decide(h.sum_sample_sqnorm, S2, h.n_samples, eta, b_cur, b_max, n_switch,
+                               b_cap, flags, out);
+  if (rc) return fail(ctx, rc, "norm_test: decision rejected S1 = %g, S2 = %g", h.sum_sample_sqnorm, S2);
+  return ADLOCO_OK;
+}

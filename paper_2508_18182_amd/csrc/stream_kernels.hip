@@ -1,0 +1,298 @@
+// HBM-streaming kernels: the multi-instance outer step (Algorithm 3: pseudo-gradient,
+// OuterOpt, worker reset) and the trainer merge (Algorithm 2).  Every parameter is read
+// once from each input and written once to each output; arithmetic is fp64 in registers
+// (free next to the memory traffic) and rounded to fp32 once.
+#include "common.h"
+
+namespace adloco {
+
+struct OuterArgs {
+  float* theta;
+  float* mom;         // may be null (mu == 0)
+  float* pg;          // may be null
+  float* inst[ADLOCO_MAX_INSTANCES];
+  size_t n_vec;       // number of float4 elements handled by the vector kernel
+  size_t n;           // total number of floats
+  double lr, mu, inv_m;
+  int nesterov, broadcast;
+};
+
+struct MergeArgs {
+  float* x[ADLOCO_MAX_INSTANCES];
+  double w[ADLOCO_MAX_INSTANCES];   // b_j
+  double inv_wsum;
+  size_t n_vec, n;
+  int rep;
+};
+
+typedef float __attribute__((ext_vector_type(4))) f32x4;
+
+__device__ __forceinline__ f32x4 ld_stream(const float* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+}
+
+template <int M>
+__device__ __forceinline__ void outer_elem(const OuterArgs& a, double th, double buf,
+                                           const double (&x)[M], double& th_new,
+                                           double& buf_new, double& delta) {
+  // Delta = (1/M) sum_m (theta_outer - theta_m): differences first, as Algorithm 3 writes it
+  double s = 0.0;
+#pragma unroll
+  for (int m = 0; m < M; ++m) s += th - x[m];
+  delta = s * a.inv_m;
+  buf_new = a.mu * buf + delta;
+  const double step = a.nesterov ? delta + a.mu * buf_new : buf_new;
+  th_new = th - a.lr * step;
+}
+
+template <int M>
+__global__ __launch_bounds__(256) void outer_step_vec_kernel(OuterArgs a) {
+  const size_t stride = size_t(gridDim.x) * blockDim.x;
+  for (size_t v = size_t(blockIdx.x) * blockDim.x + threadIdx.x; v < a.n_vec; v += stride) {
+    const size_t e = v * 4;
+    f32x4 th = *reinterpret_cast<const f32x4*>(a.theta + e);
+    f32x4 bf = {0.f, 0.f, 0.f, 0.f};
+    if (a.mom) bf = *reinterpret_cast<const f32x4*>(a.mom + e);
+    f32x4 xs[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) xs[m] = ld_stream(a.inst[m] + e);
+    f32x4 th_o, bf_o, pg_o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      double x[M];
+#pragma unroll
+      for (int m = 0; m < M; ++m) x[m] = double(xs[m][c]);
+      double tn, bn, dl;
+      outer_elem<M>(a, double(th[c]), double(bf[c]), x, tn, bn, dl);
+      th_o[c] = float(tn);
+      bf_o[c] = float(bn);
+      pg_o[c] = float(dl);
+    }
+    *reinterpret_cast<f32x4*>(a.theta + e) = th_o;
+    if (a.mom) *reinterpret_cast<f32x4*>(a.mom + e) = bf_o;
+    if (a.pg) __builtin_nontemporal_store(pg_o, reinterpret_cast<f32x4*>(a.pg + e));
+    if (a.broadcast) {
+#pragma unroll
+      for (int m = 0; m < M; ++m)
+        __builtin_nontemporal_store(th_o, reinterpret_cast<f32x4*>(a.inst[m] + e));
+    }
+  }
+}
+
+// Scalar path: the tail after the last whole float4 (first = n_vec*4) or, for pointers that
+// are not 16-byte aligned, the whole vector (first = 0).
+template <int M>
+__global__ __launch_bounds__(256) void outer_step_scalar_kernel(OuterArgs a, size_t first) {
+  const size_t stride = size_t(gridDim.x) * blockDim.x;
+  for (size_t e = first + size_t(blockIdx.x) * blockDim.x + threadIdx.x; e < a.n; e += stride) {
+    double x[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) x[m] = double(a.inst[m][e]);
+    double tn, bn, dl;
+    outer_elem<M>(a, double(a.theta[e]), a.mom ? double(a.mom[e]) : 0.0, x, tn, bn, dl);
+    a.theta[e] = float(tn);
+    if (a.mom) a.mom[e] = float(bn);
+    if (a.pg) a.pg[e] = float(dl);
+    if (a.broadcast) {
+#pragma unroll
+      for (int m = 0; m < M; ++m) a.inst[m][e] = float(tn);
+    }
+  }
+}
+
+template <int S>
+__device__ __forceinline__ double merge_elem(const MergeArgs& a, const double (&x)[S]) {
+  // x_merge = w_sum^{-1} sum_j b_j x_j
+  double s = 0.0;
+#pragma unroll
+  for (int j = 0; j < S; ++j) s += a.w[j] * x[j];
+  return s * a.inv_wsum;
+}
+
+template <int S>
+__global__ __launch_bounds__(256) void merge_vec_kernel(MergeArgs a) {
+  const size_t stride = size_t(gridDim.x) * blockDim.x;
+  for (size_t v = size_t(blockIdx.x) * blockDim.x + threadIdx.x; v < a.n_vec; v += stride) {
+    const size_t e = v * 4;
+    f32x4 xs[S];
+#pragma unroll
+    for (int j = 0; j < S; ++j) xs[j] = ld_stream(a.x[j] + e);
+    f32x4 o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      double x[S];
+#pragma unroll
+      for (int j = 0; j < S; ++j) x[j] = double(xs[j][c]);
+      o[c] = float(merge_elem<S>(a, x));
+    }
+    *reinterpret_cast<f32x4*>(a.x[a.rep] + e) = o;
+  }
+}
+
+template <int S>
+__global__ __launch_bounds__(256) void merge_scalar_kernel(MergeArgs a, size_t first) {
+  const size_t stride = size_t(gridDim.x) * blockDim.x;
+  for (size_t e = first + size_t(blockIdx.x) * blockDim.x + threadIdx.x; e < a.n; e += stride) {
+    double x[S];
+#pragma unroll
+    for (int j = 0; j < S; ++j) x[j] = double(a.x[j][e]);
+    a.x[a.rep][e] = float(merge_elem<S>(a, x));
+  }
+}
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static inline unsigned grid_for(size_t work_items, int blocks_per_cu) {
+  size_t need = (work_items + 255) / 256;
+  size_t cap = size_t(kNumCu) * blocks_per_cu;
+  if (need < 1) need = 1;
+  return static_cast<unsigned>(need < cap ? need : cap);
+}
+
+template <int M>
+static hipError_t launch_outer_m(const OuterArgs& a, bool vec, int bpc, hipStream_t st) {
+  if (vec) {
+    if (a.n_vec > 0)
+      hipLaunchKernelGGL(outer_step_vec_kernel<M>, dim3(grid_for(a.n_vec, bpc)), dim3(256), 0, st, a);
+    if (a.n_vec * 4 < a.n)
+      hipLaunchKernelGGL(outer_step_scalar_kernel<M>, dim3(1), dim3(256), 0, st, a, a.n_vec * 4);
+  } else {
+    hipLaunchKernelGGL(outer_step_scalar_kernel<M>, dim3(grid_for(a.n, bpc)), dim3(256), 0, st, a,
+                       size_t(0));
+  }
+  return hipGetLastError();
+}
+
+template <int S>
+static hipError_t launch_merge_s(const MergeArgs& a, bool vec, int bpc, hipStream_t st) {
+  if (vec) {
+    if (a.n_vec > 0)
+      hipLaunchKernelGGL(merge_vec_kernel<S>, dim3(grid_for(a.n_vec, bpc)), dim3(256), 0, st, a);
+    if (a.n_vec * 4 < a.n)
+      hipLaunchKernelGGL(merge_scalar_kernel<S>, dim3(1), dim3(256), 0, st, a, a.n_vec * 4);
+  } else {
+    hipLaunchKernelGGL(merge_scalar_kernel<S>, dim3(grid_for(a.n, bpc)), dim3(256), 0, st, a,
+                       size_t(0));
+  }
+  return hipGetLastError();
+}
+
+#define ADLOCO_DISPATCH_COUNT(n, FN, ...)                                                   \
+  switch (n) {                                                                              \
+    case 1: e = FN<1>(__VA_ARGS__); break;                                                  \
+    case 2: e = FN<2>(__VA_ARGS__); break;                                                  \
+    case 3: e = FN<3>(__VA_ARGS__); break;                                                  \
+    case 4: e = FN<4>(__VA_ARGS__); break;                                                  \
+    case 5: e = FN<5>(__VA_ARGS__); break;                                                  \
+    case 6: e = FN<6>(__VA_ARGS__); break;                                                  \
+    case 7: e = FN<7>(__VA_ARGS__); break;                                                  \
+    case 8: e = FN<8>(__VA_ARGS__); break;                                                  \
+    case 9: e = FN<9>(__VA_ARGS__); break;                                                  \
+    case 10: e = FN<10>(__VA_ARGS__); break;                                                \
+    case 11: e = FN<11>(__VA_ARGS__); break;                                                \
+    case 12: e = FN<12>(__VA_ARGS__); break;                                                \
+    case 13: e = FN<13>(__VA_ARGS__); break;                                                \
+    case 14: e = FN<14>(__VA_ARGS__); break;                                                \
+    case 15: e = FN<15>(__VA_ARGS__); break;                                                \
+    case 16: e = FN<16>(__VA_ARGS__); break;                                                \
+    default: e = hipErrorInvalidValue;                                                      \
+  }
+
+}  // namespace adloco
+
+using namespace adloco;
+
+extern "C" int adloco_outer_step(adloco_ctx* ctx, float* theta_outer, float* const* theta_inst,
+                                 int M, size_t N, float* momentum, double lr, double mu,
+                                 int nesterov, uint32_t flags, float* pseudo_grad_out,
+                                 void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (M < 1) return fail(ctx, ADLOCO_EINVAL, "outer_step: M = %d, need M >= 1", M);
+  if (M > ADLOCO_MAX_INSTANCES)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "outer_step: M = %d exceeds %d", M, ADLOCO_MAX_INSTANCES);
+  if (flags & ~ADLOCO_BROADCAST) return fail(ctx, ADLOCO_EINVAL, "outer_step: unknown flags");
+  if (!(lr == lr) || !(mu == mu)) return fail(ctx, ADLOCO_EINVAL, "outer_step: lr or mu is NaN");
+  if (N == 0) return ADLOCO_OK;
+  if (!theta_outer || !theta_inst) return fail(ctx, ADLOCO_EINVAL, "outer_step: NULL pointer");
+  if (!momentum && mu != 0.0)
+    return fail(ctx, ADLOCO_EINVAL, "outer_step: momentum is NULL but mu != 0");
+  OuterArgs a{};
+  a.theta = theta_outer;
+  a.mom = momentum;
+  a.pg = pseudo_grad_out;
+  bool vec = aligned16(theta_outer) && aligned16(momentum) && aligned16(pseudo_grad_out);
+  for (int m = 0; m < M; ++m) {
+    float* p = theta_inst[m];
+    if (!p) return fail(ctx, ADLOCO_EINVAL, "outer_step: theta_inst[%d] is NULL", m);
+    if (p == theta_outer || p == momentum || p == pseudo_grad_out)
+      return fail(ctx, ADLOCO_EINVAL, "outer_step: theta_inst[%d] aliases another argument", m);
+    for (int j = 0; j < m; ++j)
+      if (theta_inst[j] == p && (flags & ADLOCO_BROADCAST))
+        return fail(ctx, ADLOCO_EINVAL, "outer_step: theta_inst[%d] == theta_inst[%d]", j, m);
+    vec = vec && aligned16(p);
+    a.inst[m] = p;
+  }
+  if (momentum && (momentum == theta_outer || momentum == pseudo_grad_out))
+    return fail(ctx, ADLOCO_EINVAL, "outer_step: momentum aliases another argument");
+  if (pseudo_grad_out && pseudo_grad_out == theta_outer)
+    return fail(ctx, ADLOCO_EINVAL, "outer_step: pseudo_grad_out aliases theta_outer");
+  a.n = N;
+  a.n_vec = vec ? N / 4 : 0;
+  a.lr = lr;
+  a.mu = mu;
+  a.inv_m = 1.0 / double(M);
+  a.nesterov = nesterov ? 1 : 0;
+  a.broadcast = (flags & ADLOCO_BROADCAST) ? 1 : 0;
+  hipError_t e;
+  hipEvent_t ev = prof_begin(ctx, static_cast<hipStream_t>(stream));
+  ADLOCO_DISPATCH_COUNT(M, launch_outer_m, a, vec, ctx->stream_blocks_per_cu,
+                        static_cast<hipStream_t>(stream));
+  prof_end(ctx, kProfOuter, ev, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess)
+    return fail(ctx, ADLOCO_EHIP, "outer_step launch failed: %s", hipGetErrorString(e));
+  return ADLOCO_OK;
+}
+
+extern "C" int adloco_merge(adloco_ctx* ctx, float* const* x, const double* weights, int S,
+                            size_t N, int rep, int* rep_out, void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (S < 1) return fail(ctx, ADLOCO_EINVAL, "merge: S = %d, need S >= 1", S);
+  if (S > ADLOCO_MAX_INSTANCES)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "merge: S = %d exceeds %d", S, ADLOCO_MAX_INSTANCES);
+  if (!weights) return fail(ctx, ADLOCO_EINVAL, "merge: weights is NULL");
+  if (rep < -1 || rep >= S) return fail(ctx, ADLOCO_EINVAL, "merge: rep = %d out of range", rep);
+  MergeArgs a{};
+  double wsum = 0.0;
+  int arg = 0;
+  for (int j = 0; j < S; ++j) {
+    if (!(weights[j] > 0.0) || weights[j] > 1.0e300)
+      return fail(ctx, ADLOCO_EINVAL, "merge: weights[%d] must be positive and finite", j);
+    a.w[j] = weights[j];
+    wsum += weights[j];
+    if (weights[j] > weights[arg]) arg = j;   // first maximum
+  }
+  if (rep < 0) rep = arg;
+  if (rep_out) *rep_out = rep;
+  if (N == 0) return ADLOCO_OK;
+  if (!x) return fail(ctx, ADLOCO_EINVAL, "merge: x is NULL");
+  bool vec = true;
+  for (int j = 0; j < S; ++j) {
+    if (!x[j]) return fail(ctx, ADLOCO_EINVAL, "merge: x[%d] is NULL", j);
+    for (int i = 0; i < j; ++i)
+      if (x[i] == x[j]) return fail(ctx, ADLOCO_EINVAL, "merge: x[%d] == x[%d]", i, j);
+    vec = vec && aligned16(x[j]);
+    a.x[j] = x[j];
+  }
+  a.inv_wsum = 1.0 / wsum;
+  a.n = N;
+  a.n_vec = vec ? N / 4 : 0;
+  a.rep = rep;
+  if (S == 1) return ADLOCO_OK;   // a singleton merge leaves x_r as it is, bit for bit
+  hipError_t e;
+  hipEvent_t ev = prof_begin(ctx, static_cast<hipStream_t>(stream));
+  ADLOCO_DISPATCH_COUNT(S, launch_merge_s, a, vec, ctx->stream_blocks_per_cu,
+                        static_cast<hipStream_t>(stream));
+  prof_end(ctx, kProfMerge, ev, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(ctx, ADLOCO_EHIP, "merge launch failed: %s", hipGetErrorString(e));
+  return ADLOCO_OK;
+}

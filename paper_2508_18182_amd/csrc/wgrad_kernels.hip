@@ -1,0 +1,260 @@
+// Gradient sum of a linear layer over the batch: G^l (+)= sum_i delta_i^T a_i, i.e. B times
+// the mini-batch gradient of eq. 1 (and Algorithm 3's "g <- g + grad L" across micro-batches).
+// A GEMM [d_out, d_in] with the contraction over all B*T token rows.  Both operands are stored
+// token-major (the contraction index is the slow one), so tiles are staged in LDS as they are
+// and handed to the MFMA through the LDS transpose read of gfx950.
+#include "common.h"
+
+namespace adloco {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+struct WgradArgs {
+  const LayerDev* layers;
+  int n_layers;
+  long long rows;      // B*T
+  int accumulate;
+};
+
+__device__ __forceinline__ int find_layer_wg(const LayerDev* layers, int n_layers, int b) {
+  int lo = 0, hi = n_layers - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (layers[mid].wg_blk_start <= b) lo = mid; else hi = mid - 1;
+  }
+  // layers with ADLOCO_GRAD_PROVIDED own no workgroup and share a start with their successor;
+  // the search lands on the last layer with that start, which is the one that owns workgroups.
+  return lo;
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16: 128 (d_out) x 128 (d_in) output tile per workgroup, 4 waves 2x2, MFMA 32x32x16.
+// LDS stage: 32 token rows of delta[.,128] and of a[.,128], row pitch 144 elements.
+// ---------------------------------------------------------------------------------------
+constexpr int kWt = 128;
+constexpr int kWk = 32;
+constexpr int kWpitch = 144;                      // elements; 288 bytes
+constexpr int kWopBytes = kWk * kWpitch * 2;      // one operand of one stage
+constexpr int kWstage = 2 * kWopBytes;
+constexpr int kWlds = 2 * kWstage;
+
+struct WChunk { u32x4 v[4]; };
+
+__device__ __forceinline__ void wgrad_load(const LayerDev& L, long long rows, long long k0, int e0,
+                                           int c0, WChunk& r) {
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int e = threadIdx.x + 256 * it;
+    const int op = e >> 9;                 // 0: delta (d_out side), 1: a (d_in side)
+    const int row = (e & 511) >> 4;
+    const int ch = e & 15;
+    const unsigned short* base = reinterpret_cast<const unsigned short*>(op ? L.a : L.delta);
+    const long long stride = op ? L.a_stride : L.delta_stride;
+    const int d = op ? L.d_in : L.d_out;
+    const int col = (op ? c0 : e0) + ch * 8;
+    const long long k = k0 + row;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (k < rows && col < d) {
+      const unsigned short* src = base + k * stride + col;
+      if (L.fast) {
+        v = *reinterpret_cast<const u32x4*>(src);
+      } else {
+        unsigned short h[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = (col + j < d) ? src[j] : (unsigned short)0;
+        v[0] = h[0] | (unsigned(h[1]) << 16);
+        v[1] = h[2] | (unsigned(h[3]) << 16);
+        v[2] = h[4] | (unsigned(h[5]) << 16);
+        v[3] = h[6] | (unsigned(h[7]) << 16);
+      }
+    }
+    r.v[it] = v;
+  }
+}
+
+__device__ __forceinline__ void wgrad_store(unsigned char* stage, const WChunk& r) {
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int e = threadIdx.x + 256 * it;
+    const int op = e >> 9;
+    const int row = (e & 511) >> 4;
+    const int ch = e & 15;
+    *reinterpret_cast<u32x4*>(stage + op * kWopBytes + row * (kWpitch * 2) + ch * 16) = r.v[it];
+  }
+}
+
+// Fragment of the MFMA operand for output rows/cols m0..m0+31 and k-step ks (16 token rows):
+// lane l holds column m0 + l%32 at the eight token rows ks*16 + (l/32)*8 + 0..7.
+template <int VARIANT>
+__device__ __forceinline__ bf16x8 wgrad_frag(const unsigned char* op_base, int m0, int ks,
+                                             int lane) {
+  const int kbase = ks * 16 + (lane >> 5) * 8;
+  if (VARIANT == 0) {
+    // gather: eight 2-byte reads down one column
+    const unsigned short* p =
+        reinterpret_cast<const unsigned short*>(op_base) + kbase * kWpitch + m0 + (lane & 31);
+    s16x8 v;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = (short)p[j * kWpitch];
+    return __builtin_bit_cast(bf16x8, v);
+  } else {
+    // LDS transpose read: within each group of 16 lanes, lane s points at 4 consecutive columns
+    // of token row kbase + s/4 (columns 4*(s%4)..+3 of the group's 16); the instruction hands
+    // lane i the four token rows of column i.
+    const int i = lane & 15;
+    const int colbase = m0 + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
+    const unsigned short* p =
+        reinterpret_cast<const unsigned short*>(op_base) + (kbase + (i >> 2)) * kWpitch + colbase;
+    typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * kWpitch));
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+template <int VARIANT>
+__device__ __forceinline__ void wgrad_mma(const unsigned char* stage, int wm, int wn, int lane,
+                                          f32x16 (&acc)[2][2]) {
+  const unsigned char* dt = stage;               // delta tile: rows = tokens, cols = d_out
+  const unsigned char* at = stage + kWopBytes;   // a tile
+#pragma unroll
+  for (int ks = 0; ks < kWk / 16; ++ks) {
+    bf16x8 fa[2], fb[2];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) fa[m] = wgrad_frag<VARIANT>(dt, wm * 64 + m * 32, ks, lane);
+#pragma unroll
+    for (int n = 0; n < 2; ++n) fb[n] = wgrad_frag<VARIANT>(at, wn * 64 + n * 32, ks, lane);
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m], fb[n], acc[m][n], 0, 0, 0);
+  }
+}
+
+template <int VARIANT>
+__global__ __launch_bounds__(256, 2) void wgrad_bf16_kernel(WgradArgs g) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWlds];
+  const int layer = find_layer_wg(g.layers, g.n_layers, blockIdx.x);
+  const LayerDev L = g.layers[layer];
+  const int tiles_c = (L.d_in + kWt - 1) / kWt;
+  const int tile = blockIdx.x - L.wg_blk_start;
+  const int e0 = (tile / tiles_c) * kWt;
+  const int c0 = (tile % tiles_c) * kWt;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[m][n][j] = 0.f;
+
+  const long long nk = (g.rows + kWk - 1) / kWk;
+  WChunk regs;
+  wgrad_load(L, g.rows, 0, e0, c0, regs);
+  wgrad_store(lds, regs);
+  __syncthreads();
+  for (long long c = 0; c < nk; ++c) {
+    unsigned char* cur = lds + (c & 1) * kWstage;
+    unsigned char* nxt = lds + ((c + 1) & 1) * kWstage;
+    const bool more = c + 1 < nk;
+    if (more) wgrad_load(L, g.rows, (c + 1) * kWk, e0, c0, regs);
+    wgrad_mma<VARIANT>(cur, wm, wn, lane, acc);
+    if (more) wgrad_store(nxt, regs);
+    __syncthreads();
+  }
+
+  // accumulator element j of a 32x32 block: row (j/4)*8 + (lane/32)*4 + j%4, column lane%32
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+      const int col = c0 + wn * 64 + n * 32 + (lane & 31);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int row = e0 + wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        if (row < L.d_out && col < L.d_in) {
+          float* dst = L.grad_sum + (size_t)row * L.d_in + col;
+          *dst = g.accumulate ? *dst + acc[m][n][j] : acc[m][n][j];
+        }
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 inputs: plain FMA path, 32x32 output tile, 2x2 entries per thread.
+// ---------------------------------------------------------------------------------------
+constexpr int kWtF = 32;
+constexpr int kWkF = 16;
+
+__global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs g) {
+  __shared__ float sd[kWkF][kWtF + 1];
+  __shared__ float sa[kWkF][kWtF + 1];
+  const int layer = find_layer_wg(g.layers, g.n_layers, blockIdx.x);
+  const LayerDev L = g.layers[layer];
+  const int tiles_c = (L.d_in + kWtF - 1) / kWtF;
+  const int tile = blockIdx.x - L.wg_blk_start;
+  const int e0 = (tile / tiles_c) * kWtF;
+  const int c0 = (tile % tiles_c) * kWtF;
+  const float* D = reinterpret_cast<const float*>(L.delta);
+  const float* A = reinterpret_cast<const float*>(L.a);
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+  for (long long k0 = 0; k0 < g.rows; k0 += kWkF) {
+    for (int e = threadIdx.x; e < kWkF * kWtF; e += 256) {
+      const int row = e / kWtF, col = e % kWtF;
+      const long long k = k0 + row;
+      sd[row][col] = (k < g.rows && e0 + col < L.d_out) ? D[k * L.delta_stride + e0 + col] : 0.f;
+      sa[row][col] = (k < g.rows && c0 + col < L.d_in) ? A[k * L.a_stride + c0 + col] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kWkF; ++k) {
+      const float d0 = sd[k][ty * 2], d1 = sd[k][ty * 2 + 1];
+      const float a0 = sa[k][tx * 2], a1 = sa[k][tx * 2 + 1];
+      acc[0][0] = fmaf(d0, a0, acc[0][0]);
+      acc[0][1] = fmaf(d0, a1, acc[0][1]);
+      acc[1][0] = fmaf(d1, a0, acc[1][0]);
+      acc[1][1] = fmaf(d1, a1, acc[1][1]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int row = e0 + ty * 2 + i, col = c0 + tx * 2 + j;
+      if (row < L.d_out && col < L.d_in) {
+        float* dst = L.grad_sum + (size_t)row * L.d_in + col;
+        *dst = g.accumulate ? *dst + acc[i][j] : acc[i][j];
+      }
+    }
+}
+
+int wgrad_tile_edge(int dtype) { return dtype == ADLOCO_BF16 ? kWt : kWtF; }
+
+hipError_t launch_wgrad(const LayerDev* layers, int n_layers, int n_blocks, long long rows,
+                        int dtype, int accumulate, int variant, hipStream_t st) {
+  if (n_blocks <= 0) return hipSuccess;
+  WgradArgs a{layers, n_layers, rows, accumulate};
+  if (dtype == ADLOCO_BF16) {
+    if (variant == 0)
+      hipLaunchKernelGGL(wgrad_bf16_kernel<0>, dim3(n_blocks), dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL(wgrad_bf16_kernel<1>, dim3(n_blocks), dim3(256), 0, st, a);
+  } else {
+    hipLaunchKernelGGL(wgrad_f32_kernel, dim3(n_blocks), dim3(256), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace adloco

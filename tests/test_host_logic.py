@@ -1,0 +1,125 @@
+"""CPU-only tests of the C-ABI library: it loads, exports every declared symbol, and its
+host-side decision logic agrees with the hand-worked fixtures and with the oracle."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2508_18182_amd as A
+from oracle import adloco_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLD = os.path.join(ROOT, "tests", "golden")
+
+
+def _lines(name):
+    with open(os.path.join(GOLD, name)) as f:
+        for ln in f:
+            ln = ln.rstrip("\n")
+            if ln.strip() and not ln.lstrip().startswith("#"):
+                yield ln
+
+
+def _ints(s):
+    s = s.strip()
+    return [int(v) for v in s.split(",")] if s else []
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "adloco.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(adloco_[a-z_]+)\s*\(", hdr))
+    assert {"adloco_grad_stats", "adloco_norm_test", "adloco_outer_step", "adloco_merge",
+            "adloco_check_merge", "adloco_create", "adloco_destroy"} <= names
+    lib = ctypes.CDLL(A.lib_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in adloco.h but not exported"
+    assert A.adloco_version() >= 100
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(A.LinearDesc) == 56
+    assert ctypes.sizeof(A.StatsAcc) == 16
+    assert ctypes.sizeof(A.NormTestResult) == 96
+
+
+def test_check_merge_fixture():
+    for ln in _lines("check_merge_cases.txt"):
+        b, w, want = ln.split(";")
+        assert A.adloco_check_merge(_ints(b), int(w)) == _ints(want), ln
+
+
+def test_switch_mode_fixture():
+    for ln in _lines("switch_mode_cases.txt"):
+        lhs, rhs = ln.split("->")
+        b_req, b_max, nsw = [int(v) for v in lhs.split()]
+        acc, steps, micro = [int(v) for v in rhs.split()]
+        got = A.adloco_switch_mode(b_req, b_max, nsw)
+        assert (got["accumulate"], got["accum_steps"], got["b_micro"]) == (acc, steps, micro), ln
+
+
+def test_norm_test_fixture():
+    for ln in _lines("norm_test_hand_cases.txt"):
+        lhs, rhs = ln.split("->")
+        S1, S2, B, eta, b_cur, biased, shrink, cap = lhs.split()
+        var, stat, b_req, passed = rhs.split()
+        flags = (A.ADLOCO_BIASED_VAR if int(biased) else 0) | (A.ADLOCO_ALLOW_SHRINK if int(shrink) else 0)
+        res = A.adloco_norm_test_decide(float(S1), float(S2), int(B), float(eta), int(b_cur),
+                                        1 << 40, 2, int(cap), flags)
+        assert res["variance"] == pytest.approx(float(var), rel=1e-12)
+        if math.isinf(float(stat)):
+            assert math.isinf(res["stat"])
+        else:
+            assert res["stat"] == pytest.approx(float(stat), rel=1e-12)
+        assert res["b_req"] == int(b_req), ln
+        assert res["test_passed"] == int(passed), ln
+
+
+def test_decide_matches_oracle_on_random_inputs():
+    r = np.random.Generator(np.random.PCG64(123))
+    keys = ("b_req", "test_passed", "accumulate", "accum_steps", "b_micro", "stat_undefined")
+    for it in range(2000):
+        B = int(r.integers(1, 300))
+        S2 = float(r.uniform(0.0, 10.0)) * B if it % 17 else 0.0
+        S1 = S2 / B + (float(r.uniform(0.0, 100.0)) if it % 13 else 0.0)
+        eta = float(r.uniform(0.05, 0.95))
+        b_cur = int(r.integers(1, 300))
+        b_max = int(r.integers(1, 64))
+        nsw = int(r.integers(1, 4))
+        cap = int(r.integers(0, 2)) * int(r.integers(1, 2000))
+        biased = bool(r.integers(0, 2))
+        shrink = bool(r.integers(0, 2))
+        flags = (A.ADLOCO_BIASED_VAR if biased else 0) | (A.ADLOCO_ALLOW_SHRINK if shrink else 0)
+        got = A.adloco_norm_test_decide(S1, S2, B, eta, b_cur, b_max, nsw, cap, flags)
+        want = orc.norm_test(S1, S2, B, eta, b_cur, b_max, nsw, cap, biased_var=biased,
+                             allow_shrink=shrink)
+        for k in keys:
+            assert got[k] == want[k], (k, it, got, want)
+        if not want["stat_undefined"] and not math.isinf(want["stat"]):
+            assert got["stat"] == pytest.approx(want["stat"], rel=1e-12, abs=1e-300)
+
+
+def test_check_merge_matches_oracle_random():
+    r = np.random.Generator(np.random.PCG64(5))
+    for _ in range(500):
+        k = int(r.integers(0, 9))
+        b = [int(v) for v in r.integers(1, 6, size=k)]
+        w = int(r.integers(0, 10))
+        assert A.adloco_check_merge(b, w) == orc.check_merge(b, w)
+
+
+def test_host_argument_errors():
+    with pytest.raises(A.AdlocoError):
+        A.adloco_norm_test_decide(1.0, 1.0, 0, 0.3, 1, 32)      # no samples
+    with pytest.raises(A.AdlocoError):
+        A.adloco_norm_test_decide(1.0, 1.0, 4, 0.0, 1, 32)      # eta must be positive
+    with pytest.raises(A.AdlocoError):
+        A.adloco_switch_mode(0, 32, 2)
+    with pytest.raises(A.AdlocoError):
+        A.adloco_norm_test_decide(float("nan"), 1.0, 4, 0.3, 1, 32)
+    # huge requested batches do not overflow the switch rule
+    got = A.adloco_switch_mode((1 << 63) - 1, 32, 2)
+    assert got["accumulate"] == 1 and got["b_micro"] == 32
