@@ -52,6 +52,10 @@ struct adloco_ctx {
   adloco::Scratch order_tab;   // int [n_layers] launch order (heaviest first)
   std::vector<adloco::LayerDev> layer_tab_host;  // last uploaded copy
   std::vector<int> order_host;
+  adloco::Scratch job_tab;     // GramJob[] of the dual-tile Gram kernel
+  int job_tab_nt = -1;         // number of row blocks the uploaded job table was built for
+  int job_tab_n = 0;
+  bool all_fast64 = false;     // every layer: aligned rows and widths that are multiples of 64
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
   double* pinned = nullptr;    // 4 doubles of pinned host memory (norm-test read-back)
@@ -62,8 +66,8 @@ struct adloco_ctx {
   std::vector<hipEvent_t> prof_free;
   int profile = 0;
   // tuning
-  int gram_variant = 0;
-  int wgrad_variant = 0;
+  int gram_variant = 1;        // 1: dual-tile kernel when eligible, 0: always the generic one
+  int wgrad_variant = 1;
   int stream_blocks_per_cu = 8;
   int stream_variant = 0;
 };
@@ -106,7 +110,18 @@ struct GramLaunch {
   int n_pairs;              // tile pairs per (layer, sample)
   int tile;                 // T-tile edge used by the kernel
 };
+// One workgroup of the dual-tile Gram kernel: up to two 128x128 tile pairs (A-block, B-block)
+// drawn from at most three distinct 128-row blocks.
+struct GramJob {
+  int blk[3];      // distinct row blocks to stage (unused entries repeat blk[0])
+  int nblk;        // 2 or 3 (1 when T fits one block)
+  int sa[2], sb[2];  // per tile pair: which staged block supplies the rows / the columns
+  float w[2];      // 1 on the diagonal, 2 off it (symmetry), 0 for an absent second pair
+};
+std::vector<GramJob> make_gram_jobs(int nt);
 int gram_tile_edge(int dtype, int variant);
+hipError_t launch_gram_bf16_dual(const GramLaunch& g, const GramJob* jobs, int n_jobs,
+                                 hipStream_t st);
 hipError_t launch_gram_bf16(const GramLaunch& g, int variant, hipStream_t st);
 hipError_t launch_gram_f32(const GramLaunch& g, hipStream_t st);
 int wgrad_tile_edge(int dtype);

@@ -83,6 +83,9 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
                                        hipMemcpyHostToDevice, st));
   // pageable sources: make sure the runtime has consumed them before they go out of scope
   ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+  bool f64 = need_inputs;
+  for (const LayerDev& L : tab) f64 = f64 && L.fast && L.d_in % 64 == 0 && L.d_out % 64 == 0;
+  ctx->all_fast64 = f64;
   ctx->layer_tab_host = std::move(tab);
   ctx->order_host = std::move(order);
   ctx->wgrad_blocks = int(wg);
@@ -115,7 +118,23 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
 
   const int tile = gram_tile_edge(dtype, ctx->gram_variant);
   const long long nt = (T + tile - 1) / tile;
-  const long long n_pairs = nt * (nt + 1) / 2;
+  if (nt > 4096) return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: T = %d gives too many tiles", T);
+  const bool dual = dtype == ADLOCO_BF16 && ctx->gram_variant != 0 && ctx->all_fast64;
+  long long n_pairs = nt * (nt + 1) / 2;      // partial sums per (layer, sample)
+  if (dual) {
+    if (ctx->job_tab_nt != int(nt)) {
+      std::vector<GramJob> jobs = make_gram_jobs(int(nt));
+      rc = ensure_scratch(ctx, ctx->job_tab, jobs.size() * sizeof(GramJob));
+      if (rc) return rc;
+      ctx->job_tab_nt = -1;
+      ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->job_tab.ptr, jobs.data(), jobs.size() * sizeof(GramJob),
+                                           hipMemcpyHostToDevice, st));
+      ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+      ctx->job_tab_nt = int(nt);
+      ctx->job_tab_n = int(jobs.size());
+    }
+    n_pairs = ctx->job_tab_n;
+  }
   const long long n_part = (long long)n_layers * B * n_pairs;
   if (n_pairs > 0x7fffffffLL || n_part > (1LL << 40))
     return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: T = %d gives too many tile pairs", T);
@@ -134,8 +153,13 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   g.n_pairs = int(n_pairs);
   g.tile = tile;
   hipEvent_t ev = prof_begin(ctx, st);
-  hipError_t e = dtype == ADLOCO_BF16 ? launch_gram_bf16(g, ctx->gram_variant, st)
-                                      : launch_gram_f32(g, st);
+  hipError_t e;
+  if (dual)
+    e = launch_gram_bf16_dual(g, static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n, st);
+  else if (dtype == ADLOCO_BF16)
+    e = launch_gram_bf16(g, ctx->gram_variant, st);
+  else
+    e = launch_gram_f32(g, st);
   prof_end(ctx, kProfGram, ev, st);
   if (e != hipSuccess)
     return fail(ctx, ADLOCO_EHIP, "grad_stats: Gram launch failed: %s", hipGetErrorString(e));

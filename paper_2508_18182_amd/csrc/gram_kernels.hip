@@ -199,6 +199,219 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(GramArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------
+// bf16 fast path ("dual-tile" kernel), used when every operand row is 16-byte aligned and every
+// width is a multiple of 64.
+//   workgroup: 512 threads = 8 waves = two groups of four; each group owns one 128x128 tile pair
+//   of one job.  A job is a pair of tile pairs that share a row block, so that at most three
+//   distinct 128-row blocks have to be staged: less L2 and LDS-write traffic per MFMA than one
+//   tile pair per workgroup, with the same executed flops.
+//   Staging: global -> LDS directly (16 bytes per lane, no registers in between), three stages
+//   of (3 blocks x 128 rows x 64 bf16).  One workgroup barrier per k-chunk, placed in the middle
+//   of the chunk: by then every wave's loads of the next chunk have landed and every wave has
+//   finished with the previous chunk's stage, so the chunk after next is requested right there
+//   and the fragment reads never drain across a chunk boundary.
+//   Fragments for the next k-step are read from LDS while the MFMAs of the current one run.
+// ---------------------------------------------------------------------------------------
+constexpr int kDualStageRows = 3 * kTile;
+constexpr int kDualStage = kDualStageRows * kKc * 2;          // 48 KiB
+constexpr int kDualStages = 3;
+constexpr int kDualLds = kDualStages * kDualStage;            // 144 KiB
+
+struct GramDualArgs {
+  const LayerDev* layers;
+  const int* order;
+  const GramJob* jobs;
+  float* partials;
+  int n_layers, B, T, n_jobs, units_padded;
+};
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | ((N >> 4) << 14));
+}
+
+__device__ __forceinline__ void wg_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+__global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int bid = blockIdx.x;
+  const int xcd = bid % kNumXcd;
+  const int slot = bid / kNumXcd;
+  const int job = slot % g.n_jobs;
+  const int u = (slot / g.n_jobs) * kNumXcd + xcd;
+  if (u >= g.n_layers * g.B) return;
+  const int layer = g.order[u / g.B];
+  const int sample = u % g.B;
+  const LayerDev L = g.layers[layer];
+  const GramJob J = g.jobs[job];
+  const int nblk = __builtin_amdgcn_readfirstlane(J.nblk);
+  const int T = g.T;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int grp = wave >> 2;                         // which tile pair of the job
+  const int wm = (wave >> 1) & 1, wn = wave & 1;     // 2x2 waves over the 128x128 tile
+  const int slot_a = grp ? J.sa[1] : J.sa[0];
+  const int slot_b = grp ? J.sb[1] : J.sb[0];
+  const int nka = L.d_in / kKc, nk = nka + L.d_out / kKc;
+  constexpr int ROWB = kKc * 2;
+
+  // ---- direct global->LDS loads.  One wave instruction fills 8 rows (1 KiB): lane -> row lane/8,
+  // 16-byte position lane%8, which receives chunk position ^ f(row) of that row.  Wave w covers
+  // row groups w and w+8 of each staged block.  Rows beyond T re-read row T-1 (their products
+  // are masked in the epilogue).
+  const int ld_row = wave * 8 + (lane >> 3);         // row within the block for i = 0; +64 for i = 1
+  const int ld_col = swz(ld_row, lane & 7) * 8;      // element offset within the 64-wide chunk
+  long long row_off[3][2];
+#pragma unroll
+  for (int s = 0; s < 3; ++s)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int t = J.blk[s < nblk ? s : 0] * kTile + ld_row + 64 * i;
+      t = t < T ? t : T - 1;
+      row_off[s][i] = (long long)sample * T + t;
+    }
+  auto issue_loads = [&](int c) {
+    const bool is_a = c < nka;
+    const unsigned short* base = reinterpret_cast<const unsigned short*>(is_a ? L.a : L.delta);
+    const long long stride = is_a ? L.a_stride : L.delta_stride;
+    const int k0 = (is_a ? c : c - nka) * kKc + ld_col;
+    unsigned char* stage = lds + (c % kDualStages) * kDualStage;
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+      if (s < nblk) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const unsigned short* src = base + row_off[s][i] * stride + k0;
+          __builtin_amdgcn_global_load_lds(
+              (const __attribute__((address_space(1))) void*)src,
+              (__attribute__((address_space(3))) void*)(stage + (s * kTile + (wave + 8 * i) * 8) * ROWB),
+              16, 0, 0);
+        }
+      }
+    }
+  };
+
+  // ---- fragment addressing
+  const int r32 = lane & 31, kg = lane >> 5;
+  int off_a[2], off_b[2], sw_a[2], sw_b[2];
+#pragma unroll
+  for (int m = 0; m < 2; ++m) {
+    const int ra = slot_a * kTile + wm * 64 + m * 32 + r32;
+    const int rb = slot_b * kTile + wn * 64 + m * 32 + r32;
+    off_a[m] = ra * ROWB;
+    off_b[m] = rb * ROWB;
+    sw_a[m] = swz(ra, 0);
+    sw_b[m] = swz(rb, 0);
+  }
+  auto read_frags = [&](int c, int ks, bf16x8 (&fa)[2], bf16x8 (&fb)[2]) {
+    const unsigned char* stage = lds + (c % kDualStages) * kDualStage;
+    const int chunk = ks * 2 + kg;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+      fa[m] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                                             stage + off_a[m] + ((chunk ^ sw_a[m]) * 16)));
+      fb[m] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                                             stage + off_b[m] + ((chunk ^ sw_b[m]) * 16)));
+    }
+  };
+
+  f32x16 acc_a[2][2], acc_d[2][2];
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) { acc_a[m][n][j] = 0.f; acc_d[m][n][j] = 0.f; }
+
+  // ---- prologue: chunks 0 and 1 in flight, chunk 0 landed for everybody
+  issue_loads(0);
+  if (nk > 1) {
+    issue_loads(1);
+    if (nblk == 3) wait_vmcnt<6>(); else if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
+  } else {
+    wait_vmcnt<0>();
+  }
+  wg_barrier();
+  bf16x8 fa[2][2], fb[2][2];
+  read_frags(0, 0, fa[0], fb[0]);
+
+  auto mfma4 = [&](const bf16x8 (&a)[2], const bf16x8 (&b)[2], f32x16 (&acc)[2][2]) {
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
+    // issue order: MFMA, LDS read, MFMA, LDS read, ...
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+  };
+  auto chunk_step = [&](int c, f32x16 (&acc)[2][2]) {
+    // k-step 0
+    read_frags(c, 1, fa[1], fb[1]);
+    mfma4(fa[0], fb[0], acc);
+    // k-step 1, with the barrier of this chunk in front of it
+    if (c + 1 < nk) {
+      wait_vmcnt<0>();            // my share of chunk c+1 (the only loads in flight) has landed
+      wg_barrier();               // ... and so has everybody's; stage (c-1)%3 is free
+      if (c + 2 < nk) issue_loads(c + 2);
+    }
+    read_frags(c, 2, fa[0], fb[0]);
+    mfma4(fa[1], fb[1], acc);
+    // k-step 2
+    read_frags(c, 3, fa[1], fb[1]);
+    mfma4(fa[0], fb[0], acc);
+    // k-step 3: fragments of the next chunk's first k-step (after the last chunk: a harmless
+    // re-read of this chunk, so that the reads stay interleaved with the MFMAs)
+    read_frags(c + 1 < nk ? c + 1 : c, 0, fa[0], fb[0]);
+    mfma4(fa[1], fb[1], acc);
+  };
+  int c = 0;
+  for (; c < nka; ++c) chunk_step(c, acc_a);
+  for (; c < nk; ++c) chunk_step(c, acc_d);
+
+  // ---- epilogue: < A A^T , D D^T > over this wave's 64x64 part, masked beyond T
+  const float w = grp ? J.w[1] : J.w[0];
+  float s = 0.f;
+  const int blk_a = J.blk[slot_a], blk_b = J.blk[slot_b];
+  if ((blk_a + 1) * kTile <= T && (blk_b + 1) * kTile <= T) {
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += acc_a[m][n][j] * acc_d[m][n][j];
+  } else {
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int n = 0; n < 2; ++n) {
+        const int col = blk_b * kTile + wn * 64 + n * 32 + r32;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int row = blk_a * kTile + wm * 64 + m * 32 + (j >> 2) * 8 + kg * 4 + (j & 3);
+          if (row < T && col < T) s += acc_a[m][n][j] * acc_d[m][n][j];
+        }
+      }
+  }
+  s = wave_sum_f32(s) * w;
+  __syncthreads();                                    // all fragment reads are over
+  float* red = reinterpret_cast<float*>(lds);
+  if (lane == 0) red[wave] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float t0 = (red[0] + red[1]) + (red[2] + red[3]);
+    const float t1 = (red[4] + red[5]) + (red[6] + red[7]);
+    g.partials[(size_t(layer) * g.B + sample) * g.n_jobs + job] = t0 + t1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // fp32 inputs: plain FMA path (correctness path for fp32 activations; not MFMA).
 //   workgroup: 256 threads over a 32x32 tile pair, 2x2 entries per thread.
 // ---------------------------------------------------------------------------------------
@@ -291,6 +504,68 @@ hipError_t launch_gram_bf16(const GramLaunch& l, int /*variant*/, hipStream_t st
   const long long grid = (long long)a.units_padded * a.n_pairs;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(gram_bf16_kernel, dim3(unsigned(grid)), dim3(256), kGramLds, st, a);
+  return hipGetLastError();
+}
+
+// Jobs of the dual-tile kernel for nt row blocks: tile pairs (p,q), p <= q, taken two at a time
+// so that the two share a block.  Along a row p consecutive pairs (p,q),(p,q+1) share block p;
+// a row's leftover (p, nt-1) is combined with another row's leftover, which shares block nt-1.
+std::vector<GramJob> make_gram_jobs(int nt) {
+  std::vector<GramJob> jobs;
+  auto make = [&](int p0, int q0, int p1, int q1) {
+    GramJob j{};
+    int blocks[4] = {p0, q0, p1 < 0 ? p0 : p1, q1 < 0 ? q0 : q1};
+    int n = 0;
+    int idx[4];
+    for (int i = 0; i < 4; ++i) {
+      int f = -1;
+      for (int k = 0; k < n; ++k)
+        if (j.blk[k] == blocks[i]) f = k;
+      if (f < 0) { j.blk[n] = blocks[i]; f = n++; }
+      idx[i] = f;
+    }
+    j.nblk = n;
+    for (int k = n; k < 3; ++k) j.blk[k] = j.blk[0];
+    j.sa[0] = idx[0]; j.sb[0] = idx[1]; j.sa[1] = idx[2]; j.sb[1] = idx[3];
+    j.w[0] = p0 == q0 ? 1.f : 2.f;
+    j.w[1] = p1 < 0 ? 0.f : (p1 == q1 ? 1.f : 2.f);
+    jobs.push_back(j);
+  };
+  std::vector<int> left;
+  for (int p = 0; p < nt; ++p) {
+    int q = p;
+    for (; q + 1 < nt; q += 2) make(p, q, p, q + 1);
+    if (q == nt - 1) left.push_back(p);
+  }
+  size_t i = 0;
+  for (; i + 1 < left.size(); i += 2) make(left[i], nt - 1, left[i + 1], nt - 1);
+  if (i < left.size()) make(left[i], nt - 1, -1, -1);
+  return jobs;
+}
+
+hipError_t launch_gram_bf16_dual(const GramLaunch& l, const GramJob* jobs, int n_jobs,
+                                 hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gram_bf16_dual_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kDualLds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  GramDualArgs a;
+  a.layers = l.layers;
+  a.order = l.order;
+  a.jobs = jobs;
+  a.partials = l.partials;
+  a.n_layers = l.n_layers;
+  a.B = l.B;
+  a.T = l.T;
+  a.n_jobs = n_jobs;
+  const int units = l.n_layers * l.B;
+  a.units_padded = (units + kNumXcd - 1) / kNumXcd * kNumXcd;
+  const long long grid = (long long)a.units_padded * n_jobs;
+  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gram_bf16_dual_kernel, dim3(unsigned(grid)), dim3(512), kDualLds, st, a);
   return hipGetLastError();
 }
 
