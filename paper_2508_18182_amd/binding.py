@@ -10,7 +10,7 @@ import os
 from typing import Optional, Sequence
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libadloco.so")
+_LIB_PATH = os.environ.get("ADLOCO_LIBRARY_PATH") or os.path.join(_PKG, "libadloco.so")
 
 ADLOCO_F32, ADLOCO_BF16 = 0, 1
 ADLOCO_ACCUMULATE = 0x1

@@ -19,16 +19,19 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Wno-unused-command-line-argument"]
 
 
-def build(verbose: bool = False, jobs: int = 8) -> str:
+def build(verbose: bool = False, jobs: int = 8, extra_flags=(), lib_path: str = LIB,
+          objdir_name: str = "_build") -> str:
+    """Compile every source with hipcc for gfx950 and link libadloco.so.  extra_flags / lib_path
+    serve one-off experimental builds (e.g. -DADLOCO_EXPERIMENT into another file)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(PKG, "_build")
+    objdir = os.path.join(PKG, objdir_name)
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.rsplit(".", 1)[0] + ".o")
         objs.append(obj)
-        cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c"]
+        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c"]
         if src.endswith(".cpp"):
             cmd += ["-x", "hip"]
         cmd += [os.path.join(CSRC, src), "-o", obj]
@@ -49,12 +52,12 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         print(r.stdout, file=sys.stderr)
         raise RuntimeError("link failed")
-    return LIB
+    return lib_path
 
 
 if __name__ == "__main__":

@@ -121,7 +121,7 @@ struct GramJob {
 std::vector<GramJob> make_gram_jobs(int nt);
 int gram_tile_edge(int dtype, int variant);
 hipError_t launch_gram_bf16_dual(const GramLaunch& g, const GramJob* jobs, int n_jobs,
-                                 hipStream_t st);
+                                 int variant, hipStream_t st);
 hipError_t launch_gram_bf16(const GramLaunch& g, int variant, hipStream_t st);
 hipError_t launch_gram_f32(const GramLaunch& g, hipStream_t st);
 int wgrad_tile_edge(int dtype);

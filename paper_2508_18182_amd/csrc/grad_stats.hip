@@ -155,7 +155,8 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   hipEvent_t ev = prof_begin(ctx, st);
   hipError_t e;
   if (dual)
-    e = launch_gram_bf16_dual(g, static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n, st);
+    e = launch_gram_bf16_dual(g, static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n,
+                              ctx->gram_variant, st);
   else if (dtype == ADLOCO_BF16)
     e = launch_gram_bf16(g, ctx->gram_variant, st);
   else
