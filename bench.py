@@ -39,6 +39,9 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--grad-provided", action="store_true",
                    help="caller supplies the gradient sum (skips the gradient-sum GEMM)")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run three plain 1 GiB device copies (untimed) so that a counter "
+                        "profile of this command holds a kernel of known traffic")
     p.add_argument("--only", default="all", choices=["all", "stats", "outer"],
                    help="time only one half (diagnostics; the JSON line says so)")
     return p.parse_args()
@@ -155,6 +158,14 @@ def main():
             A.adloco_check_merge(b_req, M)
             A.adloco_outer_step(ctx, theta, insts, mom, ocfg["lr"], ocfg["mu"], True)
             A.adloco_merge(ctx, insts, [float(b + k) for k, b in enumerate(b_req)])
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -56,6 +56,9 @@ struct adloco_ctx {
   int job_tab_nt = -1;         // number of row blocks the uploaded job table was built for
   int job_tab_n = 0;
   bool all_fast64 = false;     // every layer: aligned rows and widths that are multiples of 64
+  adloco::Scratch wgx_tab;     // tile table of the fast gradient-sum kernel
+  int wgx_slots = 0;           // tiles per XCD in that table (0: not built for this layer table)
+  bool all_fast = false;       // every layer without a provided gradient: aligned, widths % 8 == 0
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
   double* pinned = nullptr;    // 4 doubles of pinned host memory (norm-test read-back)
@@ -67,7 +70,7 @@ struct adloco_ctx {
   int profile = 0;
   // tuning
   int gram_variant = 1;        // 1: dual-tile kernel when eligible, 0: always the generic one
-  int wgrad_variant = 1;
+  int wgrad_variant = 2;       // 2: 256x256 fast kernel when eligible; 1/0: 128x128 kernel (LDS transpose reads / gathers)
   int stream_blocks_per_cu = 8;
   int stream_variant = 0;
 };
@@ -125,6 +128,9 @@ hipError_t launch_gram_bf16_dual(const GramLaunch& g, const GramJob* jobs, int n
 hipError_t launch_gram_bf16(const GramLaunch& g, int variant, hipStream_t st);
 hipError_t launch_gram_f32(const GramLaunch& g, hipStream_t st);
 int wgrad_tile_edge(int dtype);
+int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out);
+hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots, long long rows,
+                          int accumulate, int variant, hipStream_t st);
 hipError_t launch_wgrad(const LayerDev* layers, int n_layers, int n_blocks, long long rows,
                         int dtype, int accumulate, int variant, hipStream_t st);
 hipError_t launch_finalize_stats(const float* partials, int n_layers, int B, int n_pairs,

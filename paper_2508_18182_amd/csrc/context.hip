@@ -131,7 +131,7 @@ extern "C" int adloco_destroy(adloco_ctx* ctx) {
   (void)hipSetDevice(ctx->device);
   (void)hipDeviceSynchronize();
   Scratch* all[] = {&ctx->partials, &ctx->layer_tab, &ctx->red_f64, &ctx->sample_f64,
-                    &ctx->order_tab, &ctx->job_tab};
+                    &ctx->order_tab, &ctx->job_tab, &ctx->wgx_tab};
   for (Scratch* s : all)
     if (s->ptr) (void)hipFree(s->ptr);
   for (auto& r : ctx->prof) {

@@ -86,6 +86,20 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   bool f64 = need_inputs;
   for (const LayerDev& L : tab) f64 = f64 && L.fast && L.d_in % 64 == 0 && L.d_out % 64 == 0;
   ctx->all_fast64 = f64;
+  bool fast = need_inputs;
+  for (const LayerDev& L : tab) fast = fast && (L.provided || L.fast);
+  ctx->all_fast = fast;
+  ctx->wgx_slots = 0;
+  if (fast && dtype == ADLOCO_BF16 && wg > 0) {
+    std::vector<int4> tiles;
+    const int slots = make_wgrad_x_tiles(tab, tiles);
+    rc = ensure_scratch(ctx, ctx->wgx_tab, tiles.size() * sizeof(int4));
+    if (rc) return rc;
+    ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->wgx_tab.ptr, tiles.data(), tiles.size() * sizeof(int4),
+                                         hipMemcpyHostToDevice, st));
+    ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+    ctx->wgx_slots = slots;
+  }
   ctx->layer_tab_host = std::move(tab);
   ctx->order_host = std::move(order);
   ctx->wgrad_blocks = int(wg);
@@ -165,8 +179,13 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   if (e != hipSuccess)
     return fail(ctx, ADLOCO_EHIP, "grad_stats: Gram launch failed: %s", hipGetErrorString(e));
   ev = ctx->wgrad_blocks > 0 ? prof_begin(ctx, st) : nullptr;
-  e = launch_wgrad(g.layers, n_layers, ctx->wgrad_blocks, (long long)B * T, dtype, accumulate,
-                   ctx->wgrad_variant, st);
+  const long long rows = (long long)B * T;
+  if (dtype == ADLOCO_BF16 && ctx->wgrad_variant >= 2 && ctx->wgx_slots > 0 && rows % 32 == 0)
+    e = launch_wgrad_x(g.layers, ctx->wgx_tab.ptr, ctx->wgx_slots, rows, accumulate,
+                       ctx->wgrad_variant, st);
+  else
+    e = launch_wgrad(g.layers, n_layers, ctx->wgrad_blocks, rows, dtype, accumulate,
+                     ctx->wgrad_variant >= 2 ? 1 : ctx->wgrad_variant, st);
   prof_end(ctx, kProfWgrad, ev, st);
   if (e != hipSuccess)
     return fail(ctx, ADLOCO_EHIP, "grad_stats: gradient-sum launch failed: %s", hipGetErrorString(e));

@@ -3,6 +3,8 @@
 // A GEMM [d_out, d_in] with the contraction over all B*T token rows.  Both operands are stored
 // token-major (the contraction index is the slow one), so tiles are staged in LDS as they are
 // and handed to the MFMA through the LDS transpose read of gfx950.
+#include <algorithm>
+
 #include "common.h"
 
 namespace adloco {
@@ -191,6 +193,187 @@ __global__ __launch_bounds__(256, 2) void wgrad_bf16_kernel(WgradArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------
+// bf16 fast path: 256 (d_out) x 256 (d_in) output tile per workgroup of 8 waves (2 x 4, each
+// 128 x 64), used when every row is 16-byte aligned, widths are multiples of 8 and the number
+// of token rows is a multiple of 32.
+//   Staging: global -> LDS directly, four stages of 32 token rows x (256 + 256) columns; one
+//   wave instruction moves two token rows of one operand (2 x 512 contiguous bytes); the LDS
+//   blocks are padded so that the transpose reads of four consecutive rows fall into different
+//   banks.
+//   One barrier per 32-row chunk, between its two k-steps; loads run two chunks ahead.
+//   Tiles are dealt to the XCDs layer by layer (table built on the host): the tiles of one layer
+//   run next to each other on one XCD and stream the same columns out of that XCD's L2.
+//   Columns beyond d_out / d_in re-read the last valid 16-byte piece; those accumulators are
+//   never stored.
+// ---------------------------------------------------------------------------------------
+constexpr int kXt = 256;                          // tile edge
+constexpr int kXk = 32;                           // token rows per stage
+constexpr int kXrowB = kXt * 2;                   // bytes per staged row of one operand
+constexpr int kXblk = 2 * kXrowB + 64;            // one load instruction: rows j and j+16, + 64 B pad
+constexpr int kXop = 16 * kXblk;                  // 17 KiB
+constexpr int kXstage = 2 * kXop;                 // 34 KiB
+constexpr int kXstages = 4;
+constexpr int kXlds = kXstages * kXstage;         // 136 KiB
+
+struct WgradXArgs {
+  const LayerDev* layers;
+  const int4* tiles;      // [8][slots]: (layer, e0, c0, unused); layer < 0 = no tile
+  int slots;
+  long long rows;
+  int accumulate;
+};
+
+template <int N> __device__ __forceinline__ void wgx_wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | ((N >> 4) << 14));
+}
+
+// LDS offset of staged token row `row` (0..31) of one operand: load instruction j brings rows j
+// and j+16 into one 1 KiB block; blocks are 1088 bytes apart, so four consecutive rows start
+// 64 bytes apart modulo 256 and a transpose read (per 32 lanes: 4 rows x 2 x 32 bytes) touches
+// 256 distinct bytes.  Global addresses stay linear: 512 contiguous bytes per half wave.
+__device__ __forceinline__ int wgx_row_off(int row) { return (row & 15) * kXblk + (row >> 4) * kXrowB; }
+
+// MODE is 0 in the library (non-zero only in timing experiments built with ADLOCO_EXPERIMENT:
+// bit 0 drops the loads after the prologue, bit 1 the per-chunk wait and barrier).
+template <int MODE>
+__global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
+  const int4 tile = g.tiles[xcd * g.slots + slot];
+  if (tile.x < 0) return;
+  const LayerDev L = g.layers[tile.x];
+  const int e0 = tile.y, c0 = tile.z;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 2, wn = wave & 3;        // 2 x 4 waves; wave tile 128 (e) x 64 (c)
+
+  // ---- direct loads: instruction j = wave + 8*i (i = 0..3): operand j/16, rows j%16 (lanes 0-31)
+  // and j%16 + 16 (lanes 32-63), 16-byte piece lane%32
+  const unsigned short* src_base[4];
+  long long src_stride[4];
+  int lds_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int j = wave + 8 * i;
+    const int op = j >> 4;                        // 0: delta (d_out side), 1: a (d_in side)
+    const int row = (j & 15) + 16 * (lane >> 5);
+    const int piece = lane & 31;
+    const int d = op ? L.d_in : L.d_out;
+    int col = (op ? c0 : e0) + piece * 8;
+    col = col < d ? col : d - 8;
+    const unsigned short* base = reinterpret_cast<const unsigned short*>(op ? L.a : L.delta);
+    src_stride[i] = op ? L.a_stride : L.delta_stride;
+    src_base[i] = base + row * src_stride[i] + col;
+    lds_off[i] = op * kXop + (j & 15) * kXblk;
+  }
+  auto issue_loads = [&](long long c) {
+    unsigned char* stage = lds + (c % kXstages) * kXstage;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src_base[i] + c * kXk * src_stride[i]),
+          (__attribute__((address_space(3))) void*)(stage + lds_off[i]), 16, 0, 0);
+  };
+
+  // ---- fragments by LDS transpose reads.  Within a group of 16 lanes, lane s points at the 4
+  // columns 4*(s%4).. of token row kbase + s/4; the read hands lane i column i of the group's
+  // 16 at the four token rows.  Lane l ends up with column m0 + l%32, token rows
+  // ks*16 + (l/32)*8 + 0..7.
+  const int i16 = lane & 15;
+  const int krow = (lane >> 5) * 8 + (i16 >> 2);              // + ks*16 (+4 for the upper half)
+  const int ccol = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;    // column within a 32-wide block
+  typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+  auto frag = [&](const unsigned char* op_base, int m0, int ks) -> bf16x8 {
+    const int col = m0 + ccol;
+    const int r0 = ks * 16 + krow, r1 = r0 + 4;
+    const unsigned char* p0 = op_base + wgx_row_off(r0) + col * 2;
+    const unsigned char* p1 = op_base + wgx_row_off(r1) + col * 2;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p1));
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+  auto read_frags = [&](long long c, int ks, bf16x8 (&fa)[4], bf16x8 (&fb)[2]) {
+    const unsigned char* stage = lds + (c % kXstages) * kXstage;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) fa[m] = frag(stage, wm * 128 + m * 32, ks);
+#pragma unroll
+    for (int n = 0; n < 2; ++n) fb[n] = frag(stage + kXop, wn * 64 + n * 32, ks);
+  };
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[m][n][j] = 0.f;
+
+  auto mfma8 = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
+    // issue order: one MFMA, then one or two LDS reads of the next k-step (12 reads per 8 MFMAs)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+  };
+
+  const long long nk = g.rows / kXk;
+  issue_loads(0);
+  if (nk > 1) issue_loads(1);
+  if (nk > 2) issue_loads(2);
+  if (nk > 2) wgx_wait_vmcnt<8>(); else if (nk > 1) wgx_wait_vmcnt<4>(); else wgx_wait_vmcnt<0>();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  bf16x8 fa[2][4], fb[2][2];
+  read_frags(0, 0, fa[0], fb[0]);
+  for (long long c = 0; c < nk; ++c) {
+    read_frags(c, 1, fa[1], fb[1]);
+    mfma8(fa[0], fb[0]);
+    if (c + 1 < nk) {
+      // chunk c+1 has landed for me (chunk c+2 may still be in flight), then for everybody;
+      // every wave is done with chunk c-1, whose stage takes chunk c+3
+      if (!(MODE & 2)) {
+        if (c + 2 < nk) wgx_wait_vmcnt<4>(); else wgx_wait_vmcnt<0>();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      if (!(MODE & 1) && c + 3 < nk) issue_loads(c + 3);
+    }
+    read_frags(c + 1 < nk ? c + 1 : c, 0, fa[0], fb[0]);
+    mfma8(fa[1], fb[1]);
+  }
+
+  // accumulator element j of a 32x32 block: row (j/4)*8 + (lane/32)*4 + j%4, column lane%32
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+      const int col = c0 + wn * 64 + n * 32 + (lane & 31);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int row = e0 + wm * 128 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        if (row < L.d_out && col < L.d_in) {
+          float* dst = L.grad_sum + (size_t)row * L.d_in + col;
+          *dst = g.accumulate ? *dst + acc[m][n][j] : acc[m][n][j];
+        }
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // fp32 inputs: plain FMA path, 32x32 output tile, 2x2 entries per thread.
 // ---------------------------------------------------------------------------------------
 constexpr int kWtF = 32;
@@ -241,6 +424,55 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs g) {
 }
 
 int wgrad_tile_edge(int dtype) { return dtype == ADLOCO_BF16 ? kWt : kWtF; }
+
+// Tile table of the fast kernel: [8 XCDs][slots] entries (layer, e0, c0, 0).  Layers go to the
+// XCD with the fewest tiles so far (largest layers first), so every XCD holds whole layers.
+int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out) {
+  std::vector<int> idx;
+  std::vector<long long> cnt(layers.size(), 0);
+  for (size_t l = 0; l < layers.size(); ++l) {
+    if (layers[l].provided) continue;
+    cnt[l] = (long long)((layers[l].d_out + kXt - 1) / kXt) * ((layers[l].d_in + kXt - 1) / kXt);
+    idx.push_back(int(l));
+  }
+  std::stable_sort(idx.begin(), idx.end(), [&](int x, int y) { return cnt[x] > cnt[y]; });
+  std::vector<std::vector<int4>> per(kNumXcd);
+  for (int l : idx) {
+    int best = 0;
+    for (int x = 1; x < kNumXcd; ++x)
+      if (per[x].size() < per[best].size()) best = x;
+    const int te = (layers[l].d_out + kXt - 1) / kXt, tc = (layers[l].d_in + kXt - 1) / kXt;
+    for (int a = 0; a < te; ++a)
+      for (int b = 0; b < tc; ++b) per[best].push_back(int4{l, a * kXt, b * kXt, 0});
+  }
+  size_t slots = 0;
+  for (auto& v : per) slots = std::max(slots, v.size());
+  out.assign(size_t(kNumXcd) * slots, int4{-1, 0, 0, 0});
+  for (int x = 0; x < kNumXcd; ++x)
+    for (size_t i = 0; i < per[x].size(); ++i) out[x * slots + i] = per[x][i];
+  return int(slots);
+}
+
+hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots, long long rows,
+                          int accumulate, int variant, hipStream_t st) {
+  if (slots <= 0) return hipSuccess;
+  auto kern = wgrad_bf16_x_kernel<0>;
+#ifdef ADLOCO_EXPERIMENT
+  if (variant == 3) kern = wgrad_bf16_x_kernel<1>;
+  if (variant == 4) kern = wgrad_bf16_x_kernel<2>;
+  if (variant == 5) kern = wgrad_bf16_x_kernel<3>;
+#else
+  (void)variant;
+#endif
+  {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kXlds);
+    if (e != hipSuccess) return e;
+  }
+  WgradXArgs a{layers, static_cast<const int4*>(tiles), slots, rows, accumulate};
+  hipLaunchKernelGGL(kern, dim3(unsigned(slots * kNumXcd)), dim3(512), kXlds, st, a);
+  return hipGetLastError();
+}
 
 hipError_t launch_wgrad(const LayerDev* layers, int n_layers, int n_blocks, long long rows,
                         int dtype, int accumulate, int variant, hipStream_t st) {

@@ -85,6 +85,9 @@ def test_bf16_gpt2_block_mid(ctx, variant):
     (1, 1, [(8, 16)]),                                       # one token
     (4, 257, [(7, 5), (1, 1), (9, 130)]),                    # odd widths: 2-byte path
     (9, 40, [(128, 384)]),                                   # B not a multiple of the XCD count
+    (4, 64, [(8, 16), (264, 520), (256, 256)]),              # 256-tile gradient kernel: clamped edges
+    (2, 512, [(64, 320), (320, 64)]),                        # four T tiles, many k-chunks
+    (3, 384, [(128, 64)]),                                   # three T tiles: a single-pair job
 ])
 def test_bf16_ragged_and_edges(ctx, variant, B, T, shapes):
     layers = synth.custom_grad_stats_inputs(700 + B + T, shapes, B, T, "bf16", std_delta=0.05,
