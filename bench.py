@@ -37,6 +37,8 @@ def parse():
     p.add_argument("--wgrad-variant", type=int, default=None)
     p.add_argument("--stream-blocks-per-cu", type=int, default=None)
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--cpu-blocks", type=int, default=12,
+                   help="transformer blocks (of 12) the CPU oracle is timed on")
     p.add_argument("--grad-provided", action="store_true",
                    help="caller supplies the gradient sum (skips the gradient-sum GEMM)")
     p.add_argument("--calibrate-copy", action="store_true",
@@ -61,35 +63,53 @@ def gram_flops(shapes, B, T):
     return sym, full, executed
 
 
-def cpu_baseline(synth, orc, shapes, B, T, N, M):
-    """The oracle, as it stands, on a bounded sample of the same workload."""
-    import numpy as np
+def cpu_baseline(synth, orc, shapes, B, T, N, M, blocks):
+    """The oracle, as it stands, on a bounded sample of the same workload: `blocks` of the 12
+    transformer blocks (all samples), and the outer step + merge on N/4 parameters."""
     try:
         from threadpoolctl import threadpool_info
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    # sample: the 4 linears of one of the 12 blocks, all B samples; outer step + merge on N/8
-    layers = synth.grad_stats_inputs(2, linears=range(4), B=B, T=T)
-    t0 = time.perf_counter()
-    st = orc.grad_stats([(l["a"], l["delta"]) for l in layers], two_pass=False)
-    orc.norm_test(st["S1"], st["S2"], B, 0.3, B, 32)
-    t_block = time.perf_counter() - t0
-    n_s = N // 8
+    n_blocks = len(shapes) // 4
+    t_stats = 0.0
+    for b in range(blocks):
+        layers = synth.grad_stats_inputs(2, linears=range(4 * b, 4 * b + 4), B=B, T=T)
+        t0 = time.perf_counter()
+        st = orc.grad_stats([(l["a"], l["delta"]) for l in layers], two_pass=False)
+        orc.norm_test(st["S1"], st["S2"], B, 0.3, B, 32)
+        t_stats += time.perf_counter() - t0
+        del layers, st
+    n_s = N // 4
     theta, insts, mom = synth.outer_inputs(3, N=n_s, M=M)
     t0 = time.perf_counter()
     orc.outer_step(theta, insts, mom, 0.7, 0.9, True)
     orc.merge(insts, [32.0 + k for k in range(M)])
     t_outer = time.perf_counter() - t0
-    n_blocks = len(shapes) // 4
-    t_est = n_blocks * t_block + 8 * t_outer
+    t_est = t_stats * n_blocks / blocks + 4 * t_outer
     return dict(value=B * T / t_est, unit="tokens/s", cores=int(cores), kind="oracle",
-                sample=(f"1 of {n_blocks} blocks (4 linears, all {B} samples, T={T}) took "
-                        f"{t_block:.2f} s; outer step + merge on N/8 = {n_s} params took "
-                        f"{t_outer:.2f} s; step time extrapolated linearly to "
-                        f"{n_blocks} blocks and N params: {t_est:.1f} s"),
-                grad_stats_tokens_per_s=B * T / (n_blocks * t_block),
+                sample=(f"{blocks} of {n_blocks} blocks ({4 * blocks} linears, all {B} samples, "
+                        f"T={T}) took {t_stats:.2f} s; outer step + merge on N/4 = {n_s} params "
+                        f"took {t_outer:.2f} s; step time scaled linearly to {n_blocks} blocks "
+                        f"and N params: {t_est:.1f} s"),
+                grad_stats_tokens_per_s=B * T / (t_stats * n_blocks / blocks),
                 outer_merge_GBps=((4 * (M + 2) + 8 + 4 * (M + 1)) * n_s) / t_outer / 1e9)
+
+
+def measured_traffic():
+    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs of this command, scaled as stated there); {} when the file is absent."""
+    path = os.path.join(ROOT, "profiles", "bench_gpt2small_hbm_traffic.md")
+    out = {}
+    try:
+        with open(path) as f:
+            for ln in f:
+                parts = [p.strip() for p in ln.split("|")]
+                if len(parts) >= 5 and parts[1] in ("gram", "wgrad", "outer_step", "merge", "sqnorm"):
+                    out[parts[1]] = float(parts[2]) + float(parts[3])
+    except OSError:
+        pass
+    return out
 
 
 def main():
@@ -184,31 +204,56 @@ def main():
         ms, n = ctx.profile_read(k)
         kern[k] = dict(avg_ms=(ms / n) if n else None, launches=n)
 
+    # the same statistics with the gradient sum supplied by the caller (the training framework's
+    # own weight gradient): Gram kernel + reductions + norm test only
+    provided_ms = None
+    if args.only in ("all", "stats") and not args.grad_provided:
+        for l in layers:
+            l["provided"] = True
+        d_prov = A.binding.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
+
+        def stats_provided():
+            A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, per_sample, per_layer, acc, 0,
+                                descs=d_prov)
+            A.adloco_norm_test(ctx, None, acc, eta, B, 32, 2, 256, descs=d_prov)
+        for _ in range(2):
+            stats_provided()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            stats_provided()
+        torch.cuda.synchronize()
+        provided_ms = (time.perf_counter() - t1) / args.steps * 1e3
+        for k in ("gram", "finalize", "sqnorm"):
+            ctx.profile_read(k)
+
     sym, full, executed = gram_flops(shapes, B, T)
     wgrad_flops = sum(2 * B * T * di * do for _, di, do in shapes)
     outer_bytes = (4 * (M + 2) + 8) * N
     merge_bytes = 4 * (M + 1) * N
     sq_bytes = 4 * sum(di * do for _, di, do in shapes)
 
-    def roof(bound, work, ms, peak, unit, scale, **extra):
+    traffic = measured_traffic()
+
+    def roof(name, bound, work, ms, peak, unit, scale, **extra):
         if not ms:
             return None
         a = work / (ms * 1e-3) / scale
         return dict(bound=bound, achieved=a, peak=peak / scale, unit=unit, frac=a / (peak / scale),
-                    traffic=None, avg_kernel_ms=ms, **extra)
+                    traffic=traffic.get(name), avg_kernel_ms=ms, **extra)
 
-    r_gram = roof("mfma", sym, kern["gram"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
-                  kernel="gram_bf16_kernel", flops_algorithmic_symmetric=sym, flops_full=full,
+    r_gram = roof("gram", "mfma", sym, kern["gram"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
+                  kernel="gram_bf16_dual_kernel", flops_algorithmic_symmetric=sym, flops_full=full,
                   flops_executed=executed,
                   frac_executed=(executed / (kern["gram"]["avg_ms"] * 1e-3) / PEAK_BF16_MFMA)
                   if kern["gram"]["avg_ms"] else None)
-    r_wgrad = roof("mfma", wgrad_flops, kern["wgrad"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
-                   kernel="wgrad_bf16_kernel", flops_algorithmic=wgrad_flops)
-    r_outer = roof("hbm", outer_bytes, kern["outer_step"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+    r_wgrad = roof("wgrad", "mfma", wgrad_flops, kern["wgrad"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
+                   kernel="wgrad_bf16_x_kernel", flops_algorithmic=wgrad_flops)
+    r_outer = roof("outer_step", "hbm", outer_bytes, kern["outer_step"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                    kernel="outer_step_vec_kernel", bytes_algorithmic=outer_bytes)
-    r_merge = roof("hbm", merge_bytes, kern["merge"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+    r_merge = roof("merge", "hbm", merge_bytes, kern["merge"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                    kernel="merge_vec_kernel", bytes_algorithmic=merge_bytes)
-    r_sq = roof("hbm", sq_bytes, kern["sqnorm"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+    r_sq = roof("sqnorm", "hbm", sq_bytes, kern["sqnorm"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                 kernel="sqnorm_partial_kernel", bytes_algorithmic=sq_bytes)
     roofs = dict(gram=r_gram, wgrad=r_wgrad, outer_step=r_outer, merge=r_merge, sqnorm=r_sq)
     timed = {k: v["avg_ms"] for k, v in kern.items() if v["avg_ms"]}
@@ -233,13 +278,14 @@ def main():
                     "gram": r_gram, "wgrad": r_wgrad, "outer_step": r_outer, "merge": r_merge,
                     "sqnorm": r_sq},
         "grad_stats_tokens_per_s": (B * T / (stats_ms * 1e-3)) if stats_ms else None,
+        "grad_stats_tokens_per_s_gradient_supplied": (B * T / (provided_ms * 1e-3)) if provided_ms else None,
         "outer_step_GBps": r_outer["achieved"] if r_outer else None,
         "merge_GBps": r_merge["achieved"] if r_merge else None,
         "norm_test": {k: last.get(k) for k in ("stat", "b_req", "test_passed", "accumulate")},
     }
     if not args.no_cpu_baseline:
         from oracle import adloco_oracle as orc
-        out["cpu_baseline"] = cpu_baseline(synth, orc, shapes, B, T, N, M)
+        out["cpu_baseline"] = cpu_baseline(synth, orc, shapes, B, T, N, M, max(1, min(12, args.cpu_blocks)))
     else:
         out["cpu_baseline"] = None
     ctx.close()
