@@ -58,6 +58,9 @@ struct adloco_ctx {
   bool all_fast64 = false;     // every layer: aligned rows and widths that are multiples of 64
   adloco::Scratch wgx_tab;     // tile table of the fast gradient-sum kernel
   int wgx_slots = 0;           // tiles per XCD in that table (0: not built for this layer table)
+  adloco::Scratch wgx_split;   // split tiles (layer, e0, c0, pieces) for the reduction
+  adloco::Scratch wgx_part;    // partial tiles of the split contraction, 256 KiB each
+  int wgx_n_split = 0;
   bool all_fast = false;       // every layer without a provided gradient: aligned, widths % 8 == 0
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
@@ -128,8 +131,10 @@ hipError_t launch_gram_bf16_dual(const GramLaunch& g, const GramJob* jobs, int n
 hipError_t launch_gram_bf16(const GramLaunch& g, int variant, hipStream_t st);
 hipError_t launch_gram_f32(const GramLaunch& g, hipStream_t st);
 int wgrad_tile_edge(int dtype);
-int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out);
-hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots, long long rows,
+int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out,
+                       std::vector<int4>& split_tiles, int& n_pieces);
+hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots,
+                          const void* split_tiles, int n_split, float* partials, long long rows,
                           int accumulate, int variant, hipStream_t st);
 hipError_t launch_wgrad(const LayerDev* layers, int n_layers, int n_blocks, long long rows,
                         int dtype, int accumulate, int variant, hipStream_t st);

@@ -131,7 +131,8 @@ extern "C" int adloco_destroy(adloco_ctx* ctx) {
   (void)hipSetDevice(ctx->device);
   (void)hipDeviceSynchronize();
   Scratch* all[] = {&ctx->partials, &ctx->layer_tab, &ctx->red_f64, &ctx->sample_f64,
-                    &ctx->order_tab, &ctx->job_tab, &ctx->wgx_tab};
+                    &ctx->order_tab, &ctx->job_tab, &ctx->wgx_tab,
+                    &ctx->wgx_split, &ctx->wgx_part};
   for (Scratch* s : all)
     if (s->ptr) (void)hipFree(s->ptr);
   for (auto& r : ctx->prof) {

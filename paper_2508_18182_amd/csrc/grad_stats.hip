@@ -91,14 +91,23 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   ctx->all_fast = fast;
   ctx->wgx_slots = 0;
   if (fast && dtype == ADLOCO_BF16 && wg > 0) {
-    std::vector<int4> tiles;
-    const int slots = make_wgrad_x_tiles(tab, tiles);
+    std::vector<int4> tiles, split;
+    int n_pieces = 0;
+    const int slots = make_wgrad_x_tiles(tab, tiles, split, n_pieces);
     rc = ensure_scratch(ctx, ctx->wgx_tab, tiles.size() * sizeof(int4));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->wgx_split, std::max<size_t>(split.size(), 1) * sizeof(int4));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->wgx_part, std::max<size_t>(n_pieces, 1) * 256 * 256 * sizeof(float));
     if (rc) return rc;
     ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->wgx_tab.ptr, tiles.data(), tiles.size() * sizeof(int4),
                                          hipMemcpyHostToDevice, st));
+    if (!split.empty())
+      ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->wgx_split.ptr, split.data(),
+                                           split.size() * sizeof(int4), hipMemcpyHostToDevice, st));
     ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
     ctx->wgx_slots = slots;
+    ctx->wgx_n_split = int(split.size());
   }
   ctx->layer_tab_host = std::move(tab);
   ctx->order_host = std::move(order);
@@ -181,7 +190,8 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   ev = ctx->wgrad_blocks > 0 ? prof_begin(ctx, st) : nullptr;
   const long long rows = (long long)B * T;
   if (dtype == ADLOCO_BF16 && ctx->wgrad_variant >= 2 && ctx->wgx_slots > 0 && rows % 32 == 0)
-    e = launch_wgrad_x(g.layers, ctx->wgx_tab.ptr, ctx->wgx_slots, rows, accumulate,
+    e = launch_wgrad_x(g.layers, ctx->wgx_tab.ptr, ctx->wgx_slots, ctx->wgx_split.ptr,
+                       ctx->wgx_n_split, static_cast<float*>(ctx->wgx_part.ptr), rows, accumulate,
                        ctx->wgrad_variant, st);
   else
     e = launch_wgrad(g.layers, n_layers, ctx->wgrad_blocks, rows, dtype, accumulate,

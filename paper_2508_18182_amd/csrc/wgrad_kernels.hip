@@ -217,7 +217,11 @@ constexpr int kXlds = kXstages * kXstage;         // 136 KiB
 
 struct WgradXArgs {
   const LayerDev* layers;
-  const int4* tiles;      // [8][slots]: (layer, e0, c0, unused); layer < 0 = no tile
+  const int4* tiles;      // [8][slots]: (layer, e0, c0, split); layer < 0 = no tile.
+                          // split = 0: whole contraction, result goes to grad_sum;
+                          // else (S << 24) | (piece << 16) | slot: piece of S equal parts of
+                          // the contraction, result goes to partial tile `slot` of `partials`
+  float* partials;        // [pieces][256][256] fp32
   int slots;
   long long rows;
   int accumulate;
@@ -243,9 +247,14 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   if (tile.x < 0) return;
   const LayerDev L = g.layers[tile.x];
   const int e0 = tile.y, c0 = tile.z;
+  const int split_s = (tile.w >> 24) & 0xff, split_p = (tile.w >> 16) & 0xff, split_id = tile.w & 0xffff;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 2, wn = wave & 3;        // 2 x 4 waves; wave tile 128 (e) x 64 (c)
+  // chunk range of this workgroup: everything, or piece split_p of split_s equal parts
+  const long long nk_all = g.rows / kXk;
+  const long long ck0 = split_s ? nk_all * split_p / split_s : 0;
+  const long long nk = (split_s ? nk_all * (split_p + 1) / split_s : nk_all) - ck0;
 
   // ---- direct loads: instruction j = wave + 8*i (i = 0..3): operand j/16, rows j%16 (lanes 0-31)
   // and j%16 + 16 (lanes 32-63), 16-byte piece lane%32
@@ -263,7 +272,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
     col = col < d ? col : d - 8;
     const unsigned short* base = reinterpret_cast<const unsigned short*>(op ? L.a : L.delta);
     src_stride[i] = op ? L.a_stride : L.delta_stride;
-    src_base[i] = base + row * src_stride[i] + col;
+    src_base[i] = base + (ck0 * kXk + row) * src_stride[i] + col;
     lds_off[i] = op * kXop + (j & 15) * kXblk;
   }
   auto issue_loads = [&](long long c) {
@@ -328,8 +337,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
     }
   };
 
-  const long long nk = g.rows / kXk;
-  issue_loads(0);
+  if (nk > 0) issue_loads(0);
   if (nk > 1) issue_loads(1);
   if (nk > 2) issue_loads(2);
   if (nk > 2) wgx_wait_vmcnt<8>(); else if (nk > 1) wgx_wait_vmcnt<4>(); else wgx_wait_vmcnt<0>();
@@ -357,20 +365,44 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   }
 
   // accumulator element j of a 32x32 block: row (j/4)*8 + (lane/32)*4 + j%4, column lane%32
+  float* part = split_s ? g.partials + (size_t)split_id * (kXt * kXt) : nullptr;
 #pragma unroll
   for (int m = 0; m < 4; ++m)
 #pragma unroll
     for (int n = 0; n < 2; ++n) {
-      const int col = c0 + wn * 64 + n * 32 + (lane & 31);
+      const int tc = wn * 64 + n * 32 + (lane & 31);
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const int row = e0 + wm * 128 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
-        if (row < L.d_out && col < L.d_in) {
-          float* dst = L.grad_sum + (size_t)row * L.d_in + col;
+        const int tr = wm * 128 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        if (split_s) {
+          part[tr * kXt + tc] = acc[m][n][j];
+        } else if (e0 + tr < L.d_out && c0 + tc < L.d_in) {
+          float* dst = L.grad_sum + (size_t)(e0 + tr) * L.d_in + c0 + tc;
           *dst = g.accumulate ? *dst + acc[m][n][j] : acc[m][n][j];
         }
       }
     }
+}
+
+// Sums the partial tiles of a split contraction in piece order (fixed order: repeatable) and
+// adds them to / stores them in grad_sum.  One workgroup per 16 rows of one split tile.
+struct WgradSplitTile { int layer, e0, c0, w; };   // w = (pieces << 16) | first partial tile
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const LayerDev* layers,
+                                                           const WgradSplitTile* tiles,
+                                                           const float* partials, int accumulate) {
+  const int t = blockIdx.x / 16, r0 = (blockIdx.x % 16) * 16;
+  const WgradSplitTile S = tiles[t];
+  const LayerDev L = layers[S.layer];
+  const int pieces = S.w >> 16;
+  const float* base = partials + (size_t)(S.w & 0xffff) * (kXt * kXt);
+  for (int r = r0; r < r0 + 16; ++r) {
+    const int row = S.e0 + r, col = S.c0 + threadIdx.x;
+    if (row >= L.d_out || col >= L.d_in) continue;
+    float v = 0.f;
+    for (int p = 0; p < pieces; ++p) v += base[(size_t)p * (kXt * kXt) + r * kXt + threadIdx.x];
+    float* dst = L.grad_sum + (size_t)row * L.d_in + col;
+    *dst = accumulate ? *dst + v : v;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -425,9 +457,14 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs g) {
 
 int wgrad_tile_edge(int dtype) { return dtype == ADLOCO_BF16 ? kWt : kWtF; }
 
-// Tile table of the fast kernel: [8 XCDs][slots] entries (layer, e0, c0, 0).  Layers go to the
-// XCD with the fewest tiles so far (largest layers first), so every XCD holds whole layers.
-int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out) {
+// Tile table of the fast kernel: [8 XCDs][slots] entries (layer, e0, c0, split).  Layers go to
+// the XCD with the fewest tiles so far (largest layers first), so every XCD holds whole layers.
+// All tiles cost the same, so an XCD's 32 CUs work in rounds; the tiles of an incomplete last
+// round are split along the contraction into as many pieces as fill the round, written to
+// partial tiles and summed afterwards by wgrad_reduce_kernel.
+int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out,
+                       std::vector<int4>& split_tiles, int& n_pieces) {
+  constexpr int kCuPerXcd = kNumCu / kNumXcd;
   std::vector<int> idx;
   std::vector<long long> cnt(layers.size(), 0);
   for (size_t l = 0; l < layers.size(); ++l) {
@@ -445,15 +482,38 @@ int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& o
     for (int a = 0; a < te; ++a)
       for (int b = 0; b < tc; ++b) per[best].push_back(int4{l, a * kXt, b * kXt, 0});
   }
+  split_tiles.clear();
+  n_pieces = 0;
+  std::vector<std::vector<int4>> fin(kNumXcd);
+  for (int x = 0; x < kNumXcd; ++x) {
+    const int n = int(per[x].size());
+    const int full = n / kCuPerXcd * kCuPerXcd, left = n - full;
+    const int S = left > 0 ? kCuPerXcd / left : 1;
+    for (int i = 0; i < full; ++i) fin[x].push_back(per[x][i]);
+    for (int i = full; i < n; ++i) {
+      if (S < 2 || n_pieces + S > 0xffff) {
+        fin[x].push_back(per[x][i]);
+        continue;
+      }
+      split_tiles.push_back(int4{per[x][i].x, per[x][i].y, per[x][i].z, (S << 16) | n_pieces});
+      for (int p = 0; p < S; ++p) {
+        int4 e = per[x][i];
+        e.w = (S << 24) | (p << 16) | (n_pieces + p);
+        fin[x].push_back(e);
+      }
+      n_pieces += S;
+    }
+  }
   size_t slots = 0;
-  for (auto& v : per) slots = std::max(slots, v.size());
+  for (auto& v : fin) slots = std::max(slots, v.size());
   out.assign(size_t(kNumXcd) * slots, int4{-1, 0, 0, 0});
   for (int x = 0; x < kNumXcd; ++x)
-    for (size_t i = 0; i < per[x].size(); ++i) out[x * slots + i] = per[x][i];
+    for (size_t i = 0; i < fin[x].size(); ++i) out[x * slots + i] = fin[x][i];
   return int(slots);
 }
 
-hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots, long long rows,
+hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots,
+                          const void* split_tiles, int n_split, float* partials, long long rows,
                           int accumulate, int variant, hipStream_t st) {
   if (slots <= 0) return hipSuccess;
   auto kern = wgrad_bf16_x_kernel<0>;
@@ -469,8 +529,11 @@ hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots, 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kXlds);
     if (e != hipSuccess) return e;
   }
-  WgradXArgs a{layers, static_cast<const int4*>(tiles), slots, rows, accumulate};
+  WgradXArgs a{layers, static_cast<const int4*>(tiles), partials, slots, rows, accumulate};
   hipLaunchKernelGGL(kern, dim3(unsigned(slots * kNumXcd)), dim3(512), kXlds, st, a);
+  if (n_split > 0)
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(unsigned(n_split * 16)), dim3(256), 0, st, layers,
+                       static_cast<const WgradSplitTile*>(split_tiles), partials, accumulate);
   return hipGetLastError();
 }
 
