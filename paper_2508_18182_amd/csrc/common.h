@@ -34,6 +34,22 @@ struct LayerDev {
   int sq_blk_start;        // first workgroup of this layer in the squared-norm launch
 };
 
+// One wave-wide direct load global -> LDS: lane l's 16 bytes at `src` land at LDS byte address
+// `lds_addr` + 16*l (`lds_addr` is wave-uniform and travels in M0).  Written as inline assembly
+// on purpose: the compiler orders the builtin form against every later LDS read with a full
+// `s_waitcnt vmcnt(0)`, which would expose the whole memory latency in each pipeline step.  The
+// caller therefore owns the ordering: its own s_waitcnt vmcnt(N) + workgroup barrier before any
+// wave reads the bytes, and vmcnt(0) before compiler-visible memory traffic that must see them.
+__device__ __forceinline__ void direct_load_lds16(const void* src, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(src), "s"(lds_addr) : "m0");
+}
+// LDS byte address of a pointer into the workgroup's dynamic shared memory, as a scalar.
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return __builtin_amdgcn_readfirstlane(
+      (unsigned)(size_t)(const __attribute__((address_space(3))) unsigned char*)p);
+}
+
 struct Scratch {
   void* ptr = nullptr;
   size_t bytes = 0;

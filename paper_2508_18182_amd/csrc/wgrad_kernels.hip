@@ -279,9 +279,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
     unsigned char* stage = lds + (c % kXstages) * kXstage;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src_base[i] + c * kXk * src_stride[i]),
-          (__attribute__((address_space(3))) void*)(stage + lds_off[i]), 16, 0, 0);
+      direct_load_lds16(src_base[i] + c * kXk * src_stride[i], lds_address(stage + lds_off[i]));
   };
 
   // ---- fragments by LDS transpose reads.  Within a group of 16 lanes, lane s points at the 4
@@ -304,10 +302,12 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   };
   auto read_frags = [&](long long c, int ks, bf16x8 (&fa)[4], bf16x8 (&fb)[2]) {
     const unsigned char* stage = lds + (c % kXstages) * kXstage;
+    // in the order the MFMAs need them
+    fa[0] = frag(stage, wm * 128, ks);
+    fb[0] = frag(stage + kXop, wn * 64, ks);
+    fb[1] = frag(stage + kXop, wn * 64 + 32, ks);
 #pragma unroll
-    for (int m = 0; m < 4; ++m) fa[m] = frag(stage, wm * 128 + m * 32, ks);
-#pragma unroll
-    for (int n = 0; n < 2; ++n) fb[n] = frag(stage + kXop, wn * 64 + n * 32, ks);
+    for (int m = 1; m < 4; ++m) fa[m] = frag(stage, wm * 128 + m * 32, ks);
   };
 
   f32x16 acc[4][2];
@@ -324,17 +324,14 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
 #pragma unroll
       for (int n = 0; n < 2; ++n)
         acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
-    // issue order: one MFMA, then one or two LDS reads of the next k-step (12 reads per 8 MFMAs)
+    // issue order: the 12 LDS reads of the next k-step go out two at a time behind the first
+    // six MFMAs, so that the last of them has two MFMAs to land before the next k-step starts
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 6; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
   };
 
   if (nk > 0) issue_loads(0);
