@@ -90,7 +90,7 @@ struct adloco_ctx {
   // tuning
   int gram_variant = 1;        // 1: dual-tile kernel when eligible, 0: always the generic one
   int wgrad_variant = 2;       // 2: 256x256 fast kernel when eligible; 1/0: 128x128 kernel (LDS transpose reads / gathers)
-  int stream_blocks_per_cu = 8;
+  int stream_blocks_per_cu = 0;   // resident workgroups per CU of the streaming kernels; 0: automatic
   int stream_variant = 0;
 };
 

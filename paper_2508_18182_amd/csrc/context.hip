@@ -157,7 +157,7 @@ extern "C" int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value) {
   if (n == "gram_variant") ctx->gram_variant = value;
   else if (n == "wgrad_variant") ctx->wgrad_variant = value;
   else if (n == "stream_blocks_per_cu") {
-    if (value < 1 || value > 64) return fail(ctx, ADLOCO_EINVAL, "stream_blocks_per_cu out of range");
+    if (value < 0 || value > 64) return fail(ctx, ADLOCO_EINVAL, "stream_blocks_per_cu out of range");
     ctx->stream_blocks_per_cu = value;
   } else if (n == "stream_variant") ctx->stream_variant = value;
   else if (n == "profile") ctx->profile = value ? 1 : 0;
