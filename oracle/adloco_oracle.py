@@ -17,7 +17,9 @@ a_i [T, d_in] and output gradients delta_i [T, d_out] has g_i = delta_i^T a_i.
 
 Pins (tests/test_oracle_pins.py): hand closed forms for T = 1, 2; orthonormal / constant
 token rows; permutation and rotation invariance; element-by-element brute force; torch
-autograd of a bias-free linear layer; numpy's var(ddof=1) over the stacked per-sample
+autograd of a bias-free linear layer, and of a linear bias, a LayerNorm gain and bias and an
+embedding table for the vector and table blocks (plus their one-token / all-distinct /
+all-equal-id closed forms); numpy's var(ddof=1) over the stacked per-sample
 gradients; iid-noise expectation B/eta^2; LocalSGD averaging (Section 3.1) and
 torch.optim.SGD(nesterov=True) for the outer step; convexity / identity cases for the
 merge; Algorithm 1's branches enumerated by hand.
@@ -61,10 +63,61 @@ def per_sample_gradient(a_i, delta_i) -> np.ndarray:
     return delta_i.T @ a_i
 
 
-def grad_stats(layers, two_pass: bool = True) -> dict:
-    """Statistics of the per-sample gradients of a list of linear layers.
+def per_sample_gradient_rowsum(x_i, delta_i) -> np.ndarray:
+    """Per-sample gradient of a parameter vector p [d] that enters the layer element-wise,
+    y_t = p * x_t (+ ...): g_i = sum_t delta_{i,t} * x_{i,t}, an explicit [d] fp64 vector.
+    x_i = None stands for x = 1, the bias of a linear or normalisation layer (g_i =
+    sum_t delta_{i,t}); otherwise x_i is the normalised input of a normalisation layer and p
+    its gain.  These are further blocks of the grad f(x_k; xi_i) that eq. 1 averages."""
+    delta_i = widen(delta_i)
+    if x_i is None:
+        return delta_i.sum(axis=0)
+    x_i = widen(x_i)
+    assert x_i.shape == delta_i.shape
+    return (delta_i * x_i).sum(axis=0)
 
-    layers: list of (a [B,T,d_in], delta [B,T,d_out]) sharing B and T.
+
+def per_sample_gradient_embedding(ids_i, delta_i, rows) -> np.ndarray:
+    """Per-sample gradient of an embedding table E [V, d] (y_t = E[id_t]): row v of g_i is the
+    sum of delta_{i,t} over the tokens with id_t = v.  Returned explicitly for the table rows
+    listed in `rows` (sorted ids; every other row of g_i is zero): [len(rows), d] fp64."""
+    delta_i = widen(delta_i)
+    ids_i = np.asarray(ids_i)
+    g = np.zeros((len(rows), delta_i.shape[1]), dtype=np.float64)
+    pos = np.searchsorted(rows, ids_i)
+    assert np.all(rows[pos] == ids_i)
+    for t in range(delta_i.shape[0]):        # plain loop: one token adds one row
+        g[pos[t]] += delta_i[t]
+    return g
+
+
+def _layer_kind(entry):
+    """(a, delta) is a linear layer; ("rowsum", x | None, delta) a bias / gain vector;
+    ("embed", ids, delta) an embedding table."""
+    if isinstance(entry[0], str):
+        return entry[0]
+    return "linear"
+
+
+def _entry_sample_gradient(entry, i, rows=None):
+    kind = _layer_kind(entry)
+    if kind == "linear":
+        return per_sample_gradient(np.asarray(entry[0])[i], np.asarray(entry[1])[i])
+    if kind == "rowsum":
+        x = None if entry[1] is None else np.asarray(entry[1])[i]
+        return per_sample_gradient_rowsum(x, np.asarray(entry[2])[i])
+    if kind == "embed":
+        return per_sample_gradient_embedding(np.asarray(entry[1])[i], np.asarray(entry[2])[i], rows)
+    raise ValueError(kind)
+
+
+def grad_stats(layers, two_pass: bool = True) -> dict:
+    """Statistics of the per-sample gradients of a list of parameter blocks.
+
+    layers: list of (a [B,T,d_in], delta [B,T,d_out]) for linear weights, ("rowsum", x | None,
+    delta [B,T,d]) for bias / gain vectors, ("embed", ids [B,T] int, delta [B,T,d]) for
+    embedding tables, all sharing B and T.  For an embedding table G holds only the rows whose
+    id occurs in the batch (`embed_rows[l]`, sorted); all other rows are zero.
     Returns
       n_layer_sample [L,B]  ||g_i^l||_F^2
       n_sample       [B]    ||g_i||^2 = sum_l ||g_i^l||^2   (g_i = concatenation over layers)
@@ -75,30 +128,32 @@ def grad_stats(layers, two_pass: bool = True) -> dict:
       V                     sum_i ||g_i - g_k||^2, by a second explicit pass (two_pass only)
     """
     L = len(layers)
-    B = int(np.asarray(layers[0][0]).shape[0])
+    B = int(np.asarray(layers[0][-1]).shape[0])
     n_ls = np.zeros((L, B), dtype=np.float64)
     G = []
-    for l, (a, delta) in enumerate(layers):
-        a = np.asarray(a)
-        delta = np.asarray(delta)
-        assert a.shape[0] == B and delta.shape[0] == B and a.shape[1] == delta.shape[1]
-        Gl = np.zeros((delta.shape[2], a.shape[2]), dtype=np.float64)
+    embed_rows = {}
+    for l, entry in enumerate(layers):
+        assert np.asarray(entry[-1]).shape[0] == B
+        rows = None
+        if _layer_kind(entry) == "embed":
+            rows = embed_rows[l] = np.unique(np.asarray(entry[1]))
+        Gl = None
         for i in range(B):
-            g = per_sample_gradient(a[i], delta[i])
+            g = _entry_sample_gradient(entry, i, rows)
             n_ls[l, i] = np.sum(g * g)
-            Gl += g
+            Gl = g.copy() if Gl is None else Gl + g
         G.append(Gl)
     n_s = n_ls.sum(axis=0)
     S1 = float(n_s.sum())
     S2 = float(sum(np.sum(Gl * Gl) for Gl in G))
-    out = dict(n_layer_sample=n_ls, n_sample=n_s, S1=S1, G=G, S2=S2, B=B,
+    out = dict(n_layer_sample=n_ls, n_sample=n_s, S1=S1, G=G, S2=S2, B=B, embed_rows=embed_rows,
                batch_grad_sqnorm=S2 / (B * B) if B > 0 else float("nan"))
     if two_pass:
         V = 0.0
-        for l, (a, delta) in enumerate(layers):
+        for l, entry in enumerate(layers):
             gbar = G[l] / B
             for i in range(B):
-                dev = per_sample_gradient(np.asarray(a)[i], np.asarray(delta)[i]) - gbar
+                dev = _entry_sample_gradient(entry, i, embed_rows.get(l)) - gbar
                 V += float(np.sum(dev * dev))
         out["V"] = V
     return out
@@ -111,9 +166,14 @@ def concat_micro_batches(micro_batches):
     L = len(micro_batches[0])
     out = []
     for l in range(L):
-        a = np.concatenate([np.asarray(mb[l][0]) for mb in micro_batches], axis=0)
-        d = np.concatenate([np.asarray(mb[l][1]) for mb in micro_batches], axis=0)
-        out.append((a, d))
+        first = micro_batches[0][l]
+        parts = []
+        for j in range(len(first)):
+            if isinstance(first[j], str) or first[j] is None:
+                parts.append(first[j])
+            else:
+                parts.append(np.concatenate([np.asarray(mb[l][j]) for mb in micro_batches], axis=0))
+        out.append(tuple(parts))
     return out
 
 

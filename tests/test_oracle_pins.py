@@ -158,6 +158,97 @@ def test_autograd_linear_layer():
     assert st["S2"] == pytest.approx(float((tot ** 2).sum()), rel=1e-12)
 
 
+def test_vector_table_hand_cases():
+    # tests/golden/vector_table_hand_cases.txt: bias, gain and embedding blocks by hand
+    n = 0
+    for ln in _lines("vector_table_hand_cases.txt"):
+        lhs, want = ln.split("->")
+        head, x, d = lhs.split(";")
+        kind, T, dim = head.split()
+        T, dim = int(T), int(dim)
+        delta = np.array([float(v) for v in d.split(",")], dtype=np.float32).reshape(1, T, dim)
+        if kind == "bias":
+            entry = ("rowsum", None, delta)
+        elif kind == "gain":
+            entry = ("rowsum", np.array([float(v) for v in x.split(",")], dtype=np.float32).reshape(1, T, dim), delta)
+        else:
+            entry = ("embed", np.array(_ints(x), dtype=np.int32).reshape(1, T), delta)
+        st = orc.grad_stats([entry])
+        assert st["n_sample"][0] == pytest.approx(float(want), abs=1e-12)
+        n += 1
+    assert n >= 7
+
+
+def test_autograd_bias_gain_embedding():
+    # library route: per-sample gradients of a linear bias, a LayerNorm gain and bias and an
+    # embedding table by torch.autograd, with loss sum <delta, y> per sample
+    import torch
+    r = _rng(61)
+    B, T, di, do, V = 3, 6, 5, 4, 7
+    a = r.standard_normal((B, T, di))
+    d_lin = r.standard_normal((B, T, do))
+    x = r.standard_normal((B, T, do))
+    d_ln = r.standard_normal((B, T, do))
+    ids = r.integers(0, V, size=(B, T))
+    d_emb = r.standard_normal((B, T, do))
+    lin = torch.nn.Linear(di, do, bias=True).double()
+    ln = torch.nn.LayerNorm(do).double()
+    with torch.no_grad():
+        ln.weight.copy_(torch.from_numpy(r.standard_normal(do)))
+        ln.bias.copy_(torch.from_numpy(r.standard_normal(do)))
+    emb = torch.nn.Embedding(V, do).double()
+    xhat = torch.nn.functional.layer_norm(torch.from_numpy(x), (do,)).numpy()   # no affine part
+    entries = [(a, d_lin), ("rowsum", None, d_lin), ("rowsum", xhat, d_ln), ("rowsum", None, d_ln),
+               ("embed", ids, d_emb)]
+    st = orc.grad_stats(entries)
+    params = [lin.weight, lin.bias, ln.weight, ln.bias, emb.weight]
+    tot = [torch.zeros_like(p) for p in params]
+    for i in range(B):
+        loss = (torch.from_numpy(d_lin[i]) * lin(torch.from_numpy(a[i]))).sum() \
+            + (torch.from_numpy(d_ln[i]) * ln(torch.from_numpy(x[i]))).sum() \
+            + (torch.from_numpy(d_emb[i]) * emb(torch.from_numpy(ids[i]))).sum()
+        grads = torch.autograd.grad(loss, params)
+        for l, g in enumerate(grads):
+            assert st["n_layer_sample"][l, i] == pytest.approx(float((g ** 2).sum()), rel=1e-12)
+            tot[l] += g
+    for l in range(4):
+        np.testing.assert_allclose(st["G"][l], tot[l].detach().numpy(), rtol=1e-12, atol=1e-13)
+    rows = st["embed_rows"][4]
+    dense = np.zeros((V, do))
+    dense[rows] = st["G"][4]
+    np.testing.assert_allclose(dense, tot[4].detach().numpy(), rtol=1e-12, atol=1e-13)
+    assert st["S2"] == pytest.approx(sum(float((t ** 2).sum()) for t in tot), rel=1e-12)
+
+
+def test_vector_table_closed_forms_and_invariance():
+    r = _rng(62)
+    B, T, d = 4, 9, 6
+    delta = r.standard_normal((B, T, d))
+    x = r.standard_normal((B, T, d))
+    # one-token samples: ||delta * x||^2
+    st1 = orc.grad_stats([("rowsum", x[:, :1], delta[:, :1])])
+    np.testing.assert_allclose(st1["n_sample"], ((delta[:, 0] * x[:, 0]) ** 2).sum(axis=1), rtol=1e-13)
+    # embedding: distinct ids -> sum_t ||delta_t||^2 ; equal ids -> ||sum_t delta_t||^2
+    ids_distinct = np.stack([r.permutation(50)[:T] for _ in range(B)])
+    st2 = orc.grad_stats([("embed", ids_distinct, delta)])
+    np.testing.assert_allclose(st2["n_sample"], (delta ** 2).sum(axis=(1, 2)), rtol=1e-13)
+    st3 = orc.grad_stats([("embed", np.full((B, T), 3), delta)])
+    np.testing.assert_allclose(st3["n_sample"], (delta.sum(axis=1) ** 2).sum(axis=1), rtol=1e-13)
+    # an embedding whose ids are all equal is a bias: same norms, same gradient sum
+    stb = orc.grad_stats([("rowsum", None, delta)])
+    np.testing.assert_allclose(st3["n_sample"], stb["n_sample"], rtol=1e-13)
+    np.testing.assert_allclose(st3["G"][0][0], stb["G"][0], rtol=1e-13)
+    # token order inside a sample does not matter
+    ids = r.integers(0, 5, size=(B, T))
+    perm = r.permutation(T)
+    base = orc.grad_stats([("rowsum", x, delta), ("embed", ids, delta)])
+    shuf = orc.grad_stats([("rowsum", x[:, perm], delta[:, perm]), ("embed", ids[:, perm], delta[:, perm])])
+    np.testing.assert_allclose(base["n_layer_sample"], shuf["n_layer_sample"], rtol=1e-12)
+    # two-pass variance identity over a mixed list of blocks
+    mixed = orc.grad_stats([(x, delta), ("rowsum", x, delta), ("rowsum", None, delta), ("embed", ids, delta)])
+    assert mixed["V"] == pytest.approx(mixed["S1"] - mixed["S2"] / B, rel=1e-11)
+
+
 def test_transposed_operand_detected():
     # d_in != d_out: the gradient is [d_out, d_in]; its sum over samples must match einsum
     r = _rng(7)
