@@ -148,6 +148,43 @@ def custom_grad_stats_inputs(seed: int, shapes, B: int, T: int, dtype: str,
     return out
 
 
+def token_ids(seed: int, B: int, T: int, vocab: int, zipf: float = 1.1) -> np.ndarray:
+    """int32 [B, T] token ids with a Zipf-like frequency profile (rank r drawn with weight
+    1 / r^zipf, then mapped through a fixed permutation of the vocabulary), the repeat
+    structure of natural-language token streams: a few ids occur many times per sample, most
+    at most once.  zipf = 0 is uniform."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    w = 1.0 / np.arange(1, vocab + 1, dtype=np.float64) ** zipf
+    w /= w.sum()
+    ranks = rng.choice(vocab, size=(B, T), p=w)
+    return rng.permutation(vocab)[ranks].astype(np.int32)
+
+
+def vector_table_inputs(seed: int, B: int, T: int, dtype: str, vectors=(), tables=(),
+                        std_delta: float = 1e-2, rho: float = 0.0):
+    """Host tensors for blocks that are not linear weights.
+    vectors: list of (d, has_x): a gain (has_x: x ~ N(0,1), the normalised input) or a bias.
+    tables: list of (vocab, d): token ids (Zipf-like) and delta.
+    Returns dicts {kind, d, delta, x | ids, vocab}; fp32 arrays or uint16 bf16 bit patterns."""
+    def draw(sd, d, std):
+        if rho == 0.0:
+            v = normal_f32(sd, (B, T, d), std)
+        else:
+            eps = normal_f32(sd, (B + 1, T, d), std)
+            v = np.float32(rho) * eps[:1] + np.float32(np.sqrt(1.0 - rho * rho)) * eps[1:]
+        return v if dtype == "f32" else f32_to_bf16_bits(v)
+    out = []
+    for j, (d, has_x) in enumerate(vectors):
+        e = dict(kind="vector", d=d, delta=draw(seed + 10 * j + 1, d, std_delta), x=None)
+        if has_x:
+            e["x"] = draw(seed + 10 * j, d, 1.0)
+        out.append(e)
+    for j, (vocab, d) in enumerate(tables):
+        out.append(dict(kind="embed", d=d, vocab=vocab, ids=token_ids(seed + 5000 + j, B, T, vocab),
+                        delta=draw(seed + 5000 + 10 * j + 1, d, std_delta)))
+    return out
+
+
 def outer_inputs(config: int, N=None, M=None, seed_offset=0):
     """theta_outer [N], list of M instance vectors theta_k = theta_outer - Delta_k, momentum [N].
 

@@ -48,6 +48,11 @@ extern "C" {
 /* ---- flags -------------------------------------------------------------------------- */
 #define ADLOCO_ACCUMULATE       0x1u  /* grad_stats: continue a batch (switch mode micro-batch) */
 #define ADLOCO_GRAD_PROVIDED    0x1u  /* linear_desc.flags: caller maintains grad_sum itself     */
+/* linear_desc.flags, bits 4..7: which block of the parameters the descriptor stands for      */
+#define ADLOCO_KIND_LINEAR      0x00u /* weight W [d_out, d_in] of a linear layer (the default)  */
+#define ADLOCO_KIND_VECTOR      0x10u /* vector p [d_out] used element-wise: a bias or a gain    */
+#define ADLOCO_KIND_EMBED       0x20u /* embedding table E [d_in, d_out], a = int32 token ids    */
+#define ADLOCO_KIND_MASK        0xf0u
 #define ADLOCO_BROADCAST        0x1u  /* outer_step: also write the new outer model into theta_k */
 #define ADLOCO_BIASED_VAR       0x1u  /* norm_test: variance normalised by 1/B instead of 1/(B-1)*/
 #define ADLOCO_ALLOW_SHRINK     0x2u  /* norm_test: raw ceil rule, requested batch may decrease   */
@@ -69,7 +74,7 @@ const char* adloco_last_error(const adloco_ctx* ctx);
 int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
 
 /* Measurement aid.  After adloco_set_tuning(ctx, "profile", 1) every launch of the named
- * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge") is bracketed by HIP
+ * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table") is bracketed by HIP
  * events on the call's stream.  adloco_profile_read waits for the recorded events of that
  * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
 int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
@@ -93,9 +98,23 @@ typedef struct {
                              over the (accumulated) batch.  Written by adloco_grad_stats
                              unless ADLOCO_GRAD_PROVIDED; read by adloco_norm_test.  May be
                              NULL in adloco_grad_stats with ADLOCO_GRAD_PROVIDED.             */
-  uint32_t flags;         /* 0 or ADLOCO_GRAD_PROVIDED                                        */
+  uint32_t flags;         /* ADLOCO_GRAD_PROVIDED and / or one ADLOCO_KIND_* value            */
   uint32_t reserved;      /* must be 0                                                        */
 } adloco_linear_desc;
+
+/* The other blocks of grad f(x_k; xi_i) (eq. 1 averages the gradient with respect to ALL
+ * parameters) reuse the same descriptor; their norms add to the same per-sample totals:
+ *
+ * ADLOCO_KIND_VECTOR  a vector p [d_out] that enters a layer element-wise, y_t = p * x_t + ...
+ *     g_i = sum_t delta_{i,t} * x_{i,t}.  `a` = x [B, T, d_out] (for the gain of a
+ *     normalisation layer: its normalised input), or NULL for x = 1 (a bias: g_i = sum_t
+ *     delta_{i,t}).  d_in must be 1; a_row_stride 0 means d_out; grad_sum is [d_out].
+ * ADLOCO_KIND_EMBED   an embedding table E [d_in = V, d_out]: `a` = token ids, device int32
+ *     [B, T] contiguous (a_row_stride unused); row v of g_i = sum of delta_{i,t} over the
+ *     tokens with id v, so ||g_i||^2 = sum_{t,t'} [id_t = id_t'] delta_t . delta_t'.  The table
+ *     gradient itself is the caller's: ADLOCO_GRAD_PROVIDED is required, grad_sum [V, d_out] is
+ *     only read (by adloco_norm_test) and may be NULL in adloco_grad_stats.  T <= 8192.
+ * Both kinds stream delta (and x) once; their sums run in a fixed order. */
 
 /* Running accumulator of one (possibly accumulated) batch; lives in device memory, owned by
  * the caller (16 bytes, 8-byte aligned). */

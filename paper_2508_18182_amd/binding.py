@@ -15,6 +15,7 @@ _LIB_PATH = os.environ.get("ADLOCO_LIBRARY_PATH") or os.path.join(_PKG, "libadlo
 ADLOCO_F32, ADLOCO_BF16 = 0, 1
 ADLOCO_ACCUMULATE = 0x1
 ADLOCO_GRAD_PROVIDED = 0x1
+ADLOCO_KIND_LINEAR, ADLOCO_KIND_VECTOR, ADLOCO_KIND_EMBED = 0x00, 0x10, 0x20
 ADLOCO_BROADCAST = 0x1
 ADLOCO_BIASED_VAR = 0x1
 ADLOCO_ALLOW_SHRINK = 0x2
@@ -177,31 +178,61 @@ def _dev_ptr(t, dtype=None, numel=None, name="tensor") -> C.c_void_p:
 
 def make_layer_descs(layers: Sequence[dict], B: int, T: int, dtype: int):
     """layers: dicts with a [B,T,d_in], delta [B,T,d_out], optional grad_sum [d_out,d_in] fp32,
-    optional provided=True.  Token rows may be strided views (last dim contiguous)."""
+    optional provided=True.  Token rows may be strided views (last dim contiguous).
+    kind="vector": a bias / gain block, delta [B,T,d], optional x [B,T,d], grad_sum [d].
+    kind="embed": an embedding table, ids int32 [B,T], delta [B,T,d], vocab=V, grad_sum [V,d]
+    (maintained by the caller)."""
     import torch
     tdt = torch.bfloat16 if dtype == ADLOCO_BF16 else torch.float32
     arr = (LinearDesc * len(layers))()
+
+    def check_rows(i, nm, t):
+        if not t.is_cuda or t.dtype != tdt or t.dim() != 3 or t.shape[0] != B or t.shape[1] != T:
+            raise ValueError(f"layer {i}: {nm} must be a GPU {tdt} tensor [B={B},T={T},d], got "
+                             f"{tuple(t.shape)} {t.dtype}")
+        if t.stride(2) != 1 or t.stride(0) != T * t.stride(1):
+            raise ValueError(f"layer {i}: {nm} needs unit stride in d and samples T rows apart")
+
     for i, l in enumerate(layers):
-        a, d = l["a"], l["delta"]
-        for nm, t in (("a", a), ("delta", d)):
-            if not t.is_cuda or t.dtype != tdt or t.dim() != 3 or t.shape[0] != B or t.shape[1] != T:
-                raise ValueError(f"layer {i}: {nm} must be a GPU {tdt} tensor [B={B},T={T},d], got "
-                                 f"{tuple(t.shape)} {t.dtype}")
-            if t.stride(2) != 1 or t.stride(0) != T * t.stride(1):
-                raise ValueError(f"layer {i}: {nm} needs unit stride in d and samples T rows apart")
+        kind = l.get("kind", "linear")
+        d = l["delta"]
+        check_rows(i, "delta", d)
         g = l.get("grad_sum")
+        flags = ADLOCO_GRAD_PROVIDED if l.get("provided") else 0
+        if kind == "linear":
+            a = l["a"]
+            check_rows(i, "a", a)
+            a_ptr, a_stride, d_in, gshape = a.data_ptr(), a.stride(1), a.shape[2], (d.shape[2], a.shape[2])
+        elif kind == "vector":
+            x = l.get("x")
+            if x is not None:
+                check_rows(i, "x", x)
+                if x.shape[2] != d.shape[2]:
+                    raise ValueError(f"layer {i}: x and delta differ in width")
+            a_ptr, a_stride = (x.data_ptr(), x.stride(1)) if x is not None else (None, 0)
+            d_in, gshape = 1, (d.shape[2],)
+            flags |= ADLOCO_KIND_VECTOR
+        elif kind == "embed":
+            ids = l["ids"]
+            if (not ids.is_cuda or ids.dtype != torch.int32 or not ids.is_contiguous()
+                    or tuple(ids.shape) != (B, T)):
+                raise ValueError(f"layer {i}: ids must be a contiguous GPU int32 tensor [B, T]")
+            a_ptr, a_stride, d_in, gshape = ids.data_ptr(), 0, int(l["vocab"]), (int(l["vocab"]), d.shape[2])
+            flags |= ADLOCO_KIND_EMBED | ADLOCO_GRAD_PROVIDED
+        else:
+            raise ValueError(f"layer {i}: unknown kind {kind!r}")
         if g is not None:
             if (not g.is_cuda or g.dtype != torch.float32 or not g.is_contiguous()
-                    or tuple(g.shape) != (d.shape[2], a.shape[2])):
-                raise ValueError(f"layer {i}: grad_sum must be contiguous fp32 [d_out, d_in] on the GPU")
-        arr[i].a = a.data_ptr()
+                    or tuple(g.shape) != gshape):
+                raise ValueError(f"layer {i}: grad_sum must be contiguous fp32 {gshape} on the GPU")
+        arr[i].a = a_ptr
         arr[i].delta = d.data_ptr()
-        arr[i].d_in = a.shape[2]
+        arr[i].d_in = d_in
         arr[i].d_out = d.shape[2]
-        arr[i].a_row_stride = a.stride(1)
+        arr[i].a_row_stride = a_stride
         arr[i].delta_row_stride = d.stride(1)
         arr[i].grad_sum = g.data_ptr() if g is not None else None
-        arr[i].flags = ADLOCO_GRAD_PROVIDED if l.get("provided") else 0
+        arr[i].flags = flags
         arr[i].reserved = 0
     return arr
 
@@ -233,7 +264,16 @@ def adloco_norm_test(ctx: Context, layers, acc, eta: float, b_cur: int, b_max: i
             g = l["grad_sum"]
             _dev_ptr(g, None, None, f"layer {i} grad_sum")
             arr[i].grad_sum = g.data_ptr()
-            arr[i].d_out, arr[i].d_in = g.shape
+            kind = l.get("kind", "linear")
+            if kind == "vector":
+                arr[i].d_out, arr[i].d_in = g.shape[0], 1
+                arr[i].flags = ADLOCO_KIND_VECTOR | (ADLOCO_GRAD_PROVIDED if l.get("provided") else 0)
+            elif kind == "embed":
+                arr[i].d_in, arr[i].d_out = g.shape
+                arr[i].flags = ADLOCO_KIND_EMBED | ADLOCO_GRAD_PROVIDED
+            else:
+                arr[i].d_out, arr[i].d_in = g.shape
+                arr[i].flags = ADLOCO_GRAD_PROVIDED if l.get("provided") else 0
     else:
         arr = descs
     res = NormTestResult()

@@ -32,6 +32,18 @@ struct LayerDev {
   int provided;            // 1: caller maintains grad_sum (no wgrad for this layer)
   int wg_blk_start;        // first workgroup of this layer in the wgrad launch
   int sq_blk_start;        // first workgroup of this layer in the squared-norm launch
+  int kind;                // ADLOCO_KIND_* (0: linear weight)
+};
+
+// One vector (bias / gain) or embedding-table block in the launches of its kernels.
+struct AuxDesc {
+  int layer;               // index into the layer table
+  int slabs;               // 256-column slabs of d_out
+  int blk_start;           // first workgroup in the (sample, slab) launch: B * slabs per block
+  int blk_start2;          // first workgroup in the per-slab launch (vectors: column sums)
+  long long vec_off;       // vectors: offset (floats) of this block's [B, d_out] sums
+  long long perm_off;      // tables: offset (ints) of this block's [B, T] token order
+  long long part_off;      // tables: offset (doubles) of this block's [B, slabs] slab totals
 };
 
 // One wave-wide direct load global -> LDS: lane l's 16 bytes at `src` land at LDS byte address
@@ -78,6 +90,15 @@ struct adloco_ctx {
   adloco::Scratch wgx_part;    // partial tiles of the split contraction, 256 KiB each
   int wgx_n_split = 0;
   bool all_fast = false;       // every layer without a provided gradient: aligned, widths % 8 == 0
+  int n_linear = 0;            // linear-weight blocks in the table (= entries of order_tab)
+  // vector (bias / gain) and embedding-table blocks
+  std::vector<adloco::AuxDesc> vec_host, emb_host;
+  adloco::Scratch vec_tab, emb_tab;   // device copies of the two descriptor lists
+  adloco::Scratch aux_vec;     // float  per vector block [B, d_out]
+  adloco::Scratch aux_perm;    // int    per table block  [B, T]
+  adloco::Scratch aux_part;    // double per table block  [B, slabs]
+  int aux_B = -1, aux_T = -1;  // batch shape the descriptor lists were built for
+  int vec_blocks = 0, vec_blocks2 = 0, emb_blocks = 0;
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
   double* pinned = nullptr;    // 4 doubles of pinned host memory (norm-test read-back)
@@ -116,7 +137,7 @@ inline int fail(adloco_ctx* ctx, int code, const char* fmt, ...) {
 
 // Event timing of one kernel launch when ctx->profile is set (no-ops otherwise).
 enum ProfKernel { kProfGram = 0, kProfWgrad, kProfFinalize, kProfSqnorm, kProfOuter, kProfMerge,
-                  kProfCount };
+                  kProfVecTab, kProfCount };
 hipEvent_t prof_begin(adloco_ctx* ctx, hipStream_t st);
 void prof_end(adloco_ctx* ctx, int kernel, hipEvent_t start, hipStream_t st);
 
@@ -157,6 +178,14 @@ hipError_t launch_wgrad(const LayerDev* layers, int n_layers, int n_blocks, long
 hipError_t launch_finalize_stats(const float* partials, int n_layers, int B, int n_pairs,
                                  float* per_sample, float* per_layer_sample, double* sample_f64,
                                  adloco_stats_acc* acc, int accumulate, hipStream_t st);
+int vector_table_slab();
+hipError_t launch_vector_stats(const LayerDev* layers, const AuxDesc* tab, int n_tab,
+                               int blocks_rowsum, int blocks_colsum, int B, int T, int dtype,
+                               float* vec, float* partials, int n_pairs, int accumulate,
+                               hipStream_t st);
+hipError_t launch_embed_stats(const LayerDev* layers, const AuxDesc* tab, int n_tab, int blocks_rows,
+                              int B, int T, int dtype, int* perm, double* part, float* partials,
+                              int n_pairs, hipStream_t st);
 // sum_l ||grad_sum_l||^2 -> *out (device double); partial buffer sized by sqnorm_partials().
 int sqnorm_chunk();
 size_t sqnorm_partials(const std::vector<LayerDev>& host_layers);

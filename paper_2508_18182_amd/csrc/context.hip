@@ -58,7 +58,7 @@ void prof_end(adloco_ctx* ctx, int kernel, hipEvent_t start, hipStream_t st) {
 using namespace adloco;
 
 static const char* const kProfNames[kProfCount] = {"gram", "wgrad", "finalize", "sqnorm",
-                                                   "outer_step", "merge"};
+                                                   "outer_step", "merge", "vector_table"};
 
 extern "C" int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms,
                                    int* launches) {
@@ -132,7 +132,8 @@ extern "C" int adloco_destroy(adloco_ctx* ctx) {
   (void)hipDeviceSynchronize();
   Scratch* all[] = {&ctx->partials, &ctx->layer_tab, &ctx->red_f64, &ctx->sample_f64,
                     &ctx->order_tab, &ctx->job_tab, &ctx->wgx_tab,
-                    &ctx->wgx_split, &ctx->wgx_part};
+                    &ctx->wgx_split, &ctx->wgx_part, &ctx->vec_tab, &ctx->emb_tab,
+                    &ctx->aux_vec, &ctx->aux_perm, &ctx->aux_part};
   for (Scratch* s : all)
     if (s->ptr) (void)hipFree(s->ptr);
   for (auto& r : ctx->prof) {

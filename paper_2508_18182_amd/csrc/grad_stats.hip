@@ -24,29 +24,47 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
     const adloco_linear_desc& d = layers[l];
     if (d.d_in < 1 || d.d_out < 1)
       return fail(ctx, ADLOCO_EINVAL, "layer %d: d_in = %d, d_out = %d must be >= 1", l, d.d_in, d.d_out);
-    if (d.reserved != 0 || (d.flags & ~ADLOCO_GRAD_PROVIDED))
+    if (d.reserved != 0 || (d.flags & ~(ADLOCO_GRAD_PROVIDED | ADLOCO_KIND_MASK)))
       return fail(ctx, ADLOCO_EINVAL, "layer %d: unknown flags or non-zero reserved field", l);
     const bool provided = d.flags & ADLOCO_GRAD_PROVIDED;
+    const int kind = int(d.flags & ADLOCO_KIND_MASK);
+    if (kind != ADLOCO_KIND_LINEAR && kind != ADLOCO_KIND_VECTOR && kind != ADLOCO_KIND_EMBED)
+      return fail(ctx, ADLOCO_EINVAL, "layer %d: unknown kind 0x%x", l, kind);
+    if (kind == ADLOCO_KIND_VECTOR && d.d_in != 1)
+      return fail(ctx, ADLOCO_EINVAL, "layer %d: a vector block needs d_in = 1", l);
+    if (kind == ADLOCO_KIND_EMBED && !provided)
+      return fail(ctx, ADLOCO_EINVAL, "layer %d: an embedding block needs ADLOCO_GRAD_PROVIDED", l);
     LayerDev L{};
     L.a = d.a;
     L.delta = d.delta;
     L.grad_sum = d.grad_sum;
-    L.a_stride = d.a_row_stride ? d.a_row_stride : d.d_in;
+    L.a_stride = d.a_row_stride ? d.a_row_stride : (kind == ADLOCO_KIND_VECTOR ? d.d_out : d.d_in);
     L.delta_stride = d.delta_row_stride ? d.delta_row_stride : d.d_out;
     L.d_in = d.d_in;
     L.d_out = d.d_out;
     L.provided = provided ? 1 : 0;
+    L.kind = kind;
     if (need_inputs) {
-      if (!d.a || !d.delta) return fail(ctx, ADLOCO_EINVAL, "layer %d: a or delta is NULL", l);
-      if (L.a_stride < d.d_in || L.delta_stride < d.d_out)
+      if (!d.delta || (!d.a && kind != ADLOCO_KIND_VECTOR))
+        return fail(ctx, ADLOCO_EINVAL, "layer %d: a or delta is NULL", l);
+      const long long a_width = kind == ADLOCO_KIND_LINEAR ? d.d_in : d.d_out;
+      if ((kind != ADLOCO_KIND_EMBED && d.a && L.a_stride < a_width) || L.delta_stride < d.d_out)
         return fail(ctx, ADLOCO_EINVAL, "layer %d: row stride smaller than the row", l);
-      if ((reinterpret_cast<uintptr_t>(d.a) % esize) || (reinterpret_cast<uintptr_t>(d.delta) % esize))
+      const size_t a_esize = kind == ADLOCO_KIND_EMBED ? 4 : esize;
+      if ((reinterpret_cast<uintptr_t>(d.a) % a_esize) || (reinterpret_cast<uintptr_t>(d.delta) % esize))
         return fail(ctx, ADLOCO_EINVAL, "layer %d: a or delta not aligned to its element size", l);
       if (!provided && !d.grad_sum)
         return fail(ctx, ADLOCO_EINVAL, "layer %d: grad_sum is NULL without ADLOCO_GRAD_PROVIDED", l);
-      L.fast = (reinterpret_cast<uintptr_t>(d.a) % 16 == 0) &&
-               (reinterpret_cast<uintptr_t>(d.delta) % 16 == 0) && (d.d_in % 8 == 0) &&
-               (d.d_out % 8 == 0) && (L.a_stride % 8 == 0) && (L.delta_stride % 8 == 0);
+      const bool d_fast = (reinterpret_cast<uintptr_t>(d.delta) % 16 == 0) && (d.d_out % 8 == 0) &&
+                          (L.delta_stride % 8 == 0);
+      if (kind == ADLOCO_KIND_LINEAR)
+        L.fast = d_fast && (reinterpret_cast<uintptr_t>(d.a) % 16 == 0) && (d.d_in % 8 == 0) &&
+                 (L.a_stride % 8 == 0);
+      else if (kind == ADLOCO_KIND_VECTOR)
+        L.fast = d_fast && (!d.a || ((reinterpret_cast<uintptr_t>(d.a) % 16 == 0) &&
+                                     (L.a_stride % 8 == 0)));
+      else
+        L.fast = 0;
     } else if (!d.grad_sum) {
       return fail(ctx, ADLOCO_EINVAL, "layer %d: grad_sum is NULL", l);
     }
@@ -54,7 +72,7 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
       return fail(ctx, ADLOCO_EINVAL, "layer %d: grad_sum not 4-byte aligned", l);
     L.wg_blk_start = int(wg);
     L.sq_blk_start = int(sq);
-    if (!provided)
+    if (!provided && kind == ADLOCO_KIND_LINEAR)
       wg += (long long)((d.d_out + wt - 1) / wt) * ((d.d_in + wt - 1) / wt);
     sq += ((long long)d.d_in * d.d_out + chunk - 1) / chunk;
     if (wg > 0x7fffffffLL || sq > 0x7fffffffLL)
@@ -65,30 +83,36 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
                     std::memcmp(tab.data(), ctx->layer_tab_host.data(),
                                 tab.size() * sizeof(LayerDev)) == 0;
   if (same) return ADLOCO_OK;
-  // heaviest layers first, so that the tail of the Gram launch is made of cheap workgroups
-  std::vector<int> order(n_layers);
-  std::iota(order.begin(), order.end(), 0);
+  // linear layers, heaviest first, so that the tail of the Gram launch is made of cheap workgroups
+  std::vector<int> order;
+  for (int l = 0; l < n_layers; ++l)
+    if (tab[l].kind == ADLOCO_KIND_LINEAR) order.push_back(l);
   std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
     return (long long)tab[x].d_in + tab[x].d_out > (long long)tab[y].d_in + tab[y].d_out;
   });
   int rc = ensure_scratch(ctx, ctx->layer_tab, tab.size() * sizeof(LayerDev));
   if (rc) return rc;
-  rc = ensure_scratch(ctx, ctx->order_tab, order.size() * sizeof(int));
+  rc = ensure_scratch(ctx, ctx->order_tab, std::max<size_t>(order.size(), 1) * sizeof(int));
   if (rc) return rc;
   ctx->layer_tab_host.clear();          // invalid until both copies are enqueued
   ctx->table_dtype = -1;
   ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->layer_tab.ptr, tab.data(), tab.size() * sizeof(LayerDev),
                                        hipMemcpyHostToDevice, st));
-  ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->order_tab.ptr, order.data(), order.size() * sizeof(int),
-                                       hipMemcpyHostToDevice, st));
+  if (!order.empty())
+    ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->order_tab.ptr, order.data(), order.size() * sizeof(int),
+                                         hipMemcpyHostToDevice, st));
   // pageable sources: make sure the runtime has consumed them before they go out of scope
   ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
   bool f64 = need_inputs;
-  for (const LayerDev& L : tab) f64 = f64 && L.fast && L.d_in % 64 == 0 && L.d_out % 64 == 0;
+  for (const LayerDev& L : tab)
+    if (L.kind == ADLOCO_KIND_LINEAR) f64 = f64 && L.fast && L.d_in % 64 == 0 && L.d_out % 64 == 0;
   ctx->all_fast64 = f64;
   bool fast = need_inputs;
-  for (const LayerDev& L : tab) fast = fast && (L.provided || L.fast);
+  for (const LayerDev& L : tab)
+    if (L.kind == ADLOCO_KIND_LINEAR) fast = fast && (L.provided || L.fast);
   ctx->all_fast = fast;
+  ctx->n_linear = int(order.size());
+  ctx->aux_B = ctx->aux_T = -1;         // the vector / table descriptor lists follow the table
   ctx->wgx_slots = 0;
   if (fast && dtype == ADLOCO_BF16 && wg > 0) {
     std::vector<int4> tiles, split;
@@ -116,6 +140,69 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   return ADLOCO_OK;
 }
 
+// Descriptor lists of the vector and embedding-table blocks for a batch of B x T tokens, and
+// the scratch they need.  Rebuilt when the layer table or the batch shape changed.
+int prepare_vector_table(adloco_ctx* ctx, int B, int T, hipStream_t st) {
+  if (ctx->aux_B == B && ctx->aux_T == T) return ADLOCO_OK;
+  const int slab = vector_table_slab();
+  std::vector<AuxDesc> vec, emb;
+  long long vb = 0, vb2 = 0, eb = 0, voff = 0, poff = 0, partoff = 0;
+  for (size_t l = 0; l < ctx->layer_tab_host.size(); ++l) {
+    const LayerDev& L = ctx->layer_tab_host[l];
+    if (L.kind == ADLOCO_KIND_LINEAR) continue;
+    AuxDesc A{};
+    A.layer = int(l);
+    A.slabs = (L.d_out + slab - 1) / slab;
+    if (L.kind == ADLOCO_KIND_VECTOR) {
+      A.blk_start = int(vb);
+      A.blk_start2 = int(vb2);
+      A.vec_off = voff;
+      vb += (long long)B * A.slabs;
+      vb2 += A.slabs;
+      voff += (long long)B * L.d_out;
+      vec.push_back(A);
+    } else {
+      A.blk_start = int(eb);
+      A.perm_off = poff;
+      A.part_off = partoff;
+      eb += (long long)B * A.slabs;
+      poff += (long long)B * T;
+      partoff += (long long)B * A.slabs;
+      emb.push_back(A);
+    }
+    if (vb > 0x7fffffffLL || eb > 0x7fffffffLL)
+      return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: too many vector / table blocks for one launch");
+  }
+  if (!emb.empty() && T > 8192)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: embedding blocks need T <= 8192, got %d", T);
+  int rc = ensure_scratch(ctx, ctx->vec_tab, std::max<size_t>(vec.size(), 1) * sizeof(AuxDesc));
+  if (rc) return rc;
+  rc = ensure_scratch(ctx, ctx->emb_tab, std::max<size_t>(emb.size(), 1) * sizeof(AuxDesc));
+  if (rc) return rc;
+  rc = ensure_scratch(ctx, ctx->aux_vec, std::max<size_t>(size_t(voff), 1) * sizeof(float));
+  if (rc) return rc;
+  rc = ensure_scratch(ctx, ctx->aux_perm, std::max<size_t>(size_t(poff), 1) * sizeof(int));
+  if (rc) return rc;
+  rc = ensure_scratch(ctx, ctx->aux_part, std::max<size_t>(size_t(partoff), 1) * sizeof(double));
+  if (rc) return rc;
+  ctx->aux_B = ctx->aux_T = -1;
+  if (!vec.empty())
+    ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->vec_tab.ptr, vec.data(), vec.size() * sizeof(AuxDesc),
+                                         hipMemcpyHostToDevice, st));
+  if (!emb.empty())
+    ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->emb_tab.ptr, emb.data(), emb.size() * sizeof(AuxDesc),
+                                         hipMemcpyHostToDevice, st));
+  if (!vec.empty() || !emb.empty()) ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+  ctx->vec_host = std::move(vec);
+  ctx->emb_host = std::move(emb);
+  ctx->vec_blocks = int(vb);
+  ctx->vec_blocks2 = int(vb2);
+  ctx->emb_blocks = int(eb);
+  ctx->aux_B = B;
+  ctx->aux_T = T;
+  return ADLOCO_OK;
+}
+
 }  // namespace
 
 extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
@@ -137,6 +224,8 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   const int accumulate = (flags & ADLOCO_ACCUMULATE) ? 1 : 0;
 
   int rc = prepare_tables(ctx, layers, n_layers, dtype, true, st);
+  if (rc) return rc;
+  rc = prepare_vector_table(ctx, B, T, st);
   if (rc) return rc;
 
   const int tile = gram_tile_edge(dtype, ctx->gram_variant);
@@ -169,15 +258,17 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   GramLaunch g;
   g.layers = static_cast<const LayerDev*>(ctx->layer_tab.ptr);
   g.order = static_cast<const int*>(ctx->order_tab.ptr);
-  g.n_layers = n_layers;
+  g.n_layers = ctx->n_linear;   // the Gram launch walks order_tab: linear weights only
   g.B = B;
   g.T = T;
   g.partials = static_cast<float*>(ctx->partials.ptr);
   g.n_pairs = int(n_pairs);
   g.tile = tile;
-  hipEvent_t ev = prof_begin(ctx, st);
-  hipError_t e;
-  if (dual)
+  hipEvent_t ev = ctx->n_linear > 0 ? prof_begin(ctx, st) : nullptr;
+  hipError_t e = hipSuccess;
+  if (ctx->n_linear == 0)
+    ;
+  else if (dual)
     e = launch_gram_bf16_dual(g, static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n,
                               ctx->gram_variant, st);
   else if (dtype == ADLOCO_BF16)
@@ -199,6 +290,22 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   prof_end(ctx, kProfWgrad, ev, st);
   if (e != hipSuccess)
     return fail(ctx, ADLOCO_EHIP, "grad_stats: gradient-sum launch failed: %s", hipGetErrorString(e));
+  if (!ctx->vec_host.empty() || !ctx->emb_host.empty()) {
+    ev = prof_begin(ctx, st);
+    e = launch_vector_stats(g.layers, static_cast<const AuxDesc*>(ctx->vec_tab.ptr),
+                            int(ctx->vec_host.size()), ctx->vec_blocks, ctx->vec_blocks2, B, T, dtype,
+                            static_cast<float*>(ctx->aux_vec.ptr), g.partials, int(n_pairs),
+                            accumulate, st);
+    if (e == hipSuccess)
+      e = launch_embed_stats(g.layers, static_cast<const AuxDesc*>(ctx->emb_tab.ptr),
+                             int(ctx->emb_host.size()), ctx->emb_blocks, B, T, dtype,
+                             static_cast<int*>(ctx->aux_perm.ptr),
+                             static_cast<double*>(ctx->aux_part.ptr), g.partials, int(n_pairs), st);
+    prof_end(ctx, kProfVecTab, ev, st);
+    if (e != hipSuccess)
+      return fail(ctx, ADLOCO_EHIP, "grad_stats: vector / table launch failed: %s",
+                  hipGetErrorString(e));
+  }
   e = launch_finalize_stats(g.partials, n_layers, B, int(n_pairs), per_sample_sqnorm,
                             per_layer_sample_sqnorm, static_cast<double*>(ctx->sample_f64.ptr),
                             acc, accumulate, st);

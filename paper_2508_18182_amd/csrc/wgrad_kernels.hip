@@ -465,7 +465,7 @@ int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& o
   std::vector<int> idx;
   std::vector<long long> cnt(layers.size(), 0);
   for (size_t l = 0; l < layers.size(); ++l) {
-    if (layers[l].provided) continue;
+    if (layers[l].provided || layers[l].kind != ADLOCO_KIND_LINEAR) continue;
     cnt[l] = (long long)((layers[l].d_out + kXt - 1) / kXt) * ((layers[l].d_in + kXt - 1) / kXt);
     idx.push_back(int(l));
   }
