@@ -44,6 +44,8 @@ def parse():
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run three plain 1 GiB device copies (untimed) so that a counter "
                         "profile of this command holds a kernel of known traffic")
+    p.add_argument("--no-next-rows", action="store_true",
+                   help="skip the extra leg that times the bias / gain / embedding blocks")
     p.add_argument("--only", default="all", choices=["all", "stats", "outer"],
                    help="time only one half (diagnostics; the JSON line says so)")
     return p.parse_args()
@@ -94,6 +96,48 @@ def cpu_baseline(synth, orc, shapes, B, T, N, M, blocks):
                         f"and N params: {t_est:.1f} s"),
                 grad_stats_tokens_per_s=B * T / (t_stats * n_blocks / blocks),
                 outer_merge_GBps=((4 * (M + 2) + 8 + 4 * (M + 1)) * n_s) / t_outer / 1e9)
+
+
+def vector_table_leg(torch, synth, A, ctx, layers, B, T, dev, steps):
+    """Extra leg (not part of `value`): per-sample norms of the GPT-2-small blocks that are not
+    linear weights -- the four linear biases of each block (their delta is the linear layer's),
+    two LayerNorm gains and biases per block plus the final one, token and position embeddings.
+    Returns the group's kernel time and its algorithmic HBM bytes (every delta / x element once
+    per block that uses it, 2 bytes each; ids 4 bytes)."""
+    d, V = 768, 50257
+    blocks, nbytes = [], 0
+    for l in layers:                                   # biases
+        blocks.append(dict(kind="vector", x=None, delta=l["delta"],
+                           grad_sum=torch.zeros(l["d_out"], device=dev)))
+        nbytes += 2 * B * T * l["d_out"]
+    for j in range(25):                                # LayerNorm gains and biases
+        x = synth.device_normal(7000 + 2 * j, (B, T, d), 1.0, torch.bfloat16, dev)
+        dl = synth.device_normal(7001 + 2 * j, (B, T, d), 1e-2, torch.bfloat16, dev)
+        blocks.append(dict(kind="vector", x=x, delta=dl, grad_sum=torch.zeros(d, device=dev)))
+        blocks.append(dict(kind="vector", x=None, delta=dl, grad_sum=torch.zeros(d, device=dev)))
+        nbytes += 3 * 2 * B * T * d
+    ids = torch.from_numpy(synth.token_ids(7100, B, T, V)).to(dev)
+    pos = torch.arange(T, dtype=torch.int32, device=dev).repeat(B, 1).contiguous()
+    de = synth.device_normal(7101, (B, T, d), 1e-2, torch.bfloat16, dev)
+    blocks.append(dict(kind="embed", ids=ids, vocab=V, delta=de, grad_sum=None))
+    blocks.append(dict(kind="embed", ids=pos, vocab=T, delta=de, grad_sum=None))
+    nbytes += 2 * (2 * B * T * d + 4 * B * T)
+    descs = A.make_layer_descs(blocks, B, T, A.ADLOCO_BF16)
+    ps = torch.zeros(B, dtype=torch.float32, device=dev)
+    acc = torch.zeros(2, dtype=torch.float64, device=dev)
+    for _ in range(2):
+        A.adloco_grad_stats(ctx, blocks, B, T, A.ADLOCO_BF16, ps, None, acc, 0, descs=descs)
+    torch.cuda.synchronize()
+    ctx.profile_read("vector_table")
+    for _ in range(steps):
+        A.adloco_grad_stats(ctx, blocks, B, T, A.ADLOCO_BF16, ps, None, acc, 0, descs=descs)
+    torch.cuda.synchronize()
+    ms, n = ctx.profile_read("vector_table")
+    ms = ms / n if n else None
+    return dict(bound="hbm", kernel="vector_rowsum_kernel + embed_rows_kernel (+ small reductions)",
+                blocks=len(blocks), avg_kernel_ms=ms, bytes_algorithmic=nbytes,
+                achieved=(nbytes / (ms * 1e-3) / 1e9) if ms else None, peak=PEAK_HBM / 1e9, unit="GB/s",
+                frac=(nbytes / (ms * 1e-3) / PEAK_HBM) if ms else None, traffic=None)
 
 
 def measured_traffic():
@@ -283,6 +327,9 @@ def main():
         "merge_GBps": r_merge["achieved"] if r_merge else None,
         "norm_test": {k: last.get(k) for k in ("stat", "b_req", "test_passed", "accumulate")},
     }
+    if args.only in ("all", "stats") and not args.no_next_rows:
+        out["next_rows"] = {"vector_table": vector_table_leg(torch, synth, A, ctx, layers, B, T, dev,
+                                                             args.steps)}
     if not args.no_cpu_baseline:
         from oracle import adloco_oracle as orc
         out["cpu_baseline"] = cpu_baseline(synth, orc, shapes, B, T, N, M, max(1, min(12, args.cpu_blocks)))

@@ -38,7 +38,7 @@ struct LayerDev {
 // One vector (bias / gain) or embedding-table block in the launches of its kernels.
 struct AuxDesc {
   int layer;               // index into the layer table
-  int slabs;               // 256-column slabs of d_out
+  int slabs;               // column slabs of d_out (256 wide for vectors, 64 for tables)
   int blk_start;           // first workgroup in the (sample, slab) launch: B * slabs per block
   int blk_start2;          // first workgroup in the per-slab launch (vectors: column sums)
   long long vec_off;       // vectors: offset (floats) of this block's [B, d_out] sums
@@ -179,6 +179,7 @@ hipError_t launch_finalize_stats(const float* partials, int n_layers, int B, int
                                  float* per_sample, float* per_layer_sample, double* sample_f64,
                                  adloco_stats_acc* acc, int accumulate, hipStream_t st);
 int vector_table_slab();
+int embed_table_slab();
 hipError_t launch_vector_stats(const LayerDev* layers, const AuxDesc* tab, int n_tab,
                                int blocks_rowsum, int blocks_colsum, int B, int T, int dtype,
                                float* vec, float* partials, int n_pairs, int accumulate,

@@ -152,7 +152,8 @@ int prepare_vector_table(adloco_ctx* ctx, int B, int T, hipStream_t st) {
     if (L.kind == ADLOCO_KIND_LINEAR) continue;
     AuxDesc A{};
     A.layer = int(l);
-    A.slabs = (L.d_out + slab - 1) / slab;
+    const int w = L.kind == ADLOCO_KIND_VECTOR ? slab : embed_table_slab();
+    A.slabs = (L.d_out + w - 1) / w;
     if (L.kind == ADLOCO_KIND_VECTOR) {
       A.blk_start = int(vb);
       A.blk_start2 = int(vb2);

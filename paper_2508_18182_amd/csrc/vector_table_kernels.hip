@@ -85,6 +85,7 @@ __global__ __launch_bounds__(kVtThreads) void vector_rowsum_kernel(const LayerDe
   const E* X = L.a ? reinterpret_cast<const E*>(L.a) + (long long)sample * T * L.a_stride : nullptr;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (c < d) {
+#pragma unroll 4
     for (int t = rg; t < T; t += 8) {
       float dv[8];
       load8<E>(D + (long long)t * L.delta_stride, c, d, L.fast, dv);
@@ -184,33 +185,77 @@ __global__ __launch_bounds__(kVtThreads) void embed_sort_kernel(const LayerDev* 
   }
 }
 
-// Tables, step 2: one thread per column walks the sample's tokens in id order, sums the delta
-// rows of equal ids and adds up the squares of the finished sums; one workgroup per
-// (table, sample, 256-column slab), slab totals to `part`.
+// Tables, step 2: one workgroup per (table, sample, 64-column slab).  Its four waves split the
+// sample's tokens, taken in id order, into four consecutive pieces; in each piece a thread
+// (one column) sums the delta rows of equal ids and adds up the squares of the sums that are
+// complete inside the piece.  A run of equal ids that crosses a piece boundary is stitched
+// together afterwards from the pieces' head and tail sums, in piece order.
+constexpr int kEmbSlab = 64;
+
 template <typename E>
 __global__ __launch_bounds__(kVtThreads) void embed_rows_kernel(const LayerDev* layers,
                                                                 const AuxDesc* tab, int n_tab,
                                                                 int B, int T, const int* perm,
                                                                 double* part) {
+  __shared__ float head[4][kEmbSlab], tail[4][kEmbSlab];
+  __shared__ double inner[4][kEmbSlab];
+  __shared__ int has_start[4];
   __shared__ double lds4[4];
   const AuxDesc A = tab[find_aux(tab, n_tab, blockIdx.x)];
   const LayerDev L = layers[A.layer];
   const int rel = blockIdx.x - A.blk_start;
   const int sample = rel / A.slabs, slab = rel % A.slabs;
-  const int col = slab * kSlab + threadIdx.x;
+  const int lane = threadIdx.x & 63, piece = threadIdx.x >> 6;
+  const int col = slab * kEmbSlab + lane;
+  const bool live = col < L.d_out;
   const E* D = reinterpret_cast<const E*>(L.delta) + (long long)sample * T * L.delta_stride;
   const int* order = perm + A.perm_off + (long long)sample * T;
+  const int len = (T + 3) / 4;
+  const int s_begin = piece * len, s_end = (piece + 1) * len < T ? (piece + 1) * len : T;
+  float run = 0.f, first_run = 0.f;
   double tot = 0.0;
-  if (col < L.d_out) {
-    float run = 0.f;
-    for (int s = 0; s < T; ++s) {
-      const int e = order[s];
-      if (e < 0) { tot += double(run) * double(run); run = 0.f; }
-      run += elem_to_f32(D[(long long)(e & 0x7fffffff) * L.delta_stride + col]);
-    }
-    tot += double(run) * double(run);
+  bool started = false;           // a run began inside this piece
+  // eight tokens' rows are requested together, then consumed in order
+  for (int s0 = s_begin; s0 < s_end; s0 += 8) {
+    int e[8];
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) e[j] = s0 + j < s_end ? order[s0 + j] : 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      v[j] = (live && s0 + j < s_end)
+                 ? elem_to_f32(D[(long long)(e[j] & 0x7fffffff) * L.delta_stride + col]) : 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < s_end) {
+        if (e[j] < 0) {           // first token of an id: the run before it is finished
+          if (started) tot += double(run) * double(run); else first_run = run;
+          started = true;
+          run = 0.f;
+        }
+        run += v[j];
+      }
   }
-  const double s = vt_block_sum(tot, lds4);
+  // no run began here: the whole piece continues an earlier run (head = run, nothing else)
+  head[piece][lane] = started ? first_run : run;
+  tail[piece][lane] = started ? run : 0.f;
+  inner[piece][lane] = tot;
+  if (lane == 0) has_start[piece] = started ? 1 : 0;
+  __syncthreads();
+  double total = 0.0;
+  if (piece == 0) {
+    float carry = 0.f;            // open run handed from piece to piece
+    for (int k = 0; k < 4; ++k) {
+      carry += head[k][lane];
+      if (has_start[k]) {
+        total += double(carry) * double(carry) + inner[k][lane];
+        carry = tail[k][lane];
+      }
+    }
+    total += double(carry) * double(carry);
+    if (!live) total = 0.0;
+  }
+  const double s = vt_block_sum(total, lds4);
   if (threadIdx.x == 0) part[A.part_off + (long long)sample * A.slabs + slab] = s;
 }
 
@@ -230,6 +275,7 @@ __global__ __launch_bounds__(64) void embed_finalize_kernel(const AuxDesc* tab, 
 }
 
 int vector_table_slab() { return kSlab; }
+int embed_table_slab() { return kEmbSlab; }
 
 hipError_t launch_vector_stats(const LayerDev* layers, const AuxDesc* tab, int n_tab,
                                int blocks_rowsum, int blocks_colsum, int B, int T, int dtype,
