@@ -193,3 +193,58 @@ def test_vector_table_errors(ctx):
     descs[0].flags = 0x30                               # unknown kind
     with pytest.raises(A.AdlocoError):
         A.adloco_grad_stats(ctx, None, B, T, A.ADLOCO_BF16, ps, None, new_acc(), descs=descs)
+
+
+def test_fullsize_gpt2_vector_table_blocks(ctx):
+    # the launch of bench.py's extra leg: 100 blocks (48 biases, 25 norm gains + biases, token
+    # and position embeddings), B = 32, T = 512, drawn on the device; sampled blocks are copied
+    # back and checked in full against the oracle
+    import torch
+    import paper_2508_18182_amd as A
+    from gpu_util import DEV, rel_err
+    B, T, d, V = 32, 512, 768, 50257
+
+    def bits(t):
+        return t.contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
+
+    blocks = []
+    for j, do in enumerate([2304, 768, 3072, 768] * 12):
+        dl = synth.device_normal(8000 + j, (B, T, do), 1e-2, torch.bfloat16, DEV)
+        blocks.append(dict(kind="vector", x=None, delta=dl, grad_sum=torch.zeros(do, device=DEV)))
+    for j in range(25):
+        x = synth.device_normal(8100 + 2 * j, (B, T, d), 1.0, torch.bfloat16, DEV)
+        dl = synth.device_normal(8101 + 2 * j, (B, T, d), 1e-2, torch.bfloat16, DEV)
+        blocks.append(dict(kind="vector", x=x, delta=dl, grad_sum=torch.zeros(d, device=DEV)))
+        blocks.append(dict(kind="vector", x=None, delta=dl, grad_sum=torch.zeros(d, device=DEV)))
+    ids = torch.from_numpy(synth.token_ids(8200, B, T, V)).to(DEV)
+    pos = torch.arange(T, dtype=torch.int32, device=DEV).repeat(B, 1).contiguous()
+    de = synth.device_normal(8201, (B, T, d), 1e-2, torch.bfloat16, DEV)
+    blocks.append(dict(kind="embed", ids=ids, vocab=V, delta=de, grad_sum=None))
+    blocks.append(dict(kind="embed", ids=pos, vocab=T, delta=de, grad_sum=None))
+    assert len(blocks) == 100
+    ps = torch.zeros(B, device=DEV)
+    pl = torch.zeros(len(blocks), B, device=DEV)
+    acc = torch.zeros(2, dtype=torch.float64, device=DEV)
+    A.adloco_grad_stats(ctx, blocks, B, T, A.ADLOCO_BF16, ps, pl, acc)
+    torch.cuda.synchronize()
+    pl_h = pl.cpu().numpy()
+    for l in (0, 2, 47, 48, 49, 96, 97, 98, 99):
+        b = blocks[l]
+        if b["kind"] == "vector":
+            entry = ("rowsum", None if b["x"] is None else bits(b["x"]), bits(b["delta"]))
+        else:
+            entry = ("embed", b["ids"].cpu().numpy(), bits(b["delta"]))
+        want = orc.grad_stats([entry], two_pass=False)
+        assert rel_err(pl_h[l], want["n_layer_sample"][0]) < 2e-3, l
+        if b["kind"] == "vector":
+            w = want["G"][0]
+            g = b["grad_sum"].cpu().numpy().astype(np.float64)
+            assert float(np.max(np.abs(g - w))) / (float(np.sqrt(np.mean(w * w))) + 1e-300) < 1e-4, l
+    # size-free properties: totals add up; the position table (all ids distinct) gives the sum
+    # of squared entries of delta; repeated ids make the token table differ from it
+    np.testing.assert_allclose(ps.cpu().numpy(), pl_h.sum(axis=0), rtol=1e-5)
+    S1 = float(acc.cpu()[0])
+    assert S1 == pytest.approx(float(pl_h.astype(np.float64).sum()), rel=1e-5)
+    sq = (de.float() ** 2).sum(dim=(1, 2)).cpu().numpy()
+    np.testing.assert_allclose(pl_h[99], sq, rtol=2e-3)
+    assert np.all(np.abs(pl_h[98] - sq) > 1e-6 * sq)
