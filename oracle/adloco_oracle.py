@@ -20,7 +20,8 @@ token rows; permutation and rotation invariance; element-by-element brute force;
 autograd of a bias-free linear layer, and of a linear bias, a LayerNorm gain and bias and an
 embedding table for the vector and table blocks (plus their one-token / all-distinct /
 all-equal-id closed forms); numpy's var(ddof=1) over the stacked per-sample
-gradients; iid-noise expectation B/eta^2; LocalSGD averaging (Section 3.1) and
+gradients; iid-noise expectation B/eta^2; torch.optim.AdamW and the first-step / zero-gradient
+closed forms for the inner step; LocalSGD averaging (Section 3.1) and
 torch.optim.SGD(nesterov=True) for the outer step; convexity / identity cases for the
 merge; Algorithm 1's branches enumerated by hand.
 
@@ -235,6 +236,34 @@ def norm_test(S1: float, S2: float, B: int, eta: float, b_cur: int, b_max: int,
     res["b_req"] = int(b_req)
     res.update(switch_mode(int(b_req), int(b_max), int(n_switch)))
     return res
+
+
+# --------------------------------------------------------------------------------------
+# Inner step (Algorithm 3, the InnerOpt lines; Section 6.1 names AdamW, lr 4e-4, decay 0.1)
+# --------------------------------------------------------------------------------------
+
+def inner_step(theta, exp_avg, exp_avg_sq, grad, step: int, lr: float, beta1: float = 0.9,
+               beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.1,
+               grad_scale: float = 1.0) -> dict:
+    """x_m <- InnerOpt(x_m, g) with InnerOpt = AdamW (decoupled weight decay), step = 1, 2, ...:
+        g = grad_scale * grad            (grad is a sum over samples; 1/b gives eq. 1's g_k)
+        x <- x - lr * weight_decay * x
+        m <- beta1 m + (1 - beta1) g ;   v <- beta2 v + (1 - beta2) g^2
+        x <- x - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+    fp64 arithmetic on the fp32 inputs, rounded to fp32 once.  beta1, beta2, eps are not given
+    by the paper; the defaults are the customary ones."""
+    x = widen(theta)
+    m = widen(exp_avg)
+    v = widen(exp_avg_sq)
+    g = grad_scale * widen(grad)
+    x = x - lr * weight_decay * x
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** step)
+    v_hat = v / (1.0 - beta2 ** step)
+    x = x - lr * m_hat / (np.sqrt(v_hat) + eps)
+    return dict(theta=x.astype(np.float32), exp_avg=m.astype(np.float32),
+                exp_avg_sq=v.astype(np.float32), theta_f64=x, exp_avg_f64=m, exp_avg_sq_f64=v)
 
 
 # --------------------------------------------------------------------------------------

@@ -447,6 +447,49 @@ def _outer_case(seed=60, N=257, M=3):
     return th, ins, mom
 
 
+def test_inner_step_matches_torch_adamw():
+    # library route: several steps of torch.optim.AdamW in float64
+    import torch
+    r = _rng(70)
+    N = 257
+    theta = r.standard_normal(N).astype(np.float32)
+    m = np.zeros(N, dtype=np.float32)
+    v = np.zeros(N, dtype=np.float32)
+    p = torch.tensor(theta.astype(np.float64), requires_grad=True)
+    opt = torch.optim.AdamW([p], lr=4e-4, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.1)
+    x64, m64, v64 = theta.astype(np.float64), m.astype(np.float64), v.astype(np.float64)
+    for step in range(1, 6):
+        g = r.standard_normal(N).astype(np.float32) * 3
+        p.grad = torch.tensor(0.25 * g.astype(np.float64))
+        opt.step()
+        o = orc.inner_step(x64, m64, v64, g, step, 4e-4, grad_scale=0.25)
+        x64, m64, v64 = o["theta_f64"], o["exp_avg_f64"], o["exp_avg_sq_f64"]
+        np.testing.assert_allclose(x64, p.detach().numpy(), rtol=1e-12, atol=1e-14)
+
+
+def test_inner_step_closed_forms():
+    r = _rng(71)
+    N = 64
+    theta = r.standard_normal(N).astype(np.float32)
+    g = (r.standard_normal(N) + 0.1).astype(np.float32)
+    z = np.zeros(N, dtype=np.float32)
+    # first step from a zero state without decay: m_hat = g, v_hat = g^2 -> lr * g / (|g| + eps)
+    o = orc.inner_step(theta, z, z, g, 1, 1e-2, weight_decay=0.0, eps=1e-8)
+    g64 = g.astype(np.float64)
+    np.testing.assert_allclose(o["theta_f64"], theta - 1e-2 * g64 / (np.abs(g64) + 1e-8), rtol=1e-12)
+    # zero gradient and zero state: pure decoupled decay x (1 - lr * wd)
+    o = orc.inner_step(theta, z, z, z, 3, 1e-2, weight_decay=0.1)
+    np.testing.assert_allclose(o["theta_f64"], theta.astype(np.float64) * (1 - 1e-3), rtol=1e-15)
+    # the update is odd in the gradient and invariant to its scale on the first step (eps -> 0)
+    a = orc.inner_step(z, z, z, g, 1, 1e-2, weight_decay=0.0, eps=0.0)
+    b = orc.inner_step(z, z, z, -7.0 * g, 1, 1e-2, weight_decay=0.0, eps=0.0)
+    np.testing.assert_allclose(a["theta_f64"], -b["theta_f64"], rtol=1e-12)
+    # grad_scale multiplies the gradient
+    c = orc.inner_step(theta, z, z, g, 2, 1e-3, grad_scale=0.5)
+    d = orc.inner_step(theta, z, z, (0.5 * g64).astype(np.float64), 2, 1e-3)
+    np.testing.assert_allclose(c["theta_f64"], d["theta_f64"], rtol=1e-13)
+
+
 def test_outer_m1_lr1_mu0_returns_inner_model():
     th, ins, _ = _outer_case(M=1)
     out = orc.outer_step(th, ins, None, lr=1.0, mu=0.0)
