@@ -140,6 +140,29 @@ def vector_table_leg(torch, synth, A, ctx, layers, B, T, dev, steps):
                 frac=(nbytes / (ms * 1e-3) / PEAK_HBM) if ms else None, traffic=None)
 
 
+def inner_step_leg(torch, synth, A, ctx, N, dev, steps):
+    """Extra leg (not part of `value`): the workers' fused AdamW step on N parameters; reads
+    theta, m, v, grad and writes theta, m, v: 28 bytes per parameter."""
+    th = synth.device_normal(7200, (N,), 0.02, torch.float32, dev)
+    m = synth.device_normal(7201, (N,), 1e-3, torch.float32, dev)
+    v = synth.device_normal(7202, (N,), 1e-3, torch.float32, dev).square_()
+    g = synth.device_normal(7203, (N,), 16.0, torch.float32, dev)
+    for k in range(2):
+        A.adloco_inner_step(ctx, th, m, v, g, step=k + 1, lr=4e-4, weight_decay=0.1, grad_scale=1.0 / 32)
+    torch.cuda.synchronize()
+    ctx.profile_read("inner_step")
+    for k in range(steps):
+        A.adloco_inner_step(ctx, th, m, v, g, step=k + 3, lr=4e-4, weight_decay=0.1, grad_scale=1.0 / 32)
+    torch.cuda.synchronize()
+    ms, n = ctx.profile_read("inner_step")
+    ms = ms / n if n else None
+    nbytes = 28 * N
+    return dict(bound="hbm", kernel="inner_step_vec_kernel", N=N, avg_kernel_ms=ms,
+                bytes_algorithmic=nbytes, achieved=(nbytes / (ms * 1e-3) / 1e9) if ms else None,
+                peak=PEAK_HBM / 1e9, unit="GB/s", frac=(nbytes / (ms * 1e-3) / PEAK_HBM) if ms else None,
+                traffic=None)
+
+
 def measured_traffic():
     """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
     WRITE_SIZE runs of this command, scaled as stated there); {} when the file is absent."""
@@ -327,9 +350,15 @@ def main():
         "merge_GBps": r_merge["achieved"] if r_merge else None,
         "norm_test": {k: last.get(k) for k in ("stat", "b_req", "test_passed", "accumulate")},
     }
-    if args.only in ("all", "stats") and not args.no_next_rows:
-        out["next_rows"] = {"vector_table": vector_table_leg(torch, synth, A, ctx, layers, B, T, dev,
-                                                             args.steps)}
+    if not args.no_next_rows:
+        out["next_rows"] = {}
+        if args.only in ("all", "stats"):
+            out["next_rows"]["vector_table"] = vector_table_leg(torch, synth, A, ctx, layers, B, T, dev,
+                                                                args.steps)
+        if args.only in ("all", "outer"):
+            del insts, mom
+            torch.cuda.empty_cache()
+            out["next_rows"]["inner_step"] = inner_step_leg(torch, synth, A, ctx, N, dev, args.steps)
     if not args.no_cpu_baseline:
         from oracle import adloco_oracle as orc
         out["cpu_baseline"] = cpu_baseline(synth, orc, shapes, B, T, N, M, max(1, min(12, args.cpu_blocks)))

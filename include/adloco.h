@@ -5,7 +5,8 @@
  *   1. adaptive-batch statistics: per-sample gradient squared norms of linear layers, the
  *      batch-gradient norm, the norm test / batch rule and the SwitchMode decision;
  *   2. the multi-instance DiLoCo outer step (averaged pseudo-gradient, Nesterov outer
- *      update, optional worker reset) and the batch-weighted trainer merge.
+ *      update, optional worker reset), the batch-weighted trainer merge, and the workers'
+ *      fused inner optimizer step.
  *
  * Conventions (all entry points)
  *   - Return value: 0 = ADLOCO_OK, otherwise one of the ADLOCO_E* codes below.  No exception
@@ -74,7 +75,7 @@ const char* adloco_last_error(const adloco_ctx* ctx);
 int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
 
 /* Measurement aid.  After adloco_set_tuning(ctx, "profile", 1) every launch of the named
- * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table") is bracketed by HIP
+ * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table", "inner_step") is bracketed by HIP
  * events on the call's stream.  adloco_profile_read waits for the recorded events of that
  * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
 int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
@@ -202,6 +203,25 @@ int adloco_switch_mode(int64_t b_req, int64_t b_max, int32_t n_switch,
 int adloco_outer_step(adloco_ctx* ctx, float* theta_outer, float* const* theta_inst, int M,
                       size_t N, float* momentum, double lr, double mu, int nesterov,
                       uint32_t flags, float* pseudo_grad_out, void* stream);
+
+/* adloco_inner_step: Algorithm 3's  x_m <- InnerOpt(x_m, g)  with InnerOpt = AdamW, the inner
+ * optimizer of Section 6.1 (learning rate 4e-4, weight decay 0.1), one fused pass:
+ *   g = grad_scale * grad;   x <- x - lr*weight_decay*x;
+ *   m <- beta1 m + (1-beta1) g;   v <- beta2 v + (1-beta2) g^2;
+ *   x <- x - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ *   theta        device [N] fp32, in/out: the worker's parameters x_m
+ *   exp_avg      device [N] fp32, in/out: m;   exp_avg_sq  device [N] fp32, in/out: v
+ *   grad         device [N] fp32, read only: a gradient SUM, e.g. the grad_sum buffers of
+ *                adloco_grad_stats laid out back to back (in switch mode the sum over the
+ *                accumulated micro-batches, Algorithm 3's "g <- g + grad L")
+ *   grad_scale   multiplies grad: 1 / (number of samples summed) gives eq. 1's g_k
+ *   step         1, 2, ...: the number of this update (bias correction); beta1, beta2 in [0,1)
+ * No buffer may alias another.  N = 0 is a successful no-op.  16-byte aligned pointers take
+ * the vector path, others a scalar path with the same results.  fp64 in registers, rounded
+ * once.  Reads 16 and writes 12 bytes per parameter. */
+int adloco_inner_step(adloco_ctx* ctx, float* theta, float* exp_avg, float* exp_avg_sq,
+                      const float* grad, size_t N, double grad_scale, double lr, double beta1,
+                      double beta2, double eps, double weight_decay, int64_t step, void* stream);
 
 /* adloco_merge: DoMerge (Algorithm 2; Section 4.1.1): x_r <- sum_j b_j x_j / sum_j b_j for
  * the representative r = argmax b_j (lowest index on ties) or the given `rep`; the other

@@ -96,11 +96,12 @@ def load_library():
                                       C.c_int, u32, vp, vp]
     lib.adloco_merge.argtypes = [vp, C.POINTER(vp), C.POINTER(dbl), C.c_int, sz, C.c_int,
                                  C.POINTER(C.c_int), vp]
+    lib.adloco_inner_step.argtypes = [vp, vp, vp, vp, vp, sz, dbl, dbl, dbl, dbl, dbl, dbl, i64, vp]
     lib.adloco_check_merge.argtypes = [C.POINTER(i64), C.c_int, C.c_int, C.POINTER(C.c_int),
                                        C.POINTER(C.c_int)]
     for name in ("adloco_create", "adloco_destroy", "adloco_set_tuning", "adloco_grad_stats",
                  "adloco_norm_test", "adloco_norm_test_decide", "adloco_switch_mode",
-                 "adloco_outer_step", "adloco_merge", "adloco_check_merge"):
+                 "adloco_outer_step", "adloco_merge", "adloco_check_merge", "adloco_inner_step"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -322,6 +323,18 @@ def adloco_outer_step(ctx: Context, theta_outer, theta_inst, momentum, lr: float
     ctx._check(load_library().adloco_outer_step(ctx._h, th, arr, len(theta_inst), N, mom, lr, mu,
                                                 1 if nesterov else 0, flags, pg,
                                                 _stream_ptr(stream)))
+
+
+def adloco_inner_step(ctx: Context, theta, exp_avg, exp_avg_sq, grad, step: int, lr: float,
+                      beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                      weight_decay: float = 0.1, grad_scale: float = 1.0, stream=None,
+                      N: Optional[int] = None):
+    import torch
+    N = theta.numel() if N is None else N
+    ptrs = [_dev_ptr(t, torch.float32, N, nm) for nm, t in
+            (("theta", theta), ("exp_avg", exp_avg), ("exp_avg_sq", exp_avg_sq), ("grad", grad))]
+    ctx._check(load_library().adloco_inner_step(ctx._h, *ptrs, N, grad_scale, lr, beta1, beta2, eps,
+                                                weight_decay, int(step), _stream_ptr(stream)))
 
 
 def adloco_merge(ctx: Context, x, weights, rep: int = -1, stream=None,

@@ -137,7 +137,7 @@ inline int fail(adloco_ctx* ctx, int code, const char* fmt, ...) {
 
 // Event timing of one kernel launch when ctx->profile is set (no-ops otherwise).
 enum ProfKernel { kProfGram = 0, kProfWgrad, kProfFinalize, kProfSqnorm, kProfOuter, kProfMerge,
-                  kProfVecTab, kProfCount };
+                  kProfVecTab, kProfInner, kProfCount };
 hipEvent_t prof_begin(adloco_ctx* ctx, hipStream_t st);
 void prof_end(adloco_ctx* ctx, int kernel, hipEvent_t start, hipStream_t st);
 

@@ -58,7 +58,8 @@ void prof_end(adloco_ctx* ctx, int kernel, hipEvent_t start, hipStream_t st) {
 using namespace adloco;
 
 static const char* const kProfNames[kProfCount] = {"gram", "wgrad", "finalize", "sqnorm",
-                                                   "outer_step", "merge", "vector_table"};
+                                                   "outer_step", "merge", "vector_table",
+                                                   "inner_step"};
 
 extern "C" int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms,
                                    int* launches) {

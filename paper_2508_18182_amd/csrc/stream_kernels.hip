@@ -2,6 +2,8 @@
 // OuterOpt, worker reset) and the trainer merge (Algorithm 2).  Every parameter is read
 // once from each input and written once to each output; arithmetic is fp64 in registers
 // (free next to the memory traffic) and rounded to fp32 once.
+#include <cmath>
+
 #include "common.h"
 
 namespace adloco {
@@ -159,6 +161,58 @@ __global__ __launch_bounds__(256) void merge_scalar_kernel(MergeArgs a, size_t f
 #pragma unroll
     for (int j = 0; j < S; ++j) x[j] = double(a.x[j][e]);
     a.x[a.rep][e] = float(merge_elem<S>(a, x));
+  }
+}
+
+struct InnerArgs {
+  float* theta;
+  float* m;
+  float* v;
+  const float* grad;
+  size_t n_vec, n;
+  double grad_scale, decay_keep, beta1, beta2, omb1, omb2, step_size, inv_sqrt_bc2, eps;
+};
+
+// AdamW on one parameter: decay_keep = 1 - lr*weight_decay, step_size = lr / (1 - beta1^step),
+// inv_sqrt_bc2 = 1 / sqrt(1 - beta2^step).
+__device__ __forceinline__ void inner_elem(const InnerArgs& a, double x, double m, double v,
+                                           double g0, double& xo, double& mo, double& vo) {
+  const double g = a.grad_scale * g0;
+  mo = a.beta1 * m + a.omb1 * g;
+  vo = a.beta2 * v + a.omb2 * g * g;
+  const double denom = sqrt(vo) * a.inv_sqrt_bc2 + a.eps;
+  xo = x * a.decay_keep - a.step_size * mo / denom;
+}
+
+__global__ __launch_bounds__(kStreamThreads) void inner_step_vec_kernel(InnerArgs a) {
+  const size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < a.n_vec) {
+    const size_t e = i * 4;
+    const f32x4 x = ld_stream(a.theta + e), m = ld_stream(a.m + e), v = ld_stream(a.v + e),
+                g = ld_stream(a.grad + e);
+    f32x4 xo, mo, vo;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      double xn, mn, vn;
+      inner_elem(a, double(x[c]), double(m[c]), double(v[c]), double(g[c]), xn, mn, vn);
+      xo[c] = float(xn);
+      mo[c] = float(mn);
+      vo[c] = float(vn);
+    }
+    __builtin_nontemporal_store(xo, reinterpret_cast<f32x4*>(a.theta + e));
+    __builtin_nontemporal_store(mo, reinterpret_cast<f32x4*>(a.m + e));
+    __builtin_nontemporal_store(vo, reinterpret_cast<f32x4*>(a.v + e));
+  }
+}
+
+__global__ __launch_bounds__(256) void inner_step_scalar_kernel(InnerArgs a, size_t first) {
+  const size_t stride = size_t(gridDim.x) * blockDim.x;
+  for (size_t e = first + size_t(blockIdx.x) * blockDim.x + threadIdx.x; e < a.n; e += stride) {
+    double xn, mn, vn;
+    inner_elem(a, double(a.theta[e]), double(a.m[e]), double(a.v[e]), double(a.grad[e]), xn, mn, vn);
+    a.theta[e] = float(xn);
+    a.m[e] = float(mn);
+    a.v[e] = float(vn);
   }
 }
 
@@ -326,5 +380,61 @@ extern "C" int adloco_merge(adloco_ctx* ctx, float* const* x, const double* weig
                         static_cast<hipStream_t>(stream));
   prof_end(ctx, kProfMerge, ev, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(ctx, ADLOCO_EHIP, "merge launch failed: %s", hipGetErrorString(e));
+  return ADLOCO_OK;
+}
+
+extern "C" int adloco_inner_step(adloco_ctx* ctx, float* theta, float* exp_avg, float* exp_avg_sq,
+                                 const float* grad, size_t N, double grad_scale, double lr,
+                                 double beta1, double beta2, double eps, double weight_decay,
+                                 int64_t step, void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (step < 1) return fail(ctx, ADLOCO_EINVAL, "inner_step: step = %lld, need step >= 1", (long long)step);
+  if (!(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0))
+    return fail(ctx, ADLOCO_EINVAL, "inner_step: beta1 and beta2 must lie in [0, 1)");
+  if (!(lr == lr) || !(eps >= 0.0) || !(weight_decay == weight_decay) || !(grad_scale == grad_scale))
+    return fail(ctx, ADLOCO_EINVAL, "inner_step: lr, eps, weight_decay or grad_scale is NaN (or eps < 0)");
+  if (N == 0) return ADLOCO_OK;
+  if (!theta || !exp_avg || !exp_avg_sq || !grad)
+    return fail(ctx, ADLOCO_EINVAL, "inner_step: NULL pointer");
+  const void* p[4] = {theta, exp_avg, exp_avg_sq, grad};
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < i; ++j)
+      if (p[i] == p[j]) return fail(ctx, ADLOCO_EINVAL, "inner_step: two arguments alias");
+  if (N / 4 > kMaxVecPerLaunch)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_step: N = %zu exceeds one launch", N);
+  const bool vec = aligned16(theta) && aligned16(exp_avg) && aligned16(exp_avg_sq) && aligned16(grad);
+  InnerArgs a{};
+  a.theta = theta;
+  a.m = exp_avg;
+  a.v = exp_avg_sq;
+  a.grad = grad;
+  a.n = N;
+  a.n_vec = vec ? N / 4 : 0;
+  a.grad_scale = grad_scale;
+  a.decay_keep = 1.0 - lr * weight_decay;
+  a.beta1 = beta1;
+  a.beta2 = beta2;
+  a.omb1 = 1.0 - beta1;
+  a.omb2 = 1.0 - beta2;
+  a.step_size = lr / (1.0 - std::pow(beta1, double(step)));
+  a.inv_sqrt_bc2 = 1.0 / std::sqrt(1.0 - std::pow(beta2, double(step)));
+  a.eps = eps;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t ev = prof_begin(ctx, st);
+  if (vec) {
+    if (a.n_vec > 0)
+      hipLaunchKernelGGL(inner_step_vec_kernel,
+                         dim3(unsigned((a.n_vec + kStreamThreads - 1) / kStreamThreads)),
+                         dim3(kStreamThreads), stream_lds_bytes(ctx->stream_blocks_per_cu, 4), st, a);
+    if (a.n_vec * 4 < a.n)
+      hipLaunchKernelGGL(inner_step_scalar_kernel, dim3(1), dim3(256), 0, st, a, a.n_vec * 4);
+  } else {
+    hipLaunchKernelGGL(inner_step_scalar_kernel, dim3(grid_for(a.n, ctx->stream_blocks_per_cu)),
+                       dim3(256), 0, st, a, size_t(0));
+  }
+  hipError_t e = hipGetLastError();
+  prof_end(ctx, kProfInner, ev, st);
+  if (e != hipSuccess)
+    return fail(ctx, ADLOCO_EHIP, "inner_step launch failed: %s", hipGetErrorString(e));
   return ADLOCO_OK;
 }
