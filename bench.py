@@ -172,7 +172,8 @@ def measured_traffic():
         with open(path) as f:
             for ln in f:
                 parts = [p.strip() for p in ln.split("|")]
-                if len(parts) >= 5 and parts[1] in ("gram", "wgrad", "outer_step", "merge", "sqnorm"):
+                if len(parts) >= 5 and parts[1] in ("gram", "wgrad", "outer_step", "merge", "sqnorm",
+                                                     "vector_table", "inner_step"):
                     out[parts[1]] = float(parts[2]) + float(parts[3])
     except OSError:
         pass
@@ -359,6 +360,8 @@ def main():
             del insts, mom
             torch.cuda.empty_cache()
             out["next_rows"]["inner_step"] = inner_step_leg(torch, synth, A, ctx, N, dev, args.steps)
+        for k, v in out["next_rows"].items():
+            v["traffic"] = traffic.get(k)
     if not args.no_cpu_baseline:
         from oracle import adloco_oracle as orc
         out["cpu_baseline"] = cpu_baseline(synth, orc, shapes, B, T, N, M, max(1, min(12, args.cpu_blocks)))
