@@ -44,6 +44,12 @@ def parse():
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run three plain 1 GiB device copies (untimed) so that a counter "
                         "profile of this command holds a kernel of known traffic")
+    p.add_argument("--config", type=int, default=2, choices=[2, 4, 5],
+                   help="2 (default, the benchmark workload): GPT-2-small statistics + 124M x 4 outer "
+                        "step; 4: transformer blocks of the Llama-1B-shaped workload (statistics only); "
+                        "5: blocks of the 350M round + its M = 8 outer step and merge")
+    p.add_argument("--blocks", type=int, default=None,
+                   help="transformer blocks of --config 4 / 5 to hold in memory (default 2)")
     p.add_argument("--no-next-rows", action="store_true",
                    help="skip the extra leg that times the bias / gain / embedding blocks")
     p.add_argument("--only", default="all", choices=["all", "stats", "outer"],
@@ -205,14 +211,29 @@ def main():
         ctx.set_tuning("stream_blocks_per_cu", args.stream_blocks_per_cu)
     ctx.set_tuning("profile", 1)
 
-    cfg = synth.CONFIGS[2]
+    cfg = synth.CONFIGS[args.config]
     B, T, eta = cfg["B"], cfg["T"], cfg["eta"]
-    shapes = synth.linear_shapes(2)
-    ocfg = synth.CONFIGS[3]["outer"]
+    shapes = synth.linear_shapes(args.config)
+    linears = None
+    if args.config != 2:
+        per_block = len(cfg["block"])
+        linears = range(per_block * (args.blocks or 2))
+        shapes = shapes[:len(linears)]
+        args.no_next_rows = True
+        args.no_cpu_baseline = True
+        if args.config == 4 and args.only == "all":
+            args.only = "stats"
+    ocfg = synth.CONFIGS[5 if args.config == 5 else 3]["outer"]
     N, M = ocfg["N"], ocfg["M"]
+    workload = {2: "GPT-2-small-shaped grad stats (48 linears, B=32, T=512, bf16) + norm test + "
+                   "outer step and merge (M=4 x 124M fp32)",
+                4: f"Llama-1B-shaped grad stats, {len(shapes)} linears of {len(shapes) // 7} blocks "
+                   f"(B=64, T=1024, bf16, q/k/v and gate/up share their input) + norm test",
+                5: f"350M-round grad stats, {len(shapes)} linears of {len(shapes) // 4} blocks (B=32, "
+                   f"T=1024, bf16) + norm test + outer step and merge (M=8 x 350M fp32)"}[args.config]
 
     # ---- inputs, resident in HBM
-    layers = synth.device_grad_stats_inputs(2, dev)
+    layers = synth.device_grad_stats_inputs(args.config, dev, linears=linears, share=args.config == 4)
     for l in layers:
         l["grad_sum"] = torch.zeros(l["d_out"], l["d_in"], dtype=torch.float32, device=dev)
         l["provided"] = bool(args.grad_provided)
@@ -220,7 +241,8 @@ def main():
     per_sample = torch.zeros(B, dtype=torch.float32, device=dev)
     per_layer = torch.zeros(len(layers), B, dtype=torch.float32, device=dev)
     acc = torch.zeros(2, dtype=torch.float64, device=dev)
-    theta, insts, mom = synth.device_outer_inputs(3, dev)
+    theta, insts, mom = (synth.device_outer_inputs(5 if args.config == 5 else 3, dev)
+                         if args.only in ("all", "outer") else (None, None, None))
     if args.grad_provided:
         # the caller's own weight gradient: any values do; computed once, outside the timed region
         for l in layers:
@@ -232,7 +254,7 @@ def main():
             l["provided"] = True
     torch.cuda.synchronize()
 
-    b_req = [B, B, B, B]
+    b_req = [B] * M
     last = {}
 
     def step():
@@ -335,8 +357,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "GPT-2-small-shaped grad stats (48 linears, B=32, T=512, bf16) + "
-                               "norm test + outer step and merge (M=4 x 124M fp32)",
+        "config": {"workload": workload,
+                   "blocks_held": (len(shapes) // len(cfg["block"])), "blocks_of_model": cfg["n_blocks"],
                    "B": B, "T": T, "n_linears": len(shapes), "M": M, "N": N, "eta": eta,
                    "grad_sum": "caller-provided" if args.grad_provided else "computed by the library",
                    "timed_part": args.only},

@@ -56,11 +56,12 @@ __device__ __forceinline__ void outer_elem(const OuterArgs& a, double th, double
 // Residency is capped by giving each workgroup a dynamic LDS allocation it never touches.
 constexpr int kStreamThreads = 64;
 constexpr int kLdsPerCu = 160 * 1024;
-// `blocks_per_cu` > 0 is the tuning knob; 0 picks the count that keeps about 64 KiB of loads in
-// flight per compute unit (each wave requests 1 KiB from each of `load_streams` vectors).
+// `blocks_per_cu` > 0 is the tuning knob; 0 picks the count that measured best: 48 / load_streams
+// + 2 waves per compute unit (each wave requests 1 KiB from each of `load_streams` vectors), i.e.
+// 56-70 KiB of loads in flight (14 waves for 4 streams, 10 for 6, 8 for 8, 7 for 10).
 static inline unsigned stream_lds_bytes(int blocks_per_cu, int load_streams) {
   if (blocks_per_cu < 1) {
-    blocks_per_cu = (64 + load_streams / 2) / load_streams;
+    blocks_per_cu = (48 + load_streams / 2) / load_streams + 2;
     if (blocks_per_cu < 4) blocks_per_cu = 4;
   }
   if (blocks_per_cu >= 32) return 0;            // no cap
