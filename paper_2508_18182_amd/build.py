@@ -21,8 +21,8 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 
 def build(verbose: bool = False, jobs: int = 8, extra_flags=(), lib_path: str = LIB,
           objdir_name: str = "_build") -> str:
-    """Compile every source with hipcc for gfx950 and link libadloco.so.  extra_flags / lib_path
-    serve one-off experimental builds (e.g. -DADLOCO_EXPERIMENT into another file)."""
+    """Compile every source with hipcc for gfx950 and link libadloco.so.  extra_flags / lib_path /
+    objdir_name allow a second build (other flags) next to the default one."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(PKG, objdir_name)
     os.makedirs(objdir, exist_ok=True)

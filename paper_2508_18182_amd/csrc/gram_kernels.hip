@@ -235,10 +235,6 @@ __device__ __forceinline__ void wg_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// MODE is 0 in the library.  (Non-zero values exist only for timing experiments built with
-// ADLOCO_EXPERIMENT: bit 0 drops the loads after the prologue, bit 1 drops the per-chunk wait and
-// barrier; both give wrong results.)
-template <int MODE, bool DIRECT>
 __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int bid = blockIdx.x;
@@ -289,45 +285,10 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
           const unsigned short* src = base + row_off[s][i] * stride + k0;
-          __builtin_amdgcn_global_load_lds(
-              (const __attribute__((address_space(1))) void*)src,
-              (__attribute__((address_space(3))) void*)(stage + (s * kTile + (wave + 8 * i) * 8) * ROWB),
-              16, 0, 0);
+          direct_load_lds16(src, lds_address(stage + (s * kTile + (wave + 8 * i) * 8) * ROWB));
         }
       }
     }
-  };
-
-  // Staging through registers instead (DIRECT == false): the same pieces travel global ->
-  // VGPR (requested right after the barrier of chunk c, for chunk c+2) -> LDS (written just
-  // before the barrier of chunk c+1).
-  u32x4 stage_regs[DIRECT ? 1 : 6];
-  auto issue_loads_regs = [&](int c) {
-    const bool is_a = c < nka;
-    const unsigned short* base = reinterpret_cast<const unsigned short*>(is_a ? L.a : L.delta);
-    const long long stride = is_a ? L.a_stride : L.delta_stride;
-    const int k0 = (is_a ? c : c - nka) * kKc + (lane & 7) * 8;
-#pragma unroll
-    for (int s = 0; s < 3; ++s)
-      if (s < nblk) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-          stage_regs[DIRECT ? 0 : s * 2 + i] =
-              *reinterpret_cast<const u32x4*>(base + row_off[s][i] * stride + k0);
-      }
-  };
-  auto store_regs = [&](int c) {
-    unsigned char* stage = lds + (c % kDualStages) * kDualStage;
-#pragma unroll
-    for (int s = 0; s < 3; ++s)
-      if (s < nblk) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const int row = s * kTile + ld_row + 64 * i;
-          *reinterpret_cast<u32x4*>(stage + row * ROWB + swz(row, lane & 7) * 16) =
-              stage_regs[DIRECT ? 0 : s * 2 + i];
-        }
-      }
   };
 
   // ---- fragment addressing
@@ -363,19 +324,12 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
       for (int j = 0; j < 16; ++j) { acc_a[m][n][j] = 0.f; acc_d[m][n][j] = 0.f; }
 
   // ---- prologue: chunks 0 and 1 in flight, chunk 0 landed for everybody
-  if (DIRECT) {
-    issue_loads(0);
-    if (nk > 1) {
-      issue_loads(1);
-      if (nblk == 3) wait_vmcnt<6>(); else if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
-    } else {
-      wait_vmcnt<0>();
-    }
+  issue_loads(0);
+  if (nk > 1) {
+    issue_loads(1);
+    if (nblk == 3) wait_vmcnt<6>(); else if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
   } else {
-    issue_loads_regs(0);
-    store_regs(0);
-    if (nk > 1) issue_loads_regs(1);
-    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): my LDS writes are done
+    wait_vmcnt<0>();
   }
   wg_barrier();
   bf16x8 fa[2][2], fb[2][2];
@@ -400,18 +354,9 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
     mfma4(fa[0], fb[0], acc);
     // k-step 1, with the barrier of this chunk in front of it
     if (c + 1 < nk) {
-      if (DIRECT) {
-        if (!(MODE & 2)) {
-          wait_vmcnt<0>();        // my share of chunk c+1 (the only loads in flight) has landed
-          wg_barrier();           // ... and so has everybody's; stage (c-1)%3 is free
-        }
-        if (!(MODE & 1) && c + 2 < nk) issue_loads(c + 2);
-      } else {
-        store_regs(c + 1);        // waits for the registers requested one chunk ago
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        wg_barrier();
-        if (c + 2 < nk) issue_loads_regs(c + 2);
-      }
+      wait_vmcnt<0>();        // my share of chunk c+1 (the only loads in flight) has landed
+      wg_barrier();           // ... and so has everybody's; stage (c-1)%3 is free
+      if (c + 2 < nk) issue_loads(c + 2);
     }
     read_frags(c, 2, fa[0], fb[0]);
     mfma4(fa[1], fb[1], acc);
@@ -597,15 +542,8 @@ std::vector<GramJob> make_gram_jobs(int nt) {
 
 hipError_t launch_gram_bf16_dual(const GramLaunch& l, const GramJob* jobs, int n_jobs,
                                  int variant, hipStream_t st) {
-  auto kern = gram_bf16_dual_kernel<0, true>;
-#ifdef ADLOCO_EXPERIMENT
-  if (variant == 2) kern = gram_bf16_dual_kernel<1, true>;
-  if (variant == 3) kern = gram_bf16_dual_kernel<2, true>;
-  if (variant == 4) kern = gram_bf16_dual_kernel<3, true>;
-  if (variant == 5) kern = gram_bf16_dual_kernel<0, false>;
-#else
+  auto kern = gram_bf16_dual_kernel;
   (void)variant;
-#endif
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDualLds);

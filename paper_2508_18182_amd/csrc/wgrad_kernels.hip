@@ -237,9 +237,6 @@ template <int N> __device__ __forceinline__ void wgx_wait_vmcnt() {
 // 256 distinct bytes.  Global addresses stay linear: 512 contiguous bytes per half wave.
 __device__ __forceinline__ int wgx_row_off(int row) { return (row & 15) * kXblk + (row >> 4) * kXrowB; }
 
-// MODE is 0 in the library (non-zero only in timing experiments built with ADLOCO_EXPERIMENT:
-// bit 0 drops the loads after the prologue, bit 1 the per-chunk wait and barrier).
-template <int MODE>
 __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
@@ -349,13 +346,11 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
     if (c + 1 < nk) {
       // chunk c+1 has landed for me (chunk c+2 may still be in flight), then for everybody;
       // every wave is done with chunk c-1, whose stage takes chunk c+3
-      if (!(MODE & 2)) {
-        if (c + 2 < nk) wgx_wait_vmcnt<4>(); else wgx_wait_vmcnt<0>();
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-      }
-      if (!(MODE & 1) && c + 3 < nk) issue_loads(c + 3);
+      if (c + 2 < nk) wgx_wait_vmcnt<4>(); else wgx_wait_vmcnt<0>();
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      if (c + 3 < nk) issue_loads(c + 3);
     }
     read_frags(c + 1 < nk ? c + 1 : c, 0, fa[0], fb[0]);
     mfma8(fa[1], fb[1]);
@@ -513,14 +508,8 @@ hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots,
                           const void* split_tiles, int n_split, float* partials, long long rows,
                           int accumulate, int variant, hipStream_t st) {
   if (slots <= 0) return hipSuccess;
-  auto kern = wgrad_bf16_x_kernel<0>;
-#ifdef ADLOCO_EXPERIMENT
-  if (variant == 3) kern = wgrad_bf16_x_kernel<1>;
-  if (variant == 4) kern = wgrad_bf16_x_kernel<2>;
-  if (variant == 5) kern = wgrad_bf16_x_kernel<3>;
-#else
+  auto kern = wgrad_bf16_x_kernel;
   (void)variant;
-#endif
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kXlds);
