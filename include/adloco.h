@@ -238,6 +238,91 @@ int adloco_merge(adloco_ctx* ctx, float* const* x, const double* weights, int S,
  * w <= k; else nothing.  sel_out: host [max(w,1)]; n_sel receives the count (0 or w). */
 int adloco_check_merge(const int64_t* b_req, int k, int w, int* sel_out, int* n_sel);
 
+/* ------------------------------------------------------------------------------------ *
+ * adloco_round: one outer step t of Algorithm 3 for k trainers co-resident on the device,
+ * as a host loop over the entry points above.  The model's forward / backward is the
+ * caller's: the driver asks for it through `batch_fn`.
+ *
+ *   1. k > 1: M_t = CheckMerge({b_req_i}, merge_w); if non-empty DoMerge (Algorithm 2) on the
+ *      trainers' outer models with weights b_req; the merged-away trainers are moved to the end
+ *      of `trainers` (order of the others preserved) and *k shrinks.
+ *   2. per trainer: SwitchMode(b_req_i); every worker m starts from the trainer's model
+ *      (x_m <- x_Ti), then runs `inner_steps` inner steps.  Each inner step takes accum
+ *      micro-batches of b_micro samples: batch_fn -> adloco_grad_stats (ADLOCO_ACCUMULATE from
+ *      the second micro-batch on: Algorithm 3's "g <- g + grad L") -> adloco_inner_step with
+ *      g = grad / (accum * b_micro).  After the first inner step of worker 0 the norm test
+ *      (adloco_norm_test with b_cur = b_req_i) gives the trainer's requested batch for the NEXT
+ *      outer step ("store b_req for the next outer step").
+ *   3. per trainer: Delta = (1/M) sum_m (x_Ti - x_m), x_Ti <- OuterOpt(x_Ti, Delta)
+ *      (adloco_outer_step).
+ * Readings of the listing: the switch decision is per trainer; the accumulate branch also runs
+ * `inner_steps` inner steps, each over its accumulated micro-batches; CheckMerge runs in every
+ * call (a merge cadence is the caller's: pass merge_w = 0 to skip).
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  float*  theta;        /* device [N] fp32: worker parameters x_m (overwritten from the trainer) */
+  float*  exp_avg;      /* device [N] fp32: AdamW first moment, carried across rounds            */
+  float*  exp_avg_sq;   /* device [N] fp32: AdamW second moment                                   */
+  float*  grad;         /* device [N] fp32: the grad_sum buffers of the layer list, back to back,
+                           in list order (layer l at grad + sum of the sizes before it)          */
+  int64_t step;         /* inner steps done so far (bias correction); in/out                      */
+} adloco_worker;
+
+typedef struct {
+  float*            theta_outer;        /* device [N] fp32: x_Ti, in/out                        */
+  float*            momentum;           /* device [N] fp32: OuterOpt momentum (NULL iff mu = 0) */
+  adloco_worker*    workers;            /* host array of n_workers workers                      */
+  int32_t           n_workers;          /* 1 .. ADLOCO_MAX_INSTANCES                            */
+  int32_t           reserved;           /* 0                                                    */
+  int64_t           b_req;              /* requested batch, in/out                              */
+  adloco_stats_acc* acc;                /* device accumulator (16 bytes)                        */
+  float*            per_sample_sqnorm;  /* device [b_max] fp32 scratch for the per-sample norms */
+  void*             user;               /* handed to batch_fn                                   */
+} adloco_trainer;
+
+typedef struct {
+  int32_t T;             /* tokens per sample                                                  */
+  int32_t dtype;         /* ADLOCO_F32 / ADLOCO_BF16 of every a, delta                         */
+  int32_t inner_steps;   /* H >= 1                                                             */
+  int32_t n_switch;      /* SwitchMode multiplier n (the paper uses 2)                         */
+  int32_t merge_w;       /* w of CheckMerge; 0: no merging in this call                        */
+  int32_t nesterov;      /* OuterOpt: 1 Nesterov momentum, 0 heavy ball                        */
+  int64_t b_max;         /* micro-batch (memory) cap                                           */
+  int64_t b_cap;         /* ceiling on b_req, 0 = none                                         */
+  double  eta;           /* norm test                                                          */
+  double  lr_inner, beta1, beta2, eps, weight_decay;   /* InnerOpt = AdamW                     */
+  double  lr_outer, mu_outer;                          /* OuterOpt                             */
+} adloco_round_config;
+
+/* Runs the model of worker `worker` of the trainer that owns `user` at parameters `theta`
+ * (device) on `b` fresh samples and describes the result: on entry layers[l] holds d_in, d_out,
+ * grad_sum, flags of the template; the callback fills a, delta and the row strides (device
+ * tensors [b, T, .] that stay valid until the next callback for this trainer), and for blocks
+ * with ADLOCO_GRAD_PROVIDED adds its own gradient sum into grad_sum.  Device work of the callback
+ * must be ordered before later work on `stream`.  Return 0, or non-zero to abort the round. */
+typedef int (*adloco_batch_fn)(void* user, int32_t worker, int32_t inner_step, int32_t micro_step,
+                               int64_t b, const float* theta, adloco_linear_desc* layers,
+                               int32_t n_layers, void* stream);
+
+typedef struct {
+  int64_t b_req_used;    /* the requested batch this round ran with                             */
+  int64_t b_micro;       /* SwitchMode: micro-batch size                                        */
+  int64_t accum_steps;   /* SwitchMode: micro-batches per inner step                            */
+  int32_t accumulate;    /* SwitchMode: 1 iff gradient accumulation was on                      */
+  int32_t merged_from;   /* number of trainers merged into this one in step 1 (0: none)         */
+  adloco_norm_test_result test;   /* the norm test that produced the new b_req                  */
+} adloco_round_report;
+
+/*   trainers   host array of *k trainers, reordered in place when a merge happens
+ *   k          in: number of trainers (>= 1); out: number left
+ *   layers     host template of n_layers descriptors: d_in, d_out, flags (a, delta, grad_sum
+ *              ignored); the blocks' sizes must add up to N
+ *   reports    host [k_in] or NULL; reports[i] belongs to trainers[i] after the call
+ * Returns ADLOCO_ESTATE when batch_fn fails. */
+int adloco_round(adloco_ctx* ctx, const adloco_round_config* cfg, adloco_trainer* trainers, int* k,
+                 const adloco_linear_desc* layers, int n_layers, size_t N, adloco_batch_fn batch_fn,
+                 adloco_round_report* reports, void* stream);
+
 /* Library version (major*10000 + minor*100 + patch). */
 int adloco_version(void);
 

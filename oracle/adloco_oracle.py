@@ -327,3 +327,63 @@ def merge(xs, weights, rep: int = -1) -> dict:
     if rep < 0:
         rep = int(np.argmax(w))        # first maximal element
     return dict(rep=rep, x_merge=acc.astype(np.float32), x_merge_f64=acc)
+
+
+# --------------------------------------------------------------------------------------
+# One outer step of Algorithm 3 for k trainers (host loop; the model is a callback)
+# --------------------------------------------------------------------------------------
+
+def round_step(trainers, cfg: dict, batch_fn) -> list:
+    """Algorithm 3, one outer step t, in the listing's order.
+
+    trainers: list of dicts {theta_outer [N], momentum [N], b_req, uid, workers: [{theta, exp_avg,
+    exp_avg_sq, step}]} (numpy fp32 vectors); modified in place; merged-away trainers are
+    removed from the list.  cfg: T-independent scalars {inner_steps, b_max, n_switch, b_cap, eta,
+    merge_w, lr_inner, beta1, beta2, eps, weight_decay, lr_outer, mu_outer, nesterov}.
+    batch_fn(uid, worker, inner_step, micro_step, b, theta) -> list of blocks in grad_stats'
+    entry format (linear weights and vectors only), b samples each.
+    The flat parameter vector is the concatenation of the blocks in list order (a linear weight
+    row-major [d_out, d_in]).  Readings as in the design notes: the switch decision is per trainer,
+    the accumulate branch runs the same number of inner steps, each over its accumulated
+    micro-batches, and the norm test runs on the first inner step's batch of worker 0.
+    Returns one report dict per remaining trainer."""
+    # CheckMerge / DoMerge (Algorithms 1 and 2)
+    if len(trainers) > 1 and cfg["merge_w"] > 0:
+        sel = check_merge([t["b_req"] for t in trainers], cfg["merge_w"])
+        if sel:
+            mg = merge([trainers[j]["theta_outer"] for j in sel], [trainers[j]["b_req"] for j in sel])
+            keep = sel[mg["rep"]]
+            trainers[keep]["theta_outer"] = mg["x_merge"]
+            trainers[keep]["merged_from"] = len(sel) - 1
+            for j in sorted((j for j in sel if j != keep), reverse=True):
+                del trainers[j]
+    reports = []
+    for t in trainers:
+        sm = switch_mode(int(t["b_req"]), cfg["b_max"], cfg["n_switch"])
+        rep = dict(b_req_used=int(t["b_req"]), merged_from=t.pop("merged_from", 0), **sm)
+        b_next = t["b_req"]
+        for m, w in enumerate(t["workers"]):
+            w["theta"] = np.array(t["theta_outer"], dtype=np.float32, copy=True)
+            for h in range(cfg["inner_steps"]):
+                micro = [batch_fn(t["uid"], m, h, s, sm["b_micro"], w["theta"])
+                         for s in range(sm["accum_steps"])]
+                blocks = concat_micro_batches(micro)
+                st = grad_stats(blocks, two_pass=False)
+                if m == 0 and h == 0:
+                    nt = norm_test(st["S1"], st["S2"], st["B"], cfg["eta"], int(t["b_req"]), cfg["b_max"],
+                                   cfg["n_switch"], cfg["b_cap"])
+                    rep["test"] = nt
+                    b_next = nt["b_req"]
+                g = np.concatenate([np.asarray(G).reshape(-1) for G in st["G"]])
+                w["step"] += 1
+                o = inner_step(w["theta"], w["exp_avg"], w["exp_avg_sq"], g, w["step"], cfg["lr_inner"],
+                               cfg["beta1"], cfg["beta2"], cfg["eps"], cfg["weight_decay"],
+                               grad_scale=1.0 / (sm["accum_steps"] * sm["b_micro"]))
+                w["theta"], w["exp_avg"], w["exp_avg_sq"] = o["theta"], o["exp_avg"], o["exp_avg_sq"]
+        t["b_req"] = b_next
+        reports.append(rep)
+    for t in trainers:
+        o = outer_step(t["theta_outer"], [w["theta"] for w in t["workers"]], t["momentum"],
+                       cfg["lr_outer"], cfg["mu_outer"], bool(cfg["nesterov"]))
+        t["theta_outer"], t["momentum"] = o["theta_outer"], o["momentum"]
+    return reports

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     ADLOCO_F32, ADLOCO_GRAD_PROVIDED, ADLOCO_KIND_EMBED, ADLOCO_KIND_LINEAR, ADLOCO_KIND_VECTOR,
     ADLOCO_MAX_INSTANCES, AdlocoError, Context, LinearDesc,
     NormTestResult, StatsAcc, adloco_check_merge, adloco_grad_stats, adloco_inner_step, adloco_merge,
-    adloco_norm_test, adloco_norm_test_decide, adloco_outer_step, adloco_switch_mode,
+    adloco_norm_test, adloco_norm_test_decide, adloco_outer_step, adloco_round, adloco_switch_mode,
     adloco_version, lib_path, load_library, make_layer_descs,
 )

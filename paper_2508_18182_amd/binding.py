@@ -54,6 +54,34 @@ class NormTestResult(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
+class Worker(C.Structure):
+    _fields_ = [("theta", C.c_void_p), ("exp_avg", C.c_void_p), ("exp_avg_sq", C.c_void_p),
+                ("grad", C.c_void_p), ("step", C.c_int64)]
+
+
+class Trainer(C.Structure):
+    _fields_ = [("theta_outer", C.c_void_p), ("momentum", C.c_void_p), ("workers", C.POINTER(Worker)),
+                ("n_workers", C.c_int32), ("reserved", C.c_int32), ("b_req", C.c_int64),
+                ("acc", C.c_void_p), ("per_sample_sqnorm", C.c_void_p), ("user", C.c_void_p)]
+
+
+class RoundConfig(C.Structure):
+    _fields_ = [("T", C.c_int32), ("dtype", C.c_int32), ("inner_steps", C.c_int32),
+                ("n_switch", C.c_int32), ("merge_w", C.c_int32), ("nesterov", C.c_int32),
+                ("b_max", C.c_int64), ("b_cap", C.c_int64), ("eta", C.c_double),
+                ("lr_inner", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
+                ("eps", C.c_double), ("weight_decay", C.c_double), ("lr_outer", C.c_double),
+                ("mu_outer", C.c_double)]
+
+
+class RoundReport(C.Structure):
+    _fields_ = [("b_req_used", C.c_int64), ("b_micro", C.c_int64), ("accum_steps", C.c_int64),
+                ("accumulate", C.c_int32), ("merged_from", C.c_int32), ("test", NormTestResult)]
+
+
+BATCH_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_void_p,
+                       C.POINTER(LinearDesc), C.c_int32, C.c_void_p)
+
 _lib = None
 
 
@@ -97,11 +125,13 @@ def load_library():
     lib.adloco_merge.argtypes = [vp, C.POINTER(vp), C.POINTER(dbl), C.c_int, sz, C.c_int,
                                  C.POINTER(C.c_int), vp]
     lib.adloco_inner_step.argtypes = [vp, vp, vp, vp, vp, sz, dbl, dbl, dbl, dbl, dbl, dbl, i64, vp]
+    lib.adloco_round.argtypes = [vp, C.POINTER(RoundConfig), C.POINTER(Trainer), C.POINTER(C.c_int),
+                                 C.POINTER(LinearDesc), C.c_int, sz, BATCH_FN, C.POINTER(RoundReport), vp]
     lib.adloco_check_merge.argtypes = [C.POINTER(i64), C.c_int, C.c_int, C.POINTER(C.c_int),
                                        C.POINTER(C.c_int)]
     for name in ("adloco_create", "adloco_destroy", "adloco_set_tuning", "adloco_grad_stats",
                  "adloco_norm_test", "adloco_norm_test_decide", "adloco_switch_mode",
-                 "adloco_outer_step", "adloco_merge", "adloco_check_merge", "adloco_inner_step"):
+                 "adloco_outer_step", "adloco_merge", "adloco_check_merge", "adloco_inner_step", "adloco_round"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -359,3 +389,93 @@ def adloco_check_merge(b_req: Sequence[int], w: int):
     if rc != 0:
         raise AdlocoError(rc, "adloco_check_merge rejected its arguments")
     return [sel[i] for i in range(n.value)]
+
+
+def adloco_round(ctx: Context, cfg: dict, trainers: Sequence[dict], blocks: Sequence[dict], batch_fn,
+                 stream=None):
+    """One outer step of Algorithm 3 (include/adloco.h: adloco_round).
+
+    trainers: dicts {theta_outer, momentum, b_req, acc, per_sample_sqnorm, uid, workers: [{theta,
+    exp_avg, exp_avg_sq, grad, step}]} of GPU tensors; updated in place (b_req, step); the list is
+    reordered / shortened like the C array when trainers merge.
+    blocks: template of the parameter blocks: dicts {d_in, d_out, kind ("linear" | "vector")}.
+    batch_fn(uid, worker, inner_step, micro_step, b, theta_ptr) -> list of dicts {a | x, delta}
+    (GPU tensors [b, T, .]) in block order; the tensors are kept alive until the round returns.
+    Returns the reports of the remaining trainers."""
+    import torch
+    lib = load_library()
+    n_layers = len(blocks)
+    tmpl = (LinearDesc * n_layers)()
+    N = 0
+    for l, b in enumerate(blocks):
+        kind = b.get("kind", "linear")
+        tmpl[l].d_in = 1 if kind == "vector" else b["d_in"]
+        tmpl[l].d_out = b["d_out"]
+        tmpl[l].flags = ADLOCO_KIND_VECTOR if kind == "vector" else 0
+        N += tmpl[l].d_in * tmpl[l].d_out
+    k = len(trainers)
+    arr = (Trainer * k)()
+    worker_arrays = []
+    for i, t in enumerate(trainers):
+        wa = (Worker * len(t["workers"]))()
+        for m, w in enumerate(t["workers"]):
+            wa[m].theta = _dev_ptr(w["theta"], torch.float32, N, "worker theta").value
+            wa[m].exp_avg = _dev_ptr(w["exp_avg"], torch.float32, N, "exp_avg").value
+            wa[m].exp_avg_sq = _dev_ptr(w["exp_avg_sq"], torch.float32, N, "exp_avg_sq").value
+            wa[m].grad = _dev_ptr(w["grad"], torch.float32, N, "grad").value
+            wa[m].step = int(w["step"])
+        worker_arrays.append(wa)
+        arr[i].theta_outer = _dev_ptr(t["theta_outer"], torch.float32, N, "theta_outer").value
+        arr[i].momentum = _dev_ptr(t["momentum"], torch.float32, N, "momentum").value
+        arr[i].workers = wa
+        arr[i].n_workers = len(t["workers"])
+        arr[i].b_req = int(t["b_req"])
+        arr[i].acc = t["acc"].data_ptr()
+        arr[i].per_sample_sqnorm = t["per_sample_sqnorm"].data_ptr()
+        arr[i].user = i
+    c = RoundConfig()
+    for name, _ in RoundConfig._fields_:
+        setattr(c, name, cfg[name])
+    keep_alive = []
+    errors = []
+
+    def trampoline(user, worker, inner_step, micro_step, b, theta, layers, n, stream_ptr):
+        try:
+            t = trainers[int(user or 0)]
+            got = batch_fn(t["uid"], worker, inner_step, micro_step, int(b), theta)
+            keep_alive.append(got)
+            for l in range(n):
+                e = got[l]
+                d = e["delta"]
+                layers[l].delta = d.data_ptr()
+                layers[l].delta_row_stride = d.stride(1)
+                x = e.get("a") if "a" in e else e.get("x")
+                if x is not None:
+                    layers[l].a = x.data_ptr()
+                    layers[l].a_row_stride = x.stride(1)
+            return 0
+        except Exception as exc:      # an exception must not cross the C frame
+            errors.append(exc)
+            return 1
+
+    cb = BATCH_FN(trampoline)
+    kk = C.c_int(k)
+    reports = (RoundReport * k)()
+    rc = lib.adloco_round(ctx._h, C.byref(c), arr, C.byref(kk), tmpl, n_layers, N, cb, reports,
+                          _stream_ptr(stream))
+    if errors:
+        raise errors[0]
+    ctx._check(rc)
+    order = [int(arr[i].user or 0) for i in range(k)]
+    new_list = [trainers[j] for j in order]
+    for i, t in enumerate(new_list):
+        t["b_req"] = int(arr[i].b_req)
+        for m, w in enumerate(t["workers"]):
+            w["step"] = int(arr[i].workers[m].step)
+    trainers[:] = new_list[:kk.value]
+    out = []
+    for i in range(kk.value):
+        r = reports[i]
+        out.append(dict(b_req_used=r.b_req_used, b_micro=r.b_micro, accum_steps=r.accum_steps,
+                        accumulate=r.accumulate, merged_from=r.merged_from, test=r.test.as_dict()))
+    return out

@@ -588,3 +588,77 @@ def test_merge_properties():
     h = orc.merge([np.zeros(2, np.float32), np.full(2, 4, np.float32)], [1, 3])
     np.testing.assert_array_equal(h["x_merge"], np.full(2, 3, np.float32))
     assert h["rep"] == 1
+
+
+# ------------------------------------------------------------------ one round of Algorithm 3
+
+def _round_batch_fn(shapes, T):
+    def fn(uid, worker, h, s, b, theta):
+        out = []
+        for l, (di, do) in enumerate(shapes):
+            seed = 100000 * uid + 1000 * worker + 100 * h + 10 * s + l
+            r = _rng(seed)
+            shared = r.standard_normal((1, T, di + do))
+            x = 0.6 * shared + 0.8 * r.standard_normal((b, T, di + do))
+            out.append((x[:, :, :di].astype(np.float32), (0.1 * x[:, :, di:]).astype(np.float32)))
+        return out
+    return fn
+
+
+def _round_trainers(k, M, N, b_reqs):
+    r = _rng(77)
+    ts = []
+    for i in range(k):
+        th = (0.02 * r.standard_normal(N)).astype(np.float32)
+        ts.append(dict(uid=i, theta_outer=th, momentum=np.zeros(N, np.float32), b_req=b_reqs[i],
+                       workers=[dict(theta=th.copy(), exp_avg=np.zeros(N, np.float32),
+                                     exp_avg_sq=np.zeros(N, np.float32), step=0) for _ in range(M)]))
+    return ts
+
+
+_ROUND_CFG = dict(inner_steps=2, b_max=4, n_switch=2, b_cap=64, eta=0.5, merge_w=0, lr_inner=1e-3,
+                  beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.1, lr_outer=0.7, mu_outer=0.9,
+                  nesterov=1)
+
+
+def test_round_reduces_to_its_parts():
+    # one trainer, one worker, one inner step, no merge: the round is grad_stats -> norm test ->
+    # AdamW step -> outer step on the same batch, each pinned separately above
+    shapes, T = [(5, 3), (3, 2)], 4
+    N = sum(a * b for a, b in shapes)
+    fn = _round_batch_fn(shapes, T)
+    ts = _round_trainers(1, 1, N, [3])
+    th0 = ts[0]["theta_outer"].copy()
+    cfg = dict(_ROUND_CFG, inner_steps=1)
+    rep = orc.round_step(ts, cfg, fn)
+    blocks = fn(0, 0, 0, 0, 3, th0)
+    st = orc.grad_stats(blocks, two_pass=False)
+    g = np.concatenate([G.reshape(-1) for G in st["G"]])
+    o = orc.inner_step(th0, np.zeros(N, np.float32), np.zeros(N, np.float32), g, 1, 1e-3, grad_scale=1 / 3)
+    out = orc.outer_step(th0, [o["theta"]], np.zeros(N, np.float32), 0.7, 0.9, True)
+    np.testing.assert_array_equal(ts[0]["theta_outer"], out["theta_outer"])
+    nt = orc.norm_test(st["S1"], st["S2"], 3, 0.5, 3, 4, 2, 64)
+    assert ts[0]["b_req"] == nt["b_req"] and rep[0]["accumulate"] == 0 and rep[0]["b_micro"] == 3
+
+
+def test_round_merge_switch_and_bookkeeping():
+    shapes, T = [(6, 4)], 3
+    N = 24
+    fn = _round_batch_fn(shapes, T)
+    ts = _round_trainers(3, 2, N, [2, 9, 3])
+    before = [t["theta_outer"].copy() for t in ts]
+    rep = orc.round_step(ts, dict(_ROUND_CFG, merge_w=2), fn)
+    # CheckMerge picks the two smallest requests (trainers 0 and 2); the representative is the one
+    # with the larger request (trainer 2); trainer 1 (b_req 9 > 2 * 4) accumulates 3 micro-batches of 4
+    assert [t["uid"] for t in ts] == [1, 2]
+    assert rep[0]["accumulate"] == 1 and rep[0]["accum_steps"] == 3 and rep[0]["b_micro"] == 4
+    assert rep[1]["accumulate"] == 0 and rep[1]["b_micro"] == 3 and rep[1]["merged_from"] == 1
+    assert all(w["step"] == 2 for t in ts for w in t["workers"])
+    # requested batches never shrink (monotone reading) and respect the ceiling
+    assert ts[0]["b_req"] >= 9 and ts[1]["b_req"] >= 3 and max(t["b_req"] for t in ts) <= 64
+    # with lr_inner = 0 and no decay the workers do not move: Delta = 0 and, from a zero
+    # momentum, the outer model of an unmerged trainer is unchanged
+    ts2 = _round_trainers(3, 2, N, [2, 9, 3])
+    orc.round_step(ts2, dict(_ROUND_CFG, lr_inner=0.0, weight_decay=0.0), fn)
+    for t, b in zip(ts2, before):
+        np.testing.assert_array_equal(t["theta_outer"], b)
