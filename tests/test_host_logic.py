@@ -44,6 +44,10 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(A.LinearDesc) == 56
     assert ctypes.sizeof(A.StatsAcc) == 16
     assert ctypes.sizeof(A.NormTestResult) == 96
+    from paper_2508_18182_amd import binding as b
+    # sizes printed by a C program that includes adloco.h (gcc, x86-64)
+    assert (ctypes.sizeof(b.Worker), ctypes.sizeof(b.Trainer), ctypes.sizeof(b.RoundConfig),
+            ctypes.sizeof(b.RoundReport)) == (40, 64, 104, 128)
 
 
 def test_check_merge_fixture():
