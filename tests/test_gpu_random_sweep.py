@@ -1,0 +1,118 @@
+"""Seeded random sweep of adloco_grad_stats + adloco_norm_test shapes against the oracle: mixed
+block kinds, both dtypes, ragged T, odd and aligned widths, strided rows, micro-batch accumulation.
+Every case is derived from its seed alone, so a failure names its case."""
+import numpy as np
+import pytest
+
+import adloco_synth as synth
+from oracle import adloco_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_2508_18182_amd as A
+    c = A.Context(0)
+    yield c
+    c.close()
+
+
+def _draw_case(seed):
+    r = np.random.Generator(np.random.PCG64(seed))
+    dtype = "bf16" if r.random() < 0.6 else "f32"
+    B = int(r.integers(1, 10))
+    T = int(r.choice([1, 2, 7, 31, 64, 100, 128, 129, 200, 257, 300]))
+    aligned = r.random() < 0.5
+    n_lin = int(r.integers(0, 4))
+    widths = (lambda: int(r.choice([8, 16, 64, 72, 128, 192, 256, 320]))) if aligned else \
+             (lambda: int(r.integers(1, 150)))
+    shapes = [(widths(), widths()) for _ in range(n_lin)]
+    n_vec = int(r.integers(0, 3)) if n_lin else int(r.integers(1, 3))
+    vectors = [(widths(), bool(r.random() < 0.5)) for _ in range(n_vec)]
+    tables = [(int(r.integers(2, 40)), widths())] if r.random() < 0.4 else []
+    micro = int(r.integers(1, 4)) if r.random() < 0.4 else 1
+    return dict(dtype=dtype, B=B, T=T, shapes=shapes, vectors=vectors, tables=tables, micro=micro,
+                rho=float(r.choice([0.0, 0.3, 0.7])))
+
+
+def _host_blocks(case, seed, k):
+    lin = synth.custom_grad_stats_inputs(seed + 17 * k, case["shapes"], case["B"], case["T"], case["dtype"],
+                                         std_delta=0.2, rho=case["rho"]) if case["shapes"] else []
+    aux = synth.vector_table_inputs(seed + 17 * k + 5, case["B"], case["T"], case["dtype"], case["vectors"],
+                                    case["tables"], std_delta=0.2, rho=case["rho"])
+    return list(lin) + list(aux)
+
+
+def _oracle_entry(e):
+    kind = e.get("kind", "linear")
+    if kind == "vector":
+        return ("rowsum", e["x"], e["delta"])
+    if kind == "embed":
+        return ("embed", e["ids"], e["delta"])
+    return (e["a"], e["delta"])
+
+
+@pytest.mark.parametrize("seed", list(range(9100, 9140)))
+def test_random_case(ctx, seed):
+    import torch
+    import paper_2508_18182_amd as A
+    from gpu_util import to_dev, new_acc, read_acc, rel_err, DEV
+    case = _draw_case(seed)
+    B, T = case["B"], case["T"]
+    dt = A.ADLOCO_BF16 if case["dtype"] == "bf16" else A.ADLOCO_F32
+    tol = 2e-3 if case["dtype"] == "bf16" else 1e-4
+    mbs = [_host_blocks(case, seed, k) for k in range(case["micro"])]
+    want = orc.grad_stats(orc.concat_micro_batches([[_oracle_entry(e) for e in mb] for mb in mbs]),
+                          two_pass=False)
+    # gradient sums persist across the micro-batches; table gradients come from the oracle
+    grads = []
+    for l, e in enumerate(mbs[0]):
+        kind = e.get("kind", "linear")
+        if kind == "linear":
+            grads.append(torch.full((e["d_out"], e["d_in"]), float("nan"), device=DEV))
+        elif kind == "vector":
+            grads.append(torch.full((e["d"],), float("nan"), device=DEV))
+        else:
+            g = np.zeros((e["vocab"], e["d"]), dtype=np.float32)
+            g[want["embed_rows"][l]] = want["G"][l].astype(np.float32)
+            grads.append(torch.from_numpy(g).to(DEV))
+    acc = new_acc()
+    ps = torch.zeros(B, device=DEV)
+    per_layer_tot = np.zeros((len(mbs[0]), B * case["micro"]))
+    layers = None
+    for k, mb in enumerate(mbs):
+        layers = []
+        for l, e in enumerate(mb):
+            kind = e.get("kind", "linear")
+            if kind == "linear":
+                layers.append(dict(a=to_dev(e["a"]), delta=to_dev(e["delta"]), grad_sum=grads[l]))
+            elif kind == "vector":
+                layers.append(dict(kind="vector", x=None if e["x"] is None else to_dev(e["x"]),
+                                   delta=to_dev(e["delta"]), grad_sum=grads[l]))
+            else:
+                layers.append(dict(kind="embed", ids=torch.from_numpy(e["ids"]).to(DEV), vocab=e["vocab"],
+                                   delta=to_dev(e["delta"]), grad_sum=grads[l]))
+        pl = torch.zeros(len(layers), B, device=DEV)
+        A.adloco_grad_stats(ctx, layers, B, T, dt, ps, pl, acc, A.ADLOCO_ACCUMULATE if k else 0)
+        torch.cuda.synchronize()
+        per_layer_tot[:, k * B:(k + 1) * B] = pl.cpu().numpy()
+    S1, n = read_acc(acc)
+    assert n == B * case["micro"], case
+    floor = 1e-30 + 1e-6 * float(np.max(want["n_layer_sample"]))
+    err = np.abs(per_layer_tot - want["n_layer_sample"]) / np.maximum(want["n_layer_sample"], floor)
+    assert float(err.max()) < tol, (case, float(err.max()))
+    assert rel_err(S1, want["S1"]) < tol or want["S1"] == 0.0, case
+    res = A.adloco_norm_test(ctx, layers, acc, 0.4, max(1, n), 8, 2, 512)
+    assert res["S2"] == pytest.approx(want["S2"], rel=tol, abs=1e-30), case
+    ref = orc.norm_test(want["S1"], want["S2"], n, 0.4, max(1, n), 8, 2, 512)
+    if n >= 2 and np.isfinite(ref["stat"]) and ref["stat"] > 0:
+        # S1 - S2/B cancels when the samples are strongly correlated: the statistic inherits the
+        # tolerance of S1 and S2 amplified by S1 / (S1 - S2/B)
+        amp = want["S1"] / max(want["S1"] - want["S2"] / n, 1e-300)
+        assert res["stat"] == pytest.approx(ref["stat"], rel=min(0.5, 3 * tol * amp)), case
+        slack = 3 * tol * amp * ref["stat"]
+        near_cut = (abs(ref["stat"] - round(ref["stat"])) < slack or abs(ref["stat"] - max(1, n)) < slack)
+        if not near_cut:
+            for key in ("b_req", "test_passed", "accumulate", "accum_steps", "b_micro"):
+                assert res[key] == ref[key], (key, case)
