@@ -269,6 +269,22 @@ def main():
             A.adloco_outer_step(ctx, theta, insts, mom, ocfg["lr"], ocfg["mu"], True)
             A.adloco_merge(ctx, insts, [float(b + k) for k, b in enumerate(b_req)])
 
+    # PyTorch's plain device copy of 1 GiB, for scale (a read + write stream on this machine)
+    copy_GBps = None
+    if args.only in ("all", "outer") and args.config == 2:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_GBps = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -372,6 +388,10 @@ def main():
         "outer_step_GBps": r_outer["achieved"] if r_outer else None,
         "merge_GBps": r_merge["achieved"] if r_merge else None,
         "norm_test": {k: last.get(k) for k in ("stat", "b_req", "test_passed", "accumulate")},
+        "hbm_copy_reference": ({"GBps": copy_GBps, "how": "PyTorch device copy of 1 GiB fp32 (read + write bytes), for scale",
+                              "outer_step_vs_copy": (r_outer["achieved"] / copy_GBps) if r_outer else None,
+                              "merge_vs_copy": (r_merge["achieved"] / copy_GBps) if r_merge else None}
+                             if copy_GBps else None),
     }
     if not args.no_next_rows:
         out["next_rows"] = {}
