@@ -20,7 +20,9 @@ token rows; permutation and rotation invariance; element-by-element brute force;
 autograd of a bias-free linear layer, and of a linear bias, a LayerNorm gain and bias and an
 embedding table for the vector and table blocks (plus their one-token / all-distinct /
 all-equal-id closed forms); numpy's var(ddof=1) over the stacked per-sample
-gradients; iid-noise expectation B/eta^2; torch.optim.AdamW and the first-step / zero-gradient
+gradients; iid-noise expectation B/eta^2; for the inner-product tests hand-worked vectors,
+sum_i <g_i, G> = ||G||^2, numpy's var, the explicit residual vectors against the scalar form and
+the collinear / orthogonal special cases; torch.optim.AdamW and the first-step / zero-gradient
 closed forms for the inner step; LocalSGD averaging (Section 3.1) and
 torch.optim.SGD(nesterov=True) for the outer step; convexity / identity cases for the
 merge; Algorithm 1's branches enumerated by hand.
@@ -235,6 +237,97 @@ def norm_test(S1: float, S2: float, B: int, eta: float, b_cur: int, b_max: int,
         b_req = min(ceiling, max(b_req, 1))
     res["b_req"] = int(b_req)
     res.update(switch_mode(int(b_req), int(b_max), int(n_switch)))
+    return res
+
+
+# --------------------------------------------------------------------------------------
+# Inner-product test and augmented inner-product test (Section 3.3.2)
+# --------------------------------------------------------------------------------------
+
+def inner_products(layers, G=None) -> np.ndarray:
+    """c_i = <g_i, G> for every sample, with G = sum_j g_j the gradient sum of the batch
+    (B times eq. 1's g_k) unless another list G of per-block sums is given (an accumulated batch:
+    G over all micro-batches).  Per-sample gradients are formed explicitly, block by block."""
+    B = int(np.asarray(layers[0][-1]).shape[0])
+    rows = {l: np.unique(np.asarray(e[1])) for l, e in enumerate(layers) if _layer_kind(e) == "embed"}
+    if G is None:
+        G = grad_stats(layers, two_pass=False)["G"]
+    c = np.zeros(B, dtype=np.float64)
+    for l, entry in enumerate(layers):
+        for i in range(B):
+            g = _entry_sample_gradient(entry, i, rows.get(l))
+            c[i] += float(np.sum(g * G[l]))
+    return c
+
+
+def explicit_sample_gradients(layers) -> np.ndarray:
+    """All per-sample gradients as rows of one [B, P] fp64 matrix (blocks concatenated; for an
+    embedding table only the rows whose id occurs in the batch).  Small shapes only."""
+    B = int(np.asarray(layers[0][-1]).shape[0])
+    rows = {l: np.unique(np.asarray(e[1])) for l, e in enumerate(layers) if _layer_kind(e) == "embed"}
+    out = []
+    for i in range(B):
+        out.append(np.concatenate([_entry_sample_gradient(e, i, rows.get(l)).reshape(-1)
+                                   for l, e in enumerate(layers)]))
+    return np.stack(out)
+
+
+def inner_product_test(n_sample, c, S2: float, vartheta: float, nu: float, b_cur: int, b_max: int,
+                       n_switch: int = 2, b_cap: int = 0, g_rows=None) -> dict:
+    """Section 3.3.2.  With g_k = G / B the batch gradient, c_i = <g_i, G>:
+      inner-product test:  b_ip  = ceil( Var_i(<g_i, g_k>) / (vartheta^2 ||g_k||^4) )
+      augmented test:      b_aug = ceil( max{ b_ip, Var_i(g_i - (<g_i, g_k>/||g_k||^2) g_k)
+                                                    / (nu^2 ||g_k||^2) } )
+    Var_i is the sample variance over the batch with the 1/(B-1) normalisation (for a vector:
+    the trace of the sample covariance), the convention of the norm test.  If g_rows (the explicit
+    [B, P] matrix of per-sample gradients) is given, the augmented variance is formed from the
+    explicit residual vectors; otherwise from the scalars, sum_i (||g_i||^2 - <g_i,g_k>^2 /
+    ||g_k||^2) / (B-1), which is the same number because the residuals average to zero.
+    Followed by the monotone clamp, ceiling and SwitchMode of the norm test."""
+    c = np.asarray(c, dtype=np.float64)
+    n_sample = np.asarray(n_sample, dtype=np.float64)
+    B = len(c)
+    ceiling = b_cap if b_cap > 0 else INT64_MAX
+    res = dict(S2=S2, b_cur=int(b_cur), stat_undefined=0)
+    gk2 = S2 / (float(B) * float(B))
+    res["batch_grad_sqnorm"] = gk2
+    if B < 2:
+        res.update(var_ip=float("nan"), stat_ip=float("nan"), var_aug=float("nan"),
+                   stat_aug=float("nan"), stat_undefined=1)
+        b_ip = b_aug = min(ceiling, max(int(b_cur), 2))
+    else:
+        ip = c / B                                     # <g_i, g_k>
+        var_ip = float(np.sum((ip - ip.mean()) ** 2) / (B - 1))
+        if g_rows is not None:
+            gk = g_rows.sum(axis=0) / B
+            resid = g_rows - np.outer(ip / gk2, gk)
+            var_aug = float(np.sum((resid - resid.mean(axis=0)) ** 2) / (B - 1))
+        else:
+            var_aug = float(np.sum(n_sample - ip * ip / gk2) / (B - 1)) if gk2 > 0 else float("inf")
+        res.update(var_ip=var_ip, var_aug=var_aug)
+
+        def ratio(num, den):
+            if den > 0.0:
+                return num / den
+            return float("inf") if num > 0.0 else 0.0
+
+        stat_ip = ratio(var_ip, vartheta * vartheta * gk2 * gk2)
+        stat_aug = ratio(var_aug, nu * nu * gk2)
+        res.update(stat_ip=stat_ip, stat_aug=stat_aug)
+
+        def to_batch(stat):
+            if math.isinf(stat) or stat >= float(ceiling):
+                return ceiling
+            return int(math.ceil(stat))
+
+        b_ip_raw = to_batch(stat_ip)
+        b_aug_raw = to_batch(max(float(b_ip_raw), stat_aug))
+        b_ip = min(ceiling, max(int(b_cur), b_ip_raw, 1))
+        b_aug = min(ceiling, max(int(b_cur), b_aug_raw, 1))
+    res["b_req_ip"] = int(b_ip)
+    res["b_req_aug"] = int(b_aug)
+    res["switch_ip"] = switch_mode(int(b_ip), int(b_max), int(n_switch))
+    res["switch_aug"] = switch_mode(int(b_aug), int(b_max), int(n_switch))
     return res
 
 

@@ -447,6 +447,92 @@ def _outer_case(seed=60, N=257, M=3):
     return th, ins, mom
 
 
+def test_inner_product_hand_cases():
+    n = 0
+    for ln in _lines("inner_product_hand_cases.txt"):
+        lhs, want = ln.split("->")
+        rows, vth, nu = lhs.split(";")
+        g = np.array([[float(v) for v in r.split(",")] for r in rows.split("|")])
+        B = len(g)
+        G = g.sum(axis=0)
+        c = g @ G
+        n_s = (g ** 2).sum(axis=1)
+        S2 = float(G @ G)
+        w = [float(v) for v in want.split()]
+        for rows_arg in (None, g):
+            res = orc.inner_product_test(n_s, c, S2, float(vth), float(nu), B, 64, g_rows=rows_arg)
+            assert res["var_ip"] == pytest.approx(w[0], abs=1e-12)
+            assert res["var_aug"] == pytest.approx(w[1], abs=1e-12)
+            assert res["stat_ip"] == pytest.approx(w[2], abs=1e-12)
+            assert res["stat_aug"] == pytest.approx(w[3], abs=1e-12)
+        n += 1
+    assert n >= 3
+
+
+def test_inner_products_identities():
+    r = _rng(80)
+    B, T = 5, 4
+    a = r.standard_normal((B, T, 6))
+    d = r.standard_normal((B, T, 3))
+    ids = r.integers(0, 4, size=(B, T))
+    blocks = [(a, d), ("rowsum", None, d), ("rowsum", d * 0.5, d), ("embed", ids, d)]
+    st = orc.grad_stats(blocks, two_pass=False)
+    c = orc.inner_products(blocks)
+    rows = orc.explicit_sample_gradients(blocks)
+    G = rows.sum(axis=0)
+    # c_i is the dot product of the explicit rows with their sum; the c_i add up to ||G||^2 = S2;
+    # the rows reproduce the per-sample norms
+    np.testing.assert_allclose(c, rows @ G, rtol=1e-12)
+    assert c.sum() == pytest.approx(st["S2"], rel=1e-12)
+    np.testing.assert_allclose((rows ** 2).sum(axis=1), st["n_sample"], rtol=1e-12)
+    # numpy's var over <g_i, g_k>, and the residual vectors against the scalar form
+    res_s = orc.inner_product_test(st["n_sample"], c, st["S2"], 0.3, 0.3, B, 64)
+    res_v = orc.inner_product_test(st["n_sample"], c, st["S2"], 0.3, 0.3, B, 64, g_rows=rows)
+    assert res_s["var_ip"] == pytest.approx(np.var(rows @ (G / B), ddof=1), rel=1e-12)
+    assert res_s["var_aug"] == pytest.approx(res_v["var_aug"], rel=1e-10)
+    gk = G / B
+    resid = rows - np.outer((rows @ gk) / (gk @ gk), gk)
+    np.testing.assert_allclose(resid.mean(axis=0), 0.0, atol=1e-12)      # residuals average to zero
+    np.testing.assert_allclose(resid @ gk, 0.0, atol=1e-10)              # and are orthogonal to g_k
+    assert res_s["var_aug"] == pytest.approx(np.var(resid, axis=0, ddof=1).sum(), rel=1e-10)
+    # an accumulated batch: c against the sum over both halves
+    half = [tuple(x[:2] if isinstance(x, np.ndarray) else x for x in e) for e in blocks]
+    c_half = orc.inner_products(half, G=st["G"])
+    np.testing.assert_allclose(c_half, c[:2], rtol=1e-12)
+
+
+def test_inner_product_special_cases():
+    # collinear gradients g_i = s_i * u: residuals vanish, var_aug = 0; <g_i,g_k> = s_i * mean(s)
+    u = np.array([3.0, 4.0])
+    sc = np.array([1.0, 2.0, 4.0, 5.0])
+    g = np.outer(sc, u)
+    G = g.sum(axis=0)
+    res = orc.inner_product_test((g ** 2).sum(axis=1), g @ G, float(G @ G), 0.5, 0.3, 4, 64, g_rows=g)
+    assert res["var_aug"] == pytest.approx(0.0, abs=1e-12)
+    assert res["var_ip"] == pytest.approx(np.var(sc * sc.mean() * 25.0, ddof=1), rel=1e-12)
+    # identical samples: both variances vanish, requested batches stay at b_cur
+    g = np.tile(u, (3, 1))
+    G = g.sum(axis=0)
+    res = orc.inner_product_test((g ** 2).sum(axis=1), g @ G, float(G @ G), 0.01, 0.3, 7, 64)
+    assert res["stat_ip"] == 0.0 and res["stat_aug"] == pytest.approx(0.0, abs=1e-12)
+    assert res["b_req_ip"] == 7 and res["b_req_aug"] == 7
+    # the augmented request is never below the inner-product request; scaling all gradients by s
+    # leaves both statistics unchanged
+    r = _rng(81)
+    g = r.standard_normal((6, 5))
+    G = g.sum(axis=0)
+    a = orc.inner_product_test((g ** 2).sum(axis=1), g @ G, float(G @ G), 0.2, 0.3, 2, 64)
+    g2 = 7.0 * g
+    G2 = g2.sum(axis=0)
+    b = orc.inner_product_test((g2 ** 2).sum(axis=1), g2 @ G2, float(G2 @ G2), 0.2, 0.3, 2, 64)
+    assert a["b_req_aug"] >= a["b_req_ip"]
+    assert a["stat_ip"] == pytest.approx(b["stat_ip"], rel=1e-12)
+    assert a["stat_aug"] == pytest.approx(b["stat_aug"], rel=1e-12)
+    # one sample: undefined, ask for two
+    one = orc.inner_product_test([1.0], [1.0], 1.0, 0.2, 0.3, 1, 64)
+    assert one["stat_undefined"] == 1 and one["b_req_ip"] == 2 and one["b_req_aug"] == 2
+
+
 def test_inner_step_matches_torch_adamw():
     # library route: several steps of torch.optim.AdamW in float64
     import torch
