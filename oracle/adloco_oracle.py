@@ -244,12 +244,16 @@ def norm_test(S1: float, S2: float, B: int, eta: float, b_cur: int, b_max: int,
 # Inner-product test and augmented inner-product test (Section 3.3.2)
 # --------------------------------------------------------------------------------------
 
-def inner_products(layers, G=None) -> np.ndarray:
+def inner_products(layers, G=None, embed_rows=None) -> np.ndarray:
     """c_i = <g_i, G> for every sample, with G = sum_j g_j the gradient sum of the batch
     (B times eq. 1's g_k) unless another list G of per-block sums is given (an accumulated batch:
-    G over all micro-batches).  Per-sample gradients are formed explicitly, block by block."""
+    G over all micro-batches; embed_rows then names, per embedding block, the table rows that the
+    rows of its G stand for, as grad_stats returns them).  Per-sample gradients are formed
+    explicitly, block by block."""
     B = int(np.asarray(layers[0][-1]).shape[0])
     rows = {l: np.unique(np.asarray(e[1])) for l, e in enumerate(layers) if _layer_kind(e) == "embed"}
+    if embed_rows is not None:
+        rows = {l: np.asarray(embed_rows[l]) for l in rows}
     if G is None:
         G = grad_stats(layers, two_pass=False)["G"]
     c = np.zeros(B, dtype=np.float64)
@@ -283,6 +287,8 @@ def inner_product_test(n_sample, c, S2: float, vartheta: float, nu: float, b_cur
     [B, P] matrix of per-sample gradients) is given, the augmented variance is formed from the
     explicit residual vectors; otherwise from the scalars, sum_i (||g_i||^2 - <g_i,g_k>^2 /
     ||g_k||^2) / (B-1), which is the same number because the residuals average to zero.
+    Where g_k = 0 the projection has no direction: the residual is then g_i itself (and both
+    statistics are +inf unless their variance is zero too, as in the norm test).
     Followed by the monotone clamp, ceiling and SwitchMode of the norm test."""
     c = np.asarray(c, dtype=np.float64)
     n_sample = np.asarray(n_sample, dtype=np.float64)
@@ -298,12 +304,14 @@ def inner_product_test(n_sample, c, S2: float, vartheta: float, nu: float, b_cur
     else:
         ip = c / B                                     # <g_i, g_k>
         var_ip = float(np.sum((ip - ip.mean()) ** 2) / (B - 1))
+        # g_k = 0: the component along g_k is taken to be zero, the residual is g_i itself
+        coef = ip / gk2 if gk2 > 0 else np.zeros_like(ip)
         if g_rows is not None:
             gk = g_rows.sum(axis=0) / B
-            resid = g_rows - np.outer(ip / gk2, gk)
+            resid = g_rows - np.outer(coef, gk)
             var_aug = float(np.sum((resid - resid.mean(axis=0)) ** 2) / (B - 1))
         else:
-            var_aug = float(np.sum(n_sample - ip * ip / gk2) / (B - 1)) if gk2 > 0 else float("inf")
+            var_aug = float(np.sum(n_sample - ip * coef) / (B - 1))
         res.update(var_ip=var_ip, var_aug=var_aug)
 
         def ratio(num, den):

@@ -497,8 +497,18 @@ def test_inner_products_identities():
     assert res_s["var_aug"] == pytest.approx(np.var(resid, axis=0, ddof=1).sum(), rel=1e-10)
     # an accumulated batch: c against the sum over both halves
     half = [tuple(x[:2] if isinstance(x, np.ndarray) else x for x in e) for e in blocks]
-    c_half = orc.inner_products(half, G=st["G"])
+    c_half = orc.inner_products(half, G=st["G"], embed_rows=st["embed_rows"])
     np.testing.assert_allclose(c_half, c[:2], rtol=1e-12)
+    # ... also when a micro-batch touches fewer table rows than the whole batch
+    ids2 = np.array([[0, 0, 1, 1], [5, 5, 2, 2], [7, 3, 3, 3], [1, 1, 1, 1], [6, 6, 6, 0]])
+    blocks2 = [(a, d), ("embed", ids2, d)]
+    st2 = orc.grad_stats(blocks2, two_pass=False)
+    c2 = orc.inner_products(blocks2)
+    np.testing.assert_allclose(c2, orc.explicit_sample_gradients(blocks2) @
+                               orc.explicit_sample_gradients(blocks2).sum(axis=0), rtol=1e-12)
+    tail = [(a[3:], d[3:]), ("embed", ids2[3:], d[3:])]
+    np.testing.assert_allclose(orc.inner_products(tail, G=st2["G"], embed_rows=st2["embed_rows"]),
+                               c2[3:], rtol=1e-12)
 
 
 def test_inner_product_special_cases():
@@ -516,6 +526,15 @@ def test_inner_product_special_cases():
     res = orc.inner_product_test((g ** 2).sum(axis=1), g @ G, float(G @ G), 0.01, 0.3, 7, 64)
     assert res["stat_ip"] == 0.0 and res["stat_aug"] == pytest.approx(0.0, abs=1e-12)
     assert res["b_req_ip"] == 7 and res["b_req_aug"] == 7
+    # gradients that cancel (g_k = 0): nothing to project on, the residuals are the g_i; both
+    # statistics are unbounded, the requests go to the ceiling
+    g = np.array([[1.0, 2.0], [-1.0, -2.0], [2.0, -1.0], [-2.0, 1.0]])
+    for rows_arg in (None, g):
+        res = orc.inner_product_test((g ** 2).sum(axis=1), g @ g.sum(axis=0), 0.0, 0.01, 0.3, 4, 64,
+                                     b_cap=1000, g_rows=rows_arg)
+        assert res["var_aug"] == pytest.approx(20.0 / 3.0, rel=1e-12)
+        assert res["var_ip"] == 0.0 and res["stat_ip"] == 0.0 and math.isinf(res["stat_aug"])
+        assert res["b_req_ip"] == 4 and res["b_req_aug"] == 1000
     # the augmented request is never below the inner-product request; scaling all gradients by s
     # leaves both statistics unchanged
     r = _rng(81)
