@@ -75,7 +75,7 @@ const char* adloco_last_error(const adloco_ctx* ctx);
 int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
 
 /* Measurement aid.  After adloco_set_tuning(ctx, "profile", 1) every launch of the named
- * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table", "inner_step") is bracketed by HIP
+ * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table", "inner_step", "inner_products") is bracketed by HIP
  * events on the call's stream.  adloco_profile_read waits for the recorded events of that
  * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
 int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
@@ -203,6 +203,62 @@ int adloco_switch_mode(int64_t b_req, int64_t b_max, int32_t n_switch,
 int adloco_outer_step(adloco_ctx* ctx, float* theta_outer, float* const* theta_inst, int M,
                       size_t N, float* momentum, double lr, double mu, int nesterov,
                       uint32_t flags, float* pseudo_grad_out, void* stream);
+
+/* ------------------------------------------------------------------------------------ *
+ * Inner-product test and augmented inner-product test (Section 3.3.2), the two alternatives to
+ * the norm test.  Both need, per sample, the inner product with the batch gradient
+ *   c_i = <g_i, G>,  G = sum_j g_j  (the grad_sum buffers; <g_i, g_k> = c_i / B),
+ * which can only be formed once G is complete: call adloco_inner_products after
+ * adloco_grad_stats has seen the whole (accumulated) batch, once per micro-batch whose a and
+ * delta are still (or again) available, with ADLOCO_ACCUMULATE from the second call on.
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  double  sum_ip;      /* sum_i c_i  (equals ||G||^2 once every sample has been seen)           */
+  double  sum_ip_sq;   /* sum_i c_i^2                                                           */
+  int64_t n_samples;
+  int64_t reserved;
+} adloco_ip_acc;       /* device memory, caller-owned, 32 bytes, 8-byte aligned                 */
+
+/* adloco_inner_products: c_i for the B samples of one micro-batch against the grad_sum buffers
+ * of the descriptors (every kind; all grad_sum non-NULL, only read).  For 16-byte aligned bf16
+ * linear layers with T % 32 == 0 the 256 x 256 tiles of each per-sample gradient delta_i^T a_i
+ * are formed by MFMA in registers and reduced against the fp32 tile of G on the spot; other
+ * blocks take a plain path.
+ *   per_sample_ip      device [B] fp32, overwritten: c_i
+ *   per_sample_sqnorm  device [B] fp32 or NULL, overwritten: ||g_i||^2 from the explicit per-sample
+ *                      gradients (a second route to adloco_grad_stats' Gram result)
+ *   acc                device accumulator; reset unless ADLOCO_ACCUMULATE */
+int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers, int B,
+                          int T, int dtype, float* per_sample_ip, float* per_sample_sqnorm,
+                          adloco_ip_acc* acc, uint32_t flags, void* stream);
+
+typedef struct {
+  double  S1, S2, batch_grad_sqnorm;   /* as in adloco_norm_test_result                          */
+  double  var_ip;      /* Var_i <g_i, g_k>, 1/(B-1)                                              */
+  double  stat_ip;     /* var_ip / (vartheta^2 ||g_k||^4)                                        */
+  double  var_aug;     /* Var_i (g_i - <g_i,g_k>/||g_k||^2 g_k) = sum_i (||g_i||^2 -
+                          <g_i,g_k>^2/||g_k||^2) / (B-1): the residuals average to zero          */
+  double  stat_aug;    /* var_aug / (nu^2 ||g_k||^2)                                             */
+  int64_t n_samples, b_cur;
+  int64_t b_req_ip;    /* min(b_cap, max(b_cur, ceil(stat_ip), 1))                               */
+  int64_t b_req_aug;   /* min(b_cap, max(b_cur, ceil(max(ceil(stat_ip), stat_aug)), 1))          */
+  int64_t b_micro_ip, accum_steps_ip, b_micro_aug, accum_steps_aug;   /* SwitchMode of each      */
+  int32_t accumulate_ip, accumulate_aug;
+  int32_t stat_undefined;   /* 1 iff B < 2: both requests are max(b_cur, 2)                      */
+  int32_t reserved;
+} adloco_ip_test_result;
+
+/* adloco_inner_product_test: S2 on the device as in adloco_norm_test, then both batch rules of
+ * Section 3.3.2 and SwitchMode on the host in fp64.  vartheta > 0, nu > 0 (the paper's table:
+ * 0.01 and 0.3).  Waits for `stream`.  adloco_inner_product_decide is the host-only half. */
+int adloco_inner_product_test(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
+                              const adloco_stats_acc* acc, const adloco_ip_acc* ip, double vartheta,
+                              double nu, int64_t b_cur, int64_t b_max, int32_t n_switch,
+                              int64_t b_cap, adloco_ip_test_result* out, void* stream);
+int adloco_inner_product_decide(double S1, double S2, double sum_ip, double sum_ip_sq,
+                                int64_t n_samples, double vartheta, double nu, int64_t b_cur,
+                                int64_t b_max, int32_t n_switch, int64_t b_cap,
+                                adloco_ip_test_result* out);
 
 /* adloco_inner_step: Algorithm 3's  x_m <- InnerOpt(x_m, g)  with InnerOpt = AdamW, the inner
  * optimizer of Section 6.1 (learning rate 4e-4, weight decay 0.1), one fused pass:

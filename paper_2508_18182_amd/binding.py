@@ -54,6 +54,25 @@ class NormTestResult(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
+class IpAcc(C.Structure):
+    _fields_ = [("sum_ip", C.c_double), ("sum_ip_sq", C.c_double), ("n_samples", C.c_int64),
+                ("reserved", C.c_int64)]
+
+
+class IpTestResult(C.Structure):
+    _fields_ = [("S1", C.c_double), ("S2", C.c_double), ("batch_grad_sqnorm", C.c_double),
+                ("var_ip", C.c_double), ("stat_ip", C.c_double), ("var_aug", C.c_double),
+                ("stat_aug", C.c_double), ("n_samples", C.c_int64), ("b_cur", C.c_int64),
+                ("b_req_ip", C.c_int64), ("b_req_aug", C.c_int64), ("b_micro_ip", C.c_int64),
+                ("accum_steps_ip", C.c_int64), ("b_micro_aug", C.c_int64),
+                ("accum_steps_aug", C.c_int64), ("accumulate_ip", C.c_int32),
+                ("accumulate_aug", C.c_int32), ("stat_undefined", C.c_int32),
+                ("reserved", C.c_int32)]
+
+    def as_dict(self) -> dict:
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
 class Worker(C.Structure):
     _fields_ = [("theta", C.c_void_p), ("exp_avg", C.c_void_p), ("exp_avg_sq", C.c_void_p),
                 ("grad", C.c_void_p), ("step", C.c_int64)]
@@ -127,11 +146,18 @@ def load_library():
     lib.adloco_inner_step.argtypes = [vp, vp, vp, vp, vp, sz, dbl, dbl, dbl, dbl, dbl, dbl, i64, vp]
     lib.adloco_round.argtypes = [vp, C.POINTER(RoundConfig), C.POINTER(Trainer), C.POINTER(C.c_int),
                                  C.POINTER(LinearDesc), C.c_int, sz, BATCH_FN, C.POINTER(RoundReport), vp]
+    lib.adloco_inner_products.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, C.c_int, C.c_int,
+                                          C.c_int, vp, vp, vp, u32, vp]
+    lib.adloco_inner_product_test.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, vp, vp, dbl, dbl,
+                                              i64, i64, i32, i64, C.POINTER(IpTestResult), vp]
+    lib.adloco_inner_product_decide.argtypes = [dbl, dbl, dbl, dbl, i64, dbl, dbl, i64, i64, i32,
+                                                i64, C.POINTER(IpTestResult)]
     lib.adloco_check_merge.argtypes = [C.POINTER(i64), C.c_int, C.c_int, C.POINTER(C.c_int),
                                        C.POINTER(C.c_int)]
     for name in ("adloco_create", "adloco_destroy", "adloco_set_tuning", "adloco_grad_stats",
                  "adloco_norm_test", "adloco_norm_test_decide", "adloco_switch_mode",
-                 "adloco_outer_step", "adloco_merge", "adloco_check_merge", "adloco_inner_step", "adloco_round"):
+                 "adloco_outer_step", "adloco_merge", "adloco_check_merge", "adloco_inner_step", "adloco_round",
+                 "adloco_inner_products", "adloco_inner_product_test", "adloco_inner_product_decide"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -285,28 +311,69 @@ def adloco_grad_stats(ctx: Context, layers: Sequence[dict], B: int, T: int, dtyp
                                                 _stream_ptr(stream)))
 
 
+def _grad_sum_descs(layers):
+    """Descriptors that carry only grad_sum, its shape and the block kind."""
+    arr = (LinearDesc * len(layers))()
+    for i, l in enumerate(layers):
+        g = l["grad_sum"]
+        _dev_ptr(g, None, None, f"layer {i} grad_sum")
+        arr[i].grad_sum = g.data_ptr()
+        kind = l.get("kind", "linear")
+        if kind == "vector":
+            arr[i].d_out, arr[i].d_in = g.shape[0], 1
+            arr[i].flags = ADLOCO_KIND_VECTOR | (ADLOCO_GRAD_PROVIDED if l.get("provided") else 0)
+        elif kind == "embed":
+            arr[i].d_in, arr[i].d_out = g.shape
+            arr[i].flags = ADLOCO_KIND_EMBED | ADLOCO_GRAD_PROVIDED
+        else:
+            arr[i].d_out, arr[i].d_in = g.shape
+            arr[i].flags = ADLOCO_GRAD_PROVIDED if l.get("provided") else 0
+    return arr
+
+
+def adloco_inner_products(ctx: Context, layers: Sequence[dict], B: int, T: int, dtype: int,
+                          per_sample_ip, per_sample_sqnorm, acc, flags: int = 0, stream=None,
+                          descs=None):
+    """c_i = <g_i, G> of one micro-batch against the (complete) grad_sum buffers.  acc: GPU tensor
+    of 32 bytes (e.g. torch.zeros(4, dtype=torch.float64)) holding an adloco_ip_acc."""
+    import torch
+    arr = descs if descs is not None else make_layer_descs(layers, B, T, dtype)
+    ip = _dev_ptr(per_sample_ip, torch.float32, B, "per_sample_ip")
+    sq = _dev_ptr(per_sample_sqnorm, torch.float32, B, "per_sample_sqnorm")
+    if acc is None or not acc.is_cuda or acc.numel() * acc.element_size() < 32:
+        raise ValueError("acc must be a GPU tensor of at least 32 bytes")
+    ctx._check(load_library().adloco_inner_products(ctx._h, arr, len(arr), B, T, dtype, ip, sq,
+                                                    C.c_void_p(acc.data_ptr()), flags,
+                                                    _stream_ptr(stream)))
+
+
+def adloco_inner_product_test(ctx: Context, layers, acc, ip_acc, vartheta: float, nu: float,
+                              b_cur: int, b_max: int, n_switch: int = 2, b_cap: int = 0,
+                              stream=None, descs=None) -> dict:
+    arr = descs if descs is not None else _grad_sum_descs(layers)
+    res = IpTestResult()
+    ctx._check(load_library().adloco_inner_product_test(
+        ctx._h, arr, len(arr), C.c_void_p(acc.data_ptr()), C.c_void_p(ip_acc.data_ptr()), vartheta,
+        nu, b_cur, b_max, n_switch, b_cap, C.byref(res), _stream_ptr(stream)))
+    return res.as_dict()
+
+
+def adloco_inner_product_decide(S1: float, S2: float, sum_ip: float, sum_ip_sq: float,
+                                n_samples: int, vartheta: float, nu: float, b_cur: int, b_max: int,
+                                n_switch: int = 2, b_cap: int = 0) -> dict:
+    res = IpTestResult()
+    rc = load_library().adloco_inner_product_decide(S1, S2, sum_ip, sum_ip_sq, n_samples, vartheta,
+                                                    nu, b_cur, b_max, n_switch, b_cap, C.byref(res))
+    if rc != 0:
+        raise AdlocoError(rc, "adloco_inner_product_decide rejected its arguments")
+    return res.as_dict()
+
+
 def adloco_norm_test(ctx: Context, layers, acc, eta: float, b_cur: int, b_max: int,
                      n_switch: int = 2, b_cap: int = 0, flags: int = 0, stream=None,
                      descs=None) -> dict:
     """layers: dicts with grad_sum (and d_in/d_out taken from its shape), or descs."""
-    if descs is None:
-        arr = (LinearDesc * len(layers))()
-        for i, l in enumerate(layers):
-            g = l["grad_sum"]
-            _dev_ptr(g, None, None, f"layer {i} grad_sum")
-            arr[i].grad_sum = g.data_ptr()
-            kind = l.get("kind", "linear")
-            if kind == "vector":
-                arr[i].d_out, arr[i].d_in = g.shape[0], 1
-                arr[i].flags = ADLOCO_KIND_VECTOR | (ADLOCO_GRAD_PROVIDED if l.get("provided") else 0)
-            elif kind == "embed":
-                arr[i].d_in, arr[i].d_out = g.shape
-                arr[i].flags = ADLOCO_KIND_EMBED | ADLOCO_GRAD_PROVIDED
-            else:
-                arr[i].d_out, arr[i].d_in = g.shape
-                arr[i].flags = ADLOCO_GRAD_PROVIDED if l.get("provided") else 0
-    else:
-        arr = descs
+    arr = descs if descs is not None else _grad_sum_descs(layers)
     res = NormTestResult()
     ctx._check(load_library().adloco_norm_test(ctx._h, arr, len(arr), C.c_void_p(acc.data_ptr()),
                                                eta, b_cur, b_max, n_switch, b_cap, flags,

@@ -59,7 +59,7 @@ using namespace adloco;
 
 static const char* const kProfNames[kProfCount] = {"gram", "wgrad", "finalize", "sqnorm",
                                                    "outer_step", "merge", "vector_table",
-                                                   "inner_step"};
+                                                   "inner_step", "inner_products"};
 
 extern "C" int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms,
                                    int* launches) {
@@ -134,7 +134,8 @@ extern "C" int adloco_destroy(adloco_ctx* ctx) {
   Scratch* all[] = {&ctx->partials, &ctx->layer_tab, &ctx->red_f64, &ctx->sample_f64,
                     &ctx->order_tab, &ctx->job_tab, &ctx->wgx_tab,
                     &ctx->wgx_split, &ctx->wgx_part, &ctx->vec_tab, &ctx->emb_tab,
-                    &ctx->aux_vec, &ctx->aux_perm, &ctx->aux_part};
+                    &ctx->aux_vec, &ctx->aux_perm, &ctx->aux_part, &ctx->ip_tab, &ctx->ip_tile_out,
+                    &ctx->ip_dot, &ctx->ip_sq, &ctx->ip_part, &ctx->ip_flags};
   for (Scratch* s : all)
     if (s->ptr) (void)hipFree(s->ptr);
   for (auto& r : ctx->prof) {

@@ -113,6 +113,7 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   ctx->all_fast = fast;
   ctx->n_linear = int(order.size());
   ctx->aux_B = ctx->aux_T = -1;         // the vector / table descriptor lists follow the table
+  ctx->ip_B = ctx->ip_T = -1;           // and so does the inner-product tile table
   ctx->wgx_slots = 0;
   if (fast && dtype == ADLOCO_BF16 && wg > 0) {
     std::vector<int4> tiles, split;
@@ -296,7 +297,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
     e = launch_vector_stats(g.layers, static_cast<const AuxDesc*>(ctx->vec_tab.ptr),
                             int(ctx->vec_host.size()), ctx->vec_blocks, ctx->vec_blocks2, B, T, dtype,
                             static_cast<float*>(ctx->aux_vec.ptr), g.partials, int(n_pairs),
-                            accumulate, st);
+                            accumulate, true, st);
     if (e == hipSuccess)
       e = launch_embed_stats(g.layers, static_cast<const AuxDesc*>(ctx->emb_tab.ptr),
                              int(ctx->emb_host.size()), ctx->emb_blocks, B, T, dtype,
@@ -364,5 +365,134 @@ extern "C" int adloco_norm_test(adloco_ctx* ctx, const adloco_linear_desc* layer
   rc = adloco_norm_test_decide(h.sum_sample_sqnorm, S2, h.n_samples, eta, b_cur, b_max, n_switch,
                                b_cap, flags, out);
   if (rc) return fail(ctx, rc, "norm_test: decision rejected S1 = %g, S2 = %g", h.sum_sample_sqnorm, S2);
+  return ADLOCO_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inner products c_i = <g_i, G> (Section 3.3.2)
+// ---------------------------------------------------------------------------------------------
+extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
+                                     int B, int T, int dtype, float* per_sample_ip,
+                                     float* per_sample_sqnorm, adloco_ip_acc* acc, uint32_t flags,
+                                     void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (!layers || n_layers < 1) return fail(ctx, ADLOCO_EINVAL, "inner_products: no layers");
+  if (n_layers > kMaxLayers)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: n_layers = %d exceeds %d", n_layers, kMaxLayers);
+  if (B < 1 || T < 1) return fail(ctx, ADLOCO_EINVAL, "inner_products: B = %d, T = %d must be >= 1", B, T);
+  if (dtype != ADLOCO_F32 && dtype != ADLOCO_BF16)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: dtype %d not supported", dtype);
+  if (!per_sample_ip || !acc) return fail(ctx, ADLOCO_EINVAL, "inner_products: NULL output");
+  if (reinterpret_cast<uintptr_t>(acc) % 8)
+    return fail(ctx, ADLOCO_EINVAL, "inner_products: acc not 8-byte aligned");
+  if (flags & ~ADLOCO_ACCUMULATE) return fail(ctx, ADLOCO_EINVAL, "inner_products: unknown flags");
+  for (int l = 0; l < n_layers; ++l)
+    if (!layers[l].grad_sum)
+      return fail(ctx, ADLOCO_EINVAL, "inner_products: layer %d has no grad_sum (G is read here)", l);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = prepare_tables(ctx, layers, n_layers, dtype, true, st);
+  if (rc) return rc;
+  rc = prepare_vector_table(ctx, B, T, st);
+  if (rc) return rc;
+  const std::vector<LayerDev>& tab = ctx->layer_tab_host;
+
+  // ---- which blocks go through the tile GEMM, and its tile table
+  if (ctx->ip_B != B || ctx->ip_T != T) {
+    std::vector<char> use(n_layers, 0);
+    bool any = false;
+    for (int l = 0; l < n_layers; ++l) {
+      use[l] = tab[l].kind == ADLOCO_KIND_LINEAR && dtype == ADLOCO_BF16 && tab[l].fast && T % 32 == 0;
+      any = any || use[l];
+    }
+    std::vector<int4> tiles;
+    const int slots = any ? make_ip_tiles(tab, use, B, tiles) : 0;
+    if ((long long)slots * kNumXcd > 0x7fffffffLL)
+      return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: too many tiles for one launch");
+    rc = ensure_scratch(ctx, ctx->ip_tab, std::max<size_t>(tiles.size(), 1) * sizeof(int4));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->ip_tile_out, std::max<size_t>(tiles.size(), 1) * 2 * sizeof(float));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->ip_flags, size_t(n_layers));
+    if (rc) return rc;
+    ctx->ip_B = ctx->ip_T = -1;
+    if (!tiles.empty())
+      ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->ip_tab.ptr, tiles.data(), tiles.size() * sizeof(int4),
+                                           hipMemcpyHostToDevice, st));
+    ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->ip_flags.ptr, use.data(), size_t(n_layers),
+                                         hipMemcpyHostToDevice, st));
+    ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+    ctx->ip_use = std::move(use);
+    ctx->ip_slots = slots;
+    ctx->ip_B = B;
+    ctx->ip_T = T;
+  }
+  rc = ensure_scratch(ctx, ctx->ip_dot, size_t(n_layers) * B * sizeof(float));
+  if (rc) return rc;
+  rc = ensure_scratch(ctx, ctx->ip_sq, size_t(n_layers) * B * sizeof(float));
+  if (rc) return rc;
+  rc = ensure_scratch(ctx, ctx->sample_f64, size_t(B) * sizeof(double));
+  if (rc) return rc;
+  size_t part_doubles = 1;
+  for (int l = 0; l < n_layers; ++l)
+    if (tab[l].kind == ADLOCO_KIND_LINEAR && !ctx->ip_use[l])
+      part_doubles = std::max(part_doubles, ip_generic_part_doubles(tab[l], B));
+  rc = ensure_scratch(ctx, ctx->ip_part, part_doubles * sizeof(double));
+  if (rc) return rc;
+
+  const LayerDev* dl = static_cast<const LayerDev*>(ctx->layer_tab.ptr);
+  float* dot = static_cast<float*>(ctx->ip_dot.ptr);
+  float* sq = static_cast<float*>(ctx->ip_sq.ptr);
+  hipEvent_t ev = prof_begin(ctx, st);
+  hipError_t e = launch_ip_tiles(dl, ctx->ip_tab.ptr, ctx->ip_slots, T,
+                                 static_cast<float*>(ctx->ip_tile_out.ptr), st);
+  for (int l = 0; l < n_layers && e == hipSuccess; ++l)
+    if (tab[l].kind == ADLOCO_KIND_LINEAR && !ctx->ip_use[l])
+      e = launch_ip_generic(tab[l], l, B, T, dtype, static_cast<double*>(ctx->ip_part.ptr), dot, sq, st);
+  if (e == hipSuccess && !ctx->vec_host.empty())
+    e = launch_vector_stats(dl, static_cast<const AuxDesc*>(ctx->vec_tab.ptr), int(ctx->vec_host.size()),
+                            ctx->vec_blocks, ctx->vec_blocks2, B, T, dtype,
+                            static_cast<float*>(ctx->aux_vec.ptr), sq, 1, 0, false, st);
+  if (e == hipSuccess && !ctx->emb_host.empty())
+    e = launch_embed_stats(dl, static_cast<const AuxDesc*>(ctx->emb_tab.ptr), int(ctx->emb_host.size()),
+                           ctx->emb_blocks, B, T, dtype, static_cast<int*>(ctx->aux_perm.ptr),
+                           static_cast<double*>(ctx->aux_part.ptr), sq, 1, st);
+  if (e == hipSuccess)
+    e = launch_ip_vector_table(dl, static_cast<const AuxDesc*>(ctx->vec_tab.ptr), int(ctx->vec_host.size()),
+                               static_cast<const AuxDesc*>(ctx->emb_tab.ptr), int(ctx->emb_host.size()),
+                               B, T, dtype, static_cast<const float*>(ctx->aux_vec.ptr), dot, st);
+  if (e == hipSuccess)
+    e = launch_ip_finalize(ctx->ip_tab.ptr, static_cast<const float*>(ctx->ip_tile_out.ptr),
+                           (long long)ctx->ip_slots * kNumXcd, dot, sq,
+                           static_cast<const unsigned char*>(ctx->ip_flags.ptr), n_layers, B,
+                           per_sample_ip, per_sample_sqnorm, static_cast<double*>(ctx->sample_f64.ptr),
+                           acc, (flags & ADLOCO_ACCUMULATE) ? 1 : 0, st);
+  prof_end(ctx, kProfIp, ev, st);
+  if (e != hipSuccess)
+    return fail(ctx, ADLOCO_EHIP, "inner_products: launch failed: %s", hipGetErrorString(e));
+  return ADLOCO_OK;
+}
+
+extern "C" int adloco_inner_product_test(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
+                                         const adloco_stats_acc* acc, const adloco_ip_acc* ip,
+                                         double vartheta, double nu, int64_t b_cur, int64_t b_max,
+                                         int32_t n_switch, int64_t b_cap, adloco_ip_test_result* out,
+                                         void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (!acc || !ip || !out) return fail(ctx, ADLOCO_EINVAL, "inner_product_test: NULL acc, ip or out");
+  // S2 exactly as the norm test forms it (also validates the layer list)
+  adloco_norm_test_result nt;
+  int rc = adloco_norm_test(ctx, layers, n_layers, acc, 1.0, b_cur, b_max, n_switch, b_cap, 0, &nt, stream);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  adloco_ip_acc h;
+  ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->pinned + 4, ip, sizeof h, hipMemcpyDeviceToHost, st));
+  ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+  std::memcpy(&h, ctx->pinned + 4, sizeof h);
+  if (h.n_samples != nt.n_samples)
+    return fail(ctx, ADLOCO_ESTATE, "inner_product_test: the inner products cover %lld samples, the "
+                "statistics %lld", (long long)h.n_samples, (long long)nt.n_samples);
+  rc = adloco_inner_product_decide(nt.S1, nt.S2, h.sum_ip, h.sum_ip_sq, nt.n_samples, vartheta, nu,
+                                   b_cur, b_max, n_switch, b_cap, out);
+  if (rc) return fail(ctx, rc, "inner_product_test: decision rejected its arguments");
   return ADLOCO_OK;
 }

@@ -91,3 +91,58 @@ extern "C" int adloco_check_merge(const int64_t* b_req, int k, int w, int* sel_o
   *n_sel = w;
   return ADLOCO_OK;
 }
+
+// Inner-product test and augmented inner-product test (Section 3.3.2) from the batch sums.
+extern "C" int adloco_inner_product_decide(double S1, double S2, double sum_ip, double sum_ip_sq,
+                                           int64_t n_samples, double vartheta, double nu,
+                                           int64_t b_cur, int64_t b_max, int32_t n_switch,
+                                           int64_t b_cap, adloco_ip_test_result* out) {
+  if (!out || n_samples < 1 || !(vartheta > 0.0) || !(nu > 0.0) || b_cur < 1 || b_max < 1 ||
+      n_switch < 1 || b_cap < 0 || std::isnan(S1) || std::isnan(S2) || std::isnan(sum_ip) ||
+      std::isnan(sum_ip_sq) || S1 < 0.0 || S2 < 0.0 || sum_ip_sq < 0.0)
+    return ADLOCO_EINVAL;
+  const int64_t ceiling = b_cap > 0 ? b_cap : std::numeric_limits<int64_t>::max();
+  const double Bd = static_cast<double>(n_samples);
+  adloco_ip_test_result r{};
+  r.S1 = S1;
+  r.S2 = S2;
+  r.n_samples = n_samples;
+  r.b_cur = b_cur;
+  r.batch_grad_sqnorm = S2 / (Bd * Bd);
+  const double nan = std::numeric_limits<double>::quiet_NaN();
+  const double inf = std::numeric_limits<double>::infinity();
+  if (n_samples < 2) {
+    r.var_ip = r.stat_ip = r.var_aug = r.stat_aug = nan;
+    r.stat_undefined = 1;
+    r.b_req_ip = r.b_req_aug = std::min(ceiling, std::max<int64_t>(b_cur, 2));
+  } else {
+    const double gk2 = r.batch_grad_sqnorm;
+    // <g_i, g_k> = c_i / B:  sum = sum_ip / B,  sum of squares = sum_ip_sq / B^2
+    const double s = sum_ip / Bd, s2 = sum_ip_sq / (Bd * Bd);
+    r.var_ip = std::max(s2 - s * s / Bd, 0.0) / (Bd - 1.0);
+    // g_k = 0: no direction to project on, the residual is g_i itself
+    r.var_aug = std::max(S1 - (gk2 > 0.0 ? s2 / gk2 : 0.0), 0.0) / (Bd - 1.0);
+    auto ratio = [&](double num, double den) {
+      if (den > 0.0) return num / den;
+      return num > 0.0 ? inf : 0.0;
+    };
+    r.stat_ip = ratio(r.var_ip, vartheta * vartheta * gk2 * gk2);
+    r.stat_aug = ratio(r.var_aug, nu * nu * gk2);
+    auto to_batch = [&](double stat) {
+      if (std::isinf(stat) || stat >= static_cast<double>(ceiling)) return ceiling;
+      return static_cast<int64_t>(std::ceil(stat));
+    };
+    const int64_t ip_raw = to_batch(r.stat_ip);
+    const int64_t aug_raw = to_batch(std::max(static_cast<double>(ip_raw), r.stat_aug));
+    r.b_req_ip = std::min(ceiling, std::max<int64_t>(std::max(b_cur, ip_raw), 1));
+    r.b_req_aug = std::min(ceiling, std::max<int64_t>(std::max(b_cur, aug_raw), 1));
+  }
+  int rc = adloco_switch_mode(r.b_req_ip, b_max, n_switch, &r.accumulate_ip, &r.accum_steps_ip,
+                              &r.b_micro_ip);
+  if (rc != ADLOCO_OK) return rc;
+  rc = adloco_switch_mode(r.b_req_aug, b_max, n_switch, &r.accumulate_aug, &r.accum_steps_aug,
+                          &r.b_micro_aug);
+  if (rc != ADLOCO_OK) return rc;
+  *out = r;
+  return ADLOCO_OK;
+}

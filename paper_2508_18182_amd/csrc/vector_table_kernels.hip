@@ -280,7 +280,7 @@ int embed_table_slab() { return kEmbSlab; }
 hipError_t launch_vector_stats(const LayerDev* layers, const AuxDesc* tab, int n_tab,
                                int blocks_rowsum, int blocks_colsum, int B, int T, int dtype,
                                float* vec, float* partials, int n_pairs, int accumulate,
-                               hipStream_t st) {
+                               bool write_grad_sum, hipStream_t st) {
   if (n_tab <= 0) return hipSuccess;
   if (dtype == ADLOCO_BF16)
     hipLaunchKernelGGL(vector_rowsum_kernel<unsigned short>, dim3(blocks_rowsum), dim3(kVtThreads), 0,
@@ -288,8 +288,9 @@ hipError_t launch_vector_stats(const LayerDev* layers, const AuxDesc* tab, int n
   else
     hipLaunchKernelGGL(vector_rowsum_kernel<float>, dim3(blocks_rowsum), dim3(kVtThreads), 0, st,
                        layers, tab, n_tab, B, T, vec);
-  hipLaunchKernelGGL(vector_colsum_kernel, dim3(blocks_colsum), dim3(kVtThreads), 0, st, layers, tab,
-                     n_tab, B, vec, accumulate);
+  if (write_grad_sum)
+    hipLaunchKernelGGL(vector_colsum_kernel, dim3(blocks_colsum), dim3(kVtThreads), 0, st, layers, tab,
+                       n_tab, B, vec, accumulate);
   hipLaunchKernelGGL(vector_sqnorm_kernel, dim3(n_tab * B), dim3(kVtThreads), 0, st, layers, tab, B,
                      vec, partials, n_pairs);
   return hipGetLastError();

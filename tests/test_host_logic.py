@@ -48,6 +48,7 @@ def test_struct_layouts_match_header():
     # sizes printed by a C program that includes adloco.h (gcc, x86-64)
     assert (ctypes.sizeof(b.Worker), ctypes.sizeof(b.Trainer), ctypes.sizeof(b.RoundConfig),
             ctypes.sizeof(b.RoundReport)) == (40, 64, 104, 128)
+    assert (ctypes.sizeof(A.IpAcc), ctypes.sizeof(A.IpTestResult)) == (32, 136)
 
 
 def test_check_merge_fixture():
@@ -104,6 +105,62 @@ def test_decide_matches_oracle_on_random_inputs():
             assert got[k] == want[k], (k, it, got, want)
         if not want["stat_undefined"] and not math.isinf(want["stat"]):
             assert got["stat"] == pytest.approx(want["stat"], rel=1e-12, abs=1e-300)
+
+
+def test_inner_product_decide_matches_oracle_on_random_gradients():
+    """Section 3.3.2: the host half works from four sums; the oracle from the per-sample values
+    (and, every other case, from the explicit residual vectors)."""
+    r = np.random.Generator(np.random.PCG64(77))
+    for it in range(400):
+        B = int(r.integers(1, 40))
+        P = int(r.integers(1, 30))
+        g = r.normal(size=(B, P)) * float(r.uniform(0.1, 3.0)) + r.normal(size=(1, P)) * (it % 3)
+        if it % 29 == 0:
+            g[:] = 0.0
+        G = g.sum(axis=0)
+        c = g @ G
+        n = (g * g).sum(axis=1)
+        S2 = float(G @ G)
+        vartheta = float(r.uniform(0.005, 0.5))
+        nu = float(r.uniform(0.05, 2.0))
+        b_cur, b_max = int(r.integers(1, 100)), int(r.integers(1, 64))
+        nsw = int(r.integers(1, 4))
+        cap = int(r.integers(0, 2)) * int(r.integers(1, 5000))
+        got = A.adloco_inner_product_decide(float(n.sum()), S2, float(c.sum()), float((c * c).sum()),
+                                            B, vartheta, nu, b_cur, b_max, nsw, cap)
+        want = orc.inner_product_test(n, c, S2, vartheta, nu, b_cur, b_max, nsw, cap,
+                                      g_rows=g if it % 2 else None)
+        assert got["stat_undefined"] == want["stat_undefined"]
+        if want["stat_undefined"]:
+            assert got["b_req_ip"] == want["b_req_ip"] and got["b_req_aug"] == want["b_req_aug"]
+            continue
+        near_cut = False
+        for k in ("stat_ip", "stat_aug", "var_ip", "var_aug"):
+            if math.isinf(want[k]):
+                assert math.isinf(got[k])
+            else:
+                assert got[k] == pytest.approx(want[k], rel=1e-8, abs=1e-9 * (1.0 + abs(want[k]))), (k, it)
+                if k.startswith("stat") and abs(want[k] - round(want[k])) < 1e-6 * (1 + abs(want[k])):
+                    near_cut = True
+        if near_cut:
+            continue
+        assert got["b_req_ip"] == want["b_req_ip"], (it, got, want)
+        assert got["b_req_aug"] == want["b_req_aug"], (it, got, want)
+        for tag in ("ip", "aug"):
+            sw = want["switch_" + tag]
+            assert (got["accumulate_" + tag], got["accum_steps_" + tag], got["b_micro_" + tag]) == \
+                (sw["accumulate"], sw["accum_steps"], sw["b_micro"])
+
+
+def test_inner_product_decide_rejects_bad_arguments():
+    with pytest.raises(A.AdlocoError):
+        A.adloco_inner_product_decide(1.0, 1.0, 1.0, 1.0, 0, 0.01, 0.3, 1, 32)
+    with pytest.raises(A.AdlocoError):
+        A.adloco_inner_product_decide(1.0, 1.0, 1.0, 1.0, 4, 0.0, 0.3, 1, 32)
+    with pytest.raises(A.AdlocoError):
+        A.adloco_inner_product_decide(1.0, 1.0, 1.0, 1.0, 4, 0.01, -1.0, 1, 32)
+    with pytest.raises(A.AdlocoError):
+        A.adloco_inner_product_decide(float("nan"), 1.0, 1.0, 1.0, 4, 0.01, 0.3, 1, 32)
 
 
 def test_check_merge_matches_oracle_random():
