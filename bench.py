@@ -146,6 +146,29 @@ def vector_table_leg(torch, synth, A, ctx, layers, B, T, dev, steps):
                 frac=(nbytes / (ms * 1e-3) / PEAK_HBM) if ms else None, traffic=None)
 
 
+def inner_products_leg(torch, A, ctx, layers, B, T, dev, steps):
+    """Extra leg (not part of `value`): c_i = <g_i, G> of every sample against the gradient sums
+    the timed step left in place (Section 3.3.2's tests).  Each 256 x 256 tile of each per-sample
+    gradient is one T-deep bf16 contraction: 2 * d_in * d_out * T flop per (block, sample)."""
+    flops = sum(2.0 * l["d_in"] * l["d_out"] * T * B for l in layers)
+    descs = A.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
+    c = torch.zeros(B, dtype=torch.float32, device=dev)
+    acc = torch.zeros(4, dtype=torch.float64, device=dev)
+    for _ in range(2):
+        A.adloco_inner_products(ctx, layers, B, T, A.ADLOCO_BF16, c, None, acc, 0, descs=descs)
+    torch.cuda.synchronize()
+    ctx.profile_read("inner_products")
+    for _ in range(steps):
+        A.adloco_inner_products(ctx, layers, B, T, A.ADLOCO_BF16, c, None, acc, 0, descs=descs)
+    torch.cuda.synchronize()
+    ms, n = ctx.profile_read("inner_products")
+    ms = ms / n if n else None
+    return dict(bound="mfma", kernel="ip_tile_kernel (+ small reductions)", blocks=len(layers),
+                avg_kernel_ms=ms, flops_algorithmic=flops,
+                achieved=(flops / (ms * 1e-3) / 1e12) if ms else None, peak=PEAK_BF16_MFMA / 1e12,
+                unit="TFLOP/s", frac=(flops / (ms * 1e-3) / PEAK_BF16_MFMA) if ms else None, traffic=None)
+
+
 def inner_step_leg(torch, synth, A, ctx, N, dev, steps):
     """Extra leg (not part of `value`): the workers' fused AdamW step on N parameters; reads
     theta, m, v, grad and writes theta, m, v: 28 bytes per parameter."""
@@ -179,7 +202,7 @@ def measured_traffic():
             for ln in f:
                 parts = [p.strip() for p in ln.split("|")]
                 if len(parts) >= 5 and parts[1] in ("gram", "wgrad", "outer_step", "merge", "sqnorm",
-                                                     "vector_table", "inner_step"):
+                                                     "vector_table", "inner_step", "inner_products"):
                     out[parts[1]] = float(parts[2]) + float(parts[3])
     except OSError:
         pass
@@ -398,6 +421,8 @@ def main():
         if args.only in ("all", "stats"):
             out["next_rows"]["vector_table"] = vector_table_leg(torch, synth, A, ctx, layers, B, T, dev,
                                                                 args.steps)
+            out["next_rows"]["inner_products"] = inner_products_leg(torch, A, ctx, layers, B, T, dev,
+                                                                    args.steps)
         if args.only in ("all", "outer"):
             del insts, mom
             torch.cuda.empty_cache()

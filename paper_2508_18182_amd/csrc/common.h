@@ -101,12 +101,13 @@ struct adloco_ctx {
   int vec_blocks = 0, vec_blocks2 = 0, emb_blocks = 0;
   // inner products (Section 3.3.2)
   adloco::Scratch ip_tab;      // int4 tile table of the inner-product form of the tile GEMM
-  adloco::Scratch ip_tile_out; // float [tiles][2]
+  adloco::Scratch ip_tile_out; // float [tiles][ip_group][8 waves][2]
   adloco::Scratch ip_dot, ip_sq;   // float [n_layers][B] of the blocks outside the tile table
   adloco::Scratch ip_part;     // double scratch of the plain path
   adloco::Scratch ip_flags;    // unsigned char [n_layers]: 1 = block is in the tile table
   std::vector<char> ip_use;    // host copy of ip_flags
-  int ip_slots = 0, ip_B = -1, ip_T = -1;
+  int ip_slots = 0, ip_group = 1, ip_B = -1, ip_T = -1;
+  int ip_group_tuning = 0;     // 0: cost model; else samples per tile entry
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
   double* pinned = nullptr;    // 8 doubles of pinned host memory (read-back of the tests' sums)
@@ -192,17 +193,17 @@ hipError_t launch_vector_stats(const LayerDev* layers, const AuxDesc* tab, int n
                                int blocks_rowsum, int blocks_colsum, int B, int T, int dtype,
                                float* vec, float* partials, int n_pairs, int accumulate,
                                bool write_grad_sum, hipStream_t st);
-int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B,
-                  std::vector<int4>& out);
-hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots, int T, float* ip_out,
-                           hipStream_t st);
+int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B, int T,
+                  int forced_group, std::vector<int4>& out, int& group);
+hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots, int T, int group,
+                           bool want_sq, float* ip_out, hipStream_t st);
 hipError_t launch_ip_generic(const LayerDev& L, int layer, int B, int T, int dtype, double* part,
                              float* dot, float* sq, hipStream_t st);
 size_t ip_generic_part_doubles(const LayerDev& L, int B);
 hipError_t launch_ip_vector_table(const LayerDev* layers, const AuxDesc* vec_tab, int n_vec,
                                   const AuxDesc* emb_tab, int n_emb, int B, int T, int dtype,
                                   const float* vec, float* dot, hipStream_t st);
-hipError_t launch_ip_finalize(const void* tiles, const float* tile_out, long long n_tiles,
+hipError_t launch_ip_finalize(const void* tiles, const float* tile_out, long long n_tiles, int group,
                               const float* dot, const float* sq, const unsigned char* in_tiles,
                               int n_layers, int B, float* per_sample_ip, float* per_sample_sq,
                               double* sample_f64, adloco_ip_acc* acc, int accumulate, hipStream_t st);

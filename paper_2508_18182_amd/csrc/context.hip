@@ -162,6 +162,10 @@ extern "C" int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value) {
   else if (n == "stream_blocks_per_cu") {
     if (value < 0 || value > 64) return fail(ctx, ADLOCO_EINVAL, "stream_blocks_per_cu out of range");
     ctx->stream_blocks_per_cu = value;
+  } else if (n == "ip_group") {
+    if (value < 0 || value > 0x7fff) return fail(ctx, ADLOCO_EINVAL, "ip_group out of range");
+    ctx->ip_group_tuning = value;
+    ctx->ip_B = ctx->ip_T = -1;
   } else if (n == "stream_variant") ctx->stream_variant = value;
   else if (n == "profile") ctx->profile = value ? 1 : 0;
   else return fail(ctx, ADLOCO_EINVAL, "unknown tuning knob '%s'", name);

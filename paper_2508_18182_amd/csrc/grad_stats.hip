@@ -405,12 +405,14 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
       any = any || use[l];
     }
     std::vector<int4> tiles;
-    const int slots = any ? make_ip_tiles(tab, use, B, tiles) : 0;
+    int group = 1;
+    const int slots = any ? make_ip_tiles(tab, use, B, T, ctx->ip_group_tuning, tiles, group) : 0;
     if ((long long)slots * kNumXcd > 0x7fffffffLL)
       return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: too many tiles for one launch");
     rc = ensure_scratch(ctx, ctx->ip_tab, std::max<size_t>(tiles.size(), 1) * sizeof(int4));
     if (rc) return rc;
-    rc = ensure_scratch(ctx, ctx->ip_tile_out, std::max<size_t>(tiles.size(), 1) * 2 * sizeof(float));
+    rc = ensure_scratch(ctx, ctx->ip_tile_out,
+                        std::max<size_t>(tiles.size(), 1) * group * 16 * sizeof(float));
     if (rc) return rc;
     rc = ensure_scratch(ctx, ctx->ip_flags, size_t(n_layers));
     if (rc) return rc;
@@ -423,6 +425,7 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
     ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
     ctx->ip_use = std::move(use);
     ctx->ip_slots = slots;
+    ctx->ip_group = group;
     ctx->ip_B = B;
     ctx->ip_T = T;
   }
@@ -443,7 +446,8 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
   float* dot = static_cast<float*>(ctx->ip_dot.ptr);
   float* sq = static_cast<float*>(ctx->ip_sq.ptr);
   hipEvent_t ev = prof_begin(ctx, st);
-  hipError_t e = launch_ip_tiles(dl, ctx->ip_tab.ptr, ctx->ip_slots, T,
+  hipError_t e = launch_ip_tiles(dl, ctx->ip_tab.ptr, ctx->ip_slots, T, ctx->ip_group,
+                                 per_sample_sqnorm != nullptr,
                                  static_cast<float*>(ctx->ip_tile_out.ptr), st);
   for (int l = 0; l < n_layers && e == hipSuccess; ++l)
     if (tab[l].kind == ADLOCO_KIND_LINEAR && !ctx->ip_use[l])
@@ -462,7 +466,7 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
                                B, T, dtype, static_cast<const float*>(ctx->aux_vec.ptr), dot, st);
   if (e == hipSuccess)
     e = launch_ip_finalize(ctx->ip_tab.ptr, static_cast<const float*>(ctx->ip_tile_out.ptr),
-                           (long long)ctx->ip_slots * kNumXcd, dot, sq,
+                           (long long)ctx->ip_slots * kNumXcd, ctx->ip_group, dot, sq,
                            static_cast<const unsigned char*>(ctx->ip_flags.ptr), n_layers, B,
                            per_sample_ip, per_sample_sqnorm, static_cast<double*>(ctx->sample_f64.ptr),
                            acc, (flags & ADLOCO_ACCUMULATE) ? 1 : 0, st);

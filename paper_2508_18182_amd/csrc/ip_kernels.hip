@@ -1,9 +1,8 @@
 // Per-sample inner products c_i = <g_i, G> with the batch gradient sum G, the quantity whose
 // variance the inner-product test and the augmented inner-product test of Section 3.3.2 need.
 // For aligned bf16 linear layers the tiles of each per-sample gradient g_i = delta_i^T a_i are
-// formed in registers by the tile GEMM kernel (csrc/wgrad_kernels.hip, inner-product form) and
-// reduced against the fp32 tile of G on the spot; this file holds the plain path for everything
-// else, the vector / table blocks and the reductions.  As a by-product every path also returns
+// formed in registers by MFMA and reduced against the fp32 tile of G on the spot (ip_tile_kernel);
+// a plain path covers everything else, and the vector / table blocks and reductions follow.  As a by-product every path also returns
 // the explicit ||g_i||^2, a second route to the Gram kernel's result.
 #include "common.h"
 
@@ -25,6 +24,301 @@ __device__ __forceinline__ double ip_block_sum(double v, double* lds4) {
   if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
   __syncthreads();
   return (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
+}
+
+// ---------------------------------------------------------------------------------------
+// Tile path (aligned bf16 linear layers, T a multiple of 32).
+// Work item = one 256 (d_out) x 128 (d_in) tile of one layer for a run of consecutive samples.
+// The workgroup (8 waves as 4 x 2, wave tile 64 x 64) first loads its tile of G into registers
+// (64 per lane, in the MFMA accumulator layout), then streams the token rows of its samples
+// through one uninterrupted load pipeline: the rows of consecutive samples are consecutive in
+// memory.  Every T rows the accumulators hold that sample's gradient tile: it is multiplied
+// element-wise with the G registers, summed over the wave and cleared; only two floats per
+// (tile, sample, wave) leave the chip.  A 256 x 256 tile would need 128 accumulators + 128
+// registers of G per lane, the whole register file at two waves per SIMD.
+//   Staging: global -> LDS directly, four stages of 32 token rows x (256 + 128) columns.  A load
+//   instruction moves 1 KiB: token rows j, j+16 of delta (2 x 512 B) or rows j, j+8, j+16, j+24 of
+//   a (4 x 256 B); the 1 KiB blocks are 1088 bytes apart so that the four consecutive rows of an
+//   LDS transpose read fall into different banks.  One barrier per chunk, loads two chunks ahead.
+// ---------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 ip_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float ip_f32x16;
+typedef __attribute__((ext_vector_type(4))) short ip_s16x4;
+typedef __attribute__((ext_vector_type(8))) short ip_s16x8;
+
+constexpr int kIpE = 256;                         // tile rows (d_out side)
+constexpr int kIpC = 128;                         // tile columns (d_in side)
+constexpr int kIpK = 32;                          // token rows per stage
+constexpr int kIpBlk = 1024 + 64;                 // one load instruction + 64 B skew
+constexpr int kIpOpE = 16 * kIpBlk;               // delta side of a stage
+constexpr int kIpOpC = 8 * kIpBlk;                // a side of a stage
+constexpr int kIpStage = kIpOpE + kIpOpC;         // 25.5 KiB
+constexpr int kIpStages = 4;
+constexpr int kIpLds = kIpStages * kIpStage;      // 102 KiB
+
+struct IpTileArgs {
+  const LayerDev* layers;
+  const int4* tiles;      // [8][slots]: (layer, e0, c0, first sample | samples << 16); layer < 0: none
+  float* out;             // [8 * slots][group][8 waves][2]: <tile_i, G tile>, sum of squares of tile_i
+  int slots, T, group;
+};
+
+template <int N> __device__ __forceinline__ void ip_wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ int ip_row_off_e(int row) { return (row & 15) * kIpBlk + (row >> 4) * 512; }
+__device__ __forceinline__ int ip_row_off_c(int row) { return (row & 7) * kIpBlk + (row >> 3) * 256; }
+
+template <bool SQ>
+__global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
+  const int4 tile = g.tiles[xcd * g.slots + slot];
+  if (tile.x < 0) return;
+  const LayerDev L = g.layers[tile.x];
+  const int e0 = tile.y, c0 = tile.z;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 1, wn = wave & 1;        // 4 x 2 waves; wave tile 64 (e) x 64 (c)
+  const int nk_sample = g.T / kIpK;               // chunks per sample
+  const long long ck0 = (long long)(tile.w & 0xffff) * nk_sample;
+  const long long nk = (long long)(tile.w >> 16) * nk_sample;
+
+  // ---- this lane's entries of the G tile.  Accumulator element j of a 32x32 block: row
+  // (j/4)*8 + (lane/32)*4 + j%4, column lane%32.  Entries past the edge are zero.
+  float gt[2][2][16];
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+      const int tc = c0 + wn * 64 + n * 32 + (lane & 31);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int tr = e0 + wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        const bool ok = tr < L.d_out && tc < L.d_in;
+        const float v = L.grad_sum[ok ? (size_t)tr * L.d_in + tc : 0];
+        gt[m][n][j] = ok ? v : 0.f;
+      }
+    }
+  const bool ragged = e0 + kIpE > L.d_out || c0 + kIpC > L.d_in;
+
+  // ---- direct loads, three per wave and chunk: delta instructions wave and wave + 8 (rows j and
+  // j + 16, 16-byte piece lane % 32), a instruction wave (rows j + 8 * (lane / 16), piece lane % 16)
+  const unsigned short* src_base[3];
+  long long src_stride[3];
+  int lds_off[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const bool is_a = i == 2;
+    const int j = is_a ? wave : wave + 8 * i;
+    const int row = is_a ? j + 8 * (lane >> 4) : j + 16 * (lane >> 5);
+    const int piece = is_a ? (lane & 15) : (lane & 31);
+    const int d = is_a ? L.d_in : L.d_out;
+    int col = (is_a ? c0 : e0) + piece * 8;
+    col = col < d ? col : d - 8;
+    const unsigned short* base = reinterpret_cast<const unsigned short*>(is_a ? L.a : L.delta);
+    src_stride[i] = is_a ? L.a_stride : L.delta_stride;
+    src_base[i] = base + (ck0 * kIpK + row) * src_stride[i] + col;
+    lds_off[i] = (is_a ? kIpOpE : 0) + j * kIpBlk;
+  }
+  const unsigned lds_base = lds_address(lds);       // LDS byte addresses are handled as integers
+  auto issue_loads = [&](long long c) {
+    const unsigned stage = lds_base + unsigned(c % kIpStages) * kIpStage;
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+      direct_load_lds16(src_base[i] + c * kIpK * src_stride[i], stage + lds_off[i]);
+  };
+
+  // ---- fragments by LDS transpose reads.  Within a group of 16 lanes, lane s points at the 4
+  // columns 4*(s%4).. of token row kbase + s/4; the read hands lane i column i of the group's
+  // 16 at the four token rows.  Lane l ends up with column m0 + l%32, token rows
+  // ks*16 + (l/32)*8 + 0..7.
+  const int i16 = lane & 15;
+  const int krow = (lane >> 5) * 8 + (i16 >> 2);              // + ks*16 (+4 for the upper half)
+  const int ccol = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;    // column within a 32-wide block
+  typedef __attribute__((address_space(3))) ip_s16x4* lds_ptr;
+  auto frag = [&](unsigned p0, unsigned p1) -> ip_bf16x8 {
+    ip_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(size_t)p0);
+    ip_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(size_t)p1);
+    ip_s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(ip_bf16x8, v);
+  };
+  auto read_frags = [&](long long c, int ks, ip_bf16x8 (&fa)[2], ip_bf16x8 (&fb)[2]) {
+    const unsigned stage = lds_base + unsigned(c % kIpStages) * kIpStage;
+    const int r0 = ks * 16 + krow, r1 = r0 + 4;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+      const int col = wm * 64 + m * 32 + ccol;
+      fa[m] = frag(stage + ip_row_off_e(r0) + col * 2, stage + ip_row_off_e(r1) + col * 2);
+    }
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+      const int col = wn * 64 + n * 32 + ccol;
+      fb[n] = frag(stage + kIpOpE + ip_row_off_c(r0) + col * 2, stage + kIpOpE + ip_row_off_c(r1) + col * 2);
+    }
+  };
+
+  ip_f32x16 acc[2][2];
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[m][n][j] = 0.f;
+
+  auto mfma4 = [&](const ip_bf16x8 (&a)[2], const ip_bf16x8 (&b)[2]) {
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
+    // the 8 LDS reads of the next k-step go out two at a time behind the MFMAs
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+  };
+
+  if (nk > 0) issue_loads(0);
+  if (nk > 1) issue_loads(1);
+  if (nk > 2) issue_loads(2);
+  // The G registers are needed only at the end of the first sample, but a wait placed there by the
+  // compiler would drain the load pipeline at every sample; pin them down here, once.
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) asm volatile("" : "+v"(gt[m][n][j]));
+  if (nk > 2) ip_wait_vmcnt<6>(); else if (nk > 1) ip_wait_vmcnt<3>(); else ip_wait_vmcnt<0>();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  int left = nk_sample, sample_out = 0;
+  float* dst = g.out + ((size_t(xcd) * g.slots + slot) * g.group * 8 + wave) * 2;
+  ip_bf16x8 fa[2][2], fb[2][2];
+  read_frags(0, 0, fa[0], fb[0]);
+  for (long long c = 0; c < nk; ++c) {
+    read_frags(c, 1, fa[1], fb[1]);
+    mfma4(fa[0], fb[0]);
+    if (c + 1 < nk) {
+      // chunk c+1 has landed for me (chunk c+2 may still be in flight), then for everybody;
+      // every wave is done with chunk c-1, whose stage takes chunk c+3
+      if (c + 2 < nk) ip_wait_vmcnt<3>(); else ip_wait_vmcnt<0>();
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      if (c + 3 < nk) issue_loads(c + 3);
+    }
+    read_frags(c + 1 < nk ? c + 1 : c, 0, fa[0], fb[0]);
+    mfma4(fa[1], fb[1]);
+    if (--left == 0) {
+      // the sample's tile is complete: reduce it against the G tile, clear it
+      float dot = 0.f, sq = 0.f;
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int n = 0; n < 2; ++n) {
+          const bool col_ok = c0 + wn * 64 + n * 32 + (lane & 31) < L.d_in;
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            float v = acc[m][n][j];
+            dot = fmaf(v, gt[m][n][j], dot);
+            if (SQ) {
+              if (ragged) {
+                const int tr = e0 + wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+                v = (col_ok && tr < L.d_out) ? v : 0.f;
+              }
+              sq = fmaf(v, v, sq);
+            }
+            acc[m][n][j] = 0.f;
+          }
+        }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        dot += __shfl_xor(dot, o, 64);
+        if (SQ) sq += __shfl_xor(sq, o, 64);
+      }
+      if (lane == 0) {
+        dst[size_t(sample_out) * 16] = dot;
+        dst[size_t(sample_out) * 16 + 1] = sq;
+      }
+      ++sample_out;
+      left = nk_sample;
+    }
+  }
+}
+
+// Tile table.  All tiles of one (layer, run of samples) stream the same rows, so such a set
+// goes to one XCD (one L2); sets are dealt to the least loaded XCD, largest first.  The run
+// length trades the once-per-entry costs (G tile, pipeline fill) against the balance of the last
+// round of workgroups.
+int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B, int T,
+                  int forced_group, std::vector<int4>& out, int& group) {
+  auto tiles_of = [&](const LayerDev& L) {
+    return (long long)((L.d_out + kIpE - 1) / kIpE) * ((L.d_in + kIpC - 1) / kIpC);
+  };
+  long long tiles_all = 0;
+  for (size_t l = 0; l < layers.size(); ++l)
+    if (use[l]) tiles_all += tiles_of(layers[l]);
+  // cost in chunks of 32 token rows: an entry of s samples costs s * T/32 + 8; 32 workgroups run
+  // at a time on each of the 8 XCDs
+  const double per_sample = double(T) / kIpK, fixed = 8.0;
+  double best = 0.0;
+  group = 1;
+  for (int gsz = 1; gsz <= std::min(B, 0x7fff); ++gsz) {
+    const long long runs = (B + gsz - 1) / gsz;
+    const double rounds = std::ceil(double(tiles_all * runs) / (32.0 * kNumXcd));
+    const double cost = rounds * (gsz * per_sample + fixed);
+    if (gsz == 1 || cost < best * 0.999) {
+      best = cost;
+      group = gsz;
+    }
+  }
+  if (forced_group > 0) group = std::min(std::min(forced_group, B), 0x7fff);
+  struct Set { int layer, s0, cnt; long long n; };
+  std::vector<Set> sets;
+  for (size_t l = 0; l < layers.size(); ++l) {
+    if (!use[l]) continue;
+    for (int s0 = 0; s0 < B; s0 += group)
+      sets.push_back({int(l), s0, std::min(group, B - s0), tiles_of(layers[l])});
+  }
+  std::stable_sort(sets.begin(), sets.end(), [](const Set& x, const Set& y) {
+    return x.n * x.cnt > y.n * y.cnt;
+  });
+  std::vector<std::vector<int4>> per(kNumXcd);
+  std::vector<long long> load(kNumXcd, 0);
+  for (const Set& S : sets) {
+    int bx = 0;
+    for (int x = 1; x < kNumXcd; ++x)
+      if (load[x] < load[bx]) bx = x;
+    load[bx] += S.n * S.cnt;
+    const LayerDev& L = layers[S.layer];
+    for (int e0 = 0; e0 < L.d_out; e0 += kIpE)
+      for (int c0 = 0; c0 < L.d_in; c0 += kIpC) per[bx].push_back(int4{S.layer, e0, c0, S.s0 | (S.cnt << 16)});
+  }
+  size_t slots = 0;
+  for (auto& v : per) slots = std::max(slots, v.size());
+  out.assign(size_t(kNumXcd) * slots, int4{-1, 0, 0, 0});
+  for (int x = 0; x < kNumXcd; ++x)
+    for (size_t i = 0; i < per[x].size(); ++i) out[x * slots + i] = per[x][i];
+  return int(slots);
+}
+
+hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots, int T, int group,
+                           bool want_sq, float* ip_out, hipStream_t st) {
+  if (slots <= 0) return hipSuccess;
+  auto kern = want_sq ? ip_tile_kernel<true> : ip_tile_kernel<false>;
+  {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kIpLds);
+    if (e != hipSuccess) return e;
+  }
+  IpTileArgs a{layers, static_cast<const int4*>(tiles), ip_out, slots, T, group};
+  hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(512), kIpLds, st, a);
+  return hipGetLastError();
 }
 
 // Plain path for one linear layer: workgroup = (sample, 256 rows e of the gradient); a thread owns
@@ -110,9 +404,10 @@ __global__ __launch_bounds__(kIpThreads) void embed_ip_kernel(const LayerDev* la
 }
 
 // One workgroup per sample i: c_i = sum of its tile results + sum over the other blocks;
-// likewise the explicit ||g_i||^2.  tile_out may be null (no tile launch).
+// likewise the explicit ||g_i||^2.  A tile entry covers samples [w & 0xffff, + (w >> 16)) and
+// leaves, per sample and wave, a pair at tile_out[((k * group + sample - first) * 8 + wave) * 2].
 __global__ __launch_bounds__(kIpThreads) void ip_finalize_samples_kernel(
-    const int4* tiles, const float* tile_out, long long n_tiles, const float* dot, const float* sq,
+    const int4* tiles, const float* tile_out, long long n_tiles, int group, const float* dot, const float* sq,
     const unsigned char* in_tiles, int n_layers, int B, float* per_sample_ip, float* per_sample_sq,
     double* sample_f64) {
   __shared__ double lds4[4];
@@ -120,9 +415,14 @@ __global__ __launch_bounds__(kIpThreads) void ip_finalize_samples_kernel(
   double c = 0.0, q = 0.0;
   for (long long k = threadIdx.x; k < n_tiles; k += kIpThreads) {
     const int4 t = tiles[k];
-    if (t.x >= 0 && t.w == i) {
-      c += double(tile_out[2 * k]);
-      q += double(tile_out[2 * k + 1]);
+    const int s0 = t.w & 0xffff, cnt = t.w >> 16;
+    if (t.x >= 0 && i >= s0 && i < s0 + cnt) {
+      const float* o = tile_out + ((size_t)k * group + (i - s0)) * 16;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) {
+        c += double(o[2 * w]);
+        q += double(o[2 * w + 1]);
+      }
     }
   }
   for (int l = threadIdx.x; l < n_layers; l += kIpThreads)
@@ -207,12 +507,12 @@ hipError_t launch_ip_vector_table(const LayerDev* layers, const AuxDesc* vec_tab
   return hipGetLastError();
 }
 
-hipError_t launch_ip_finalize(const void* tiles, const float* tile_out, long long n_tiles,
+hipError_t launch_ip_finalize(const void* tiles, const float* tile_out, long long n_tiles, int group,
                               const float* dot, const float* sq, const unsigned char* in_tiles,
                               int n_layers, int B, float* per_sample_ip, float* per_sample_sq,
                               double* sample_f64, adloco_ip_acc* acc, int accumulate, hipStream_t st) {
   hipLaunchKernelGGL(ip_finalize_samples_kernel, dim3(B), dim3(kIpThreads), 0, st,
-                     static_cast<const int4*>(tiles), tile_out, n_tiles, dot, sq, in_tiles, n_layers, B,
+                     static_cast<const int4*>(tiles), tile_out, n_tiles, group, dot, sq, in_tiles, n_layers, B,
                      per_sample_ip, per_sample_sq, sample_f64);
   hipLaunchKernelGGL(ip_finalize_batch_kernel, dim3(1), dim3(1024), 0, st, sample_f64, B, acc,
                      accumulate);

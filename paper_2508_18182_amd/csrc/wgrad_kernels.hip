@@ -225,11 +225,6 @@ struct WgradXArgs {
   int slots;
   long long rows;
   int accumulate;
-  // inner-product form (IP): the contraction runs over the T token rows of ONE sample (tile.w),
-  // the tile of that sample's gradient stays in registers and only <tile, grad_sum tile> and the
-  // tile's sum of squares leave the chip: ip_out[2 * workgroup + {0, 1}]
-  float* ip_out;
-  int T;
 };
 
 template <int N> __device__ __forceinline__ void wgx_wait_vmcnt() {
@@ -242,26 +237,21 @@ template <int N> __device__ __forceinline__ void wgx_wait_vmcnt() {
 // 256 distinct bytes.  Global addresses stay linear: 512 contiguous bytes per half wave.
 __device__ __forceinline__ int wgx_row_off(int row) { return (row & 15) * kXblk + (row >> 4) * kXrowB; }
 
-template <bool IP>
 __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
   const int4 tile = g.tiles[xcd * g.slots + slot];
-  if (tile.x < 0) {
-    if (IP && threadIdx.x < 2) g.ip_out[2 * (size_t(xcd) * g.slots + slot) + threadIdx.x] = 0.f;
-    return;
-  }
+  if (tile.x < 0) return;
   const LayerDev L = g.layers[tile.x];
   const int e0 = tile.y, c0 = tile.z;
-  const int split_s = IP ? 0 : (tile.w >> 24) & 0xff, split_p = (tile.w >> 16) & 0xff,
-            split_id = tile.w & 0xffff;
+  const int split_s = (tile.w >> 24) & 0xff, split_p = (tile.w >> 16) & 0xff, split_id = tile.w & 0xffff;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 2, wn = wave & 3;        // 2 x 4 waves; wave tile 128 (e) x 64 (c)
   // chunk range of this workgroup: everything, or piece split_p of split_s equal parts
-  const long long nk_all = IP ? g.T / kXk : g.rows / kXk;
-  const long long ck0 = IP ? (long long)tile.w * nk_all : (split_s ? nk_all * split_p / split_s : 0);
-  const long long nk = IP ? nk_all : (split_s ? nk_all * (split_p + 1) / split_s : nk_all) - ck0;
+  const long long nk_all = g.rows / kXk;
+  const long long ck0 = split_s ? nk_all * split_p / split_s : 0;
+  const long long nk = (split_s ? nk_all * (split_p + 1) / split_s : nk_all) - ck0;
 
   // ---- direct loads: instruction j = wave + 8*i (i = 0..3): operand j/16, rows j%16 (lanes 0-31)
   // and j%16 + 16 (lanes 32-63), 16-byte piece lane%32
@@ -367,40 +357,6 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   }
 
   // accumulator element j of a 32x32 block: row (j/4)*8 + (lane/32)*4 + j%4, column lane%32
-  if (IP) {
-    float dot = 0.f, sq = 0.f;
-#pragma unroll
-    for (int m = 0; m < 4; ++m)
-#pragma unroll
-      for (int n = 0; n < 2; ++n) {
-        const int tc = wn * 64 + n * 32 + (lane & 31);
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int tr = wm * 128 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
-          if (e0 + tr < L.d_out && c0 + tc < L.d_in) {
-            const float v = acc[m][n][j];
-            dot = fmaf(v, L.grad_sum[(size_t)(e0 + tr) * L.d_in + c0 + tc], dot);
-            sq = fmaf(v, v, sq);
-          }
-        }
-      }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      dot += __shfl_xor(dot, o, 64);
-      sq += __shfl_xor(sq, o, 64);
-    }
-    __syncthreads();                               // every wave is done with the staged tiles
-    float* red = reinterpret_cast<float*>(lds);
-    if (lane == 0) { red[2 * wave] = dot; red[2 * wave + 1] = sq; }
-    __syncthreads();
-    if (threadIdx.x < 2) {
-      float t = 0.f;
-#pragma unroll
-      for (int w = 0; w < 8; ++w) t += red[2 * w + threadIdx.x];
-      g.ip_out[2 * (size_t(xcd) * g.slots + slot) + threadIdx.x] = t;
-    }
-    return;
-  }
   float* part = split_s ? g.partials + (size_t)split_id * (kXt * kXt) : nullptr;
 #pragma unroll
   for (int m = 0; m < 4; ++m)
@@ -552,64 +508,18 @@ hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots,
                           const void* split_tiles, int n_split, float* partials, long long rows,
                           int accumulate, int variant, hipStream_t st) {
   if (slots <= 0) return hipSuccess;
-  auto kern = wgrad_bf16_x_kernel<false>;
+  auto kern = wgrad_bf16_x_kernel;
   (void)variant;
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kXlds);
     if (e != hipSuccess) return e;
   }
-  WgradXArgs a{layers, static_cast<const int4*>(tiles), partials, slots, rows, accumulate, nullptr, 0};
+  WgradXArgs a{layers, static_cast<const int4*>(tiles), partials, slots, rows, accumulate};
   hipLaunchKernelGGL(kern, dim3(unsigned(slots * kNumXcd)), dim3(512), kXlds, st, a);
   if (n_split > 0)
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(unsigned(n_split * 16)), dim3(256), 0, st, layers,
                        static_cast<const WgradSplitTile*>(split_tiles), partials, accumulate);
-  return hipGetLastError();
-}
-
-// Tile table of the inner-product form: entries (layer, e0, c0, sample).  Whole layers go to one
-// XCD (largest first, to the XCD with the fewest entries); inside an XCD the order is layer ->
-// sample -> tile, so that the tiles of one (layer, sample) stream that sample's rows out of the
-// XCD's L2 while the layer's gradient stays close by.  Only layers with `use[l]` set take part.
-int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B,
-                  std::vector<int4>& out) {
-  std::vector<int> idx;
-  std::vector<long long> cnt(layers.size(), 0);
-  for (size_t l = 0; l < layers.size(); ++l) {
-    if (!use[l]) continue;
-    cnt[l] = (long long)((layers[l].d_out + kXt - 1) / kXt) * ((layers[l].d_in + kXt - 1) / kXt) * B;
-    idx.push_back(int(l));
-  }
-  std::stable_sort(idx.begin(), idx.end(), [&](int x, int y) { return cnt[x] > cnt[y]; });
-  std::vector<std::vector<int4>> per(kNumXcd);
-  for (int l : idx) {
-    int best = 0;
-    for (int x = 1; x < kNumXcd; ++x)
-      if (per[x].size() < per[best].size()) best = x;
-    const int te = (layers[l].d_out + kXt - 1) / kXt, tc = (layers[l].d_in + kXt - 1) / kXt;
-    for (int i = 0; i < B; ++i)
-      for (int a = 0; a < te; ++a)
-        for (int b = 0; b < tc; ++b) per[best].push_back(int4{l, a * kXt, b * kXt, i});
-  }
-  size_t slots = 0;
-  for (auto& v : per) slots = std::max(slots, v.size());
-  out.assign(size_t(kNumXcd) * slots, int4{-1, 0, 0, 0});
-  for (int x = 0; x < kNumXcd; ++x)
-    for (size_t i = 0; i < per[x].size(); ++i) out[x * slots + i] = per[x][i];
-  return int(slots);
-}
-
-hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots, int T, float* ip_out,
-                           hipStream_t st) {
-  if (slots <= 0) return hipSuccess;
-  auto kern = wgrad_bf16_x_kernel<true>;
-  {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kXlds);
-    if (e != hipSuccess) return e;
-  }
-  WgradXArgs a{layers, static_cast<const int4*>(tiles), nullptr, slots, 0, 0, ip_out, T};
-  hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(512), kXlds, st, a);
   return hipGetLastError();
 }
 
