@@ -70,12 +70,13 @@ int adloco_destroy(adloco_ctx* ctx);
 const char* adloco_last_error(const adloco_ctx* ctx);
 
 /* Tuning knob for benchmarking kernel variants ("gram_variant", "wgrad_variant",
- * "stream_blocks_per_cu", ...).  Unknown names give ADLOCO_EINVAL.  Results never depend on
+ * "stream_blocks_per_cu", "ip_group", ...).  Unknown names give ADLOCO_EINVAL.  Results never depend on
  * a knob beyond floating-point summation order. */
 int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
 
 /* Measurement aid.  After adloco_set_tuning(ctx, "profile", 1) every launch of the named
- * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table", "inner_step", "inner_products") is bracketed by HIP
+ * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table",
+ * "inner_step", "inner_products") is bracketed by HIP
  * events on the call's stream.  adloco_profile_read waits for the recorded events of that
  * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
 int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
@@ -220,10 +221,10 @@ typedef struct {
 } adloco_ip_acc;       /* device memory, caller-owned, 32 bytes, 8-byte aligned                 */
 
 /* adloco_inner_products: c_i for the B samples of one micro-batch against the grad_sum buffers
- * of the descriptors (every kind; all grad_sum non-NULL, only read).  For 16-byte aligned bf16
- * linear layers with T % 32 == 0 the 256 x 256 tiles of each per-sample gradient delta_i^T a_i
- * are formed by MFMA in registers and reduced against the fp32 tile of G on the spot; other
- * blocks take a plain path.
+ * of the descriptors (every kind; all grad_sum non-NULL, only read; table ids outside [0, V)
+ * contribute nothing).  For 16-byte aligned bf16 linear layers with T % 32 == 0 the 256 x 128
+ * tiles of each per-sample gradient delta_i^T a_i are formed by MFMA in registers and reduced
+ * against the fp32 tile of G on the spot; other blocks take a plain (slow) path.  B <= 32767.
  *   per_sample_ip      device [B] fp32, overwritten: c_i
  *   per_sample_sqnorm  device [B] fp32 or NULL, overwritten: ||g_i||^2 from the explicit per-sample
  *                      gradients (a second route to adloco_grad_stats' Gram result)

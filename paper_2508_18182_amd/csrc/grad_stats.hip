@@ -380,6 +380,7 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
   if (n_layers > kMaxLayers)
     return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: n_layers = %d exceeds %d", n_layers, kMaxLayers);
   if (B < 1 || T < 1) return fail(ctx, ADLOCO_EINVAL, "inner_products: B = %d, T = %d must be >= 1", B, T);
+  if (B > 0x7fff) return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: B = %d exceeds 32767", B);
   if (dtype != ADLOCO_F32 && dtype != ADLOCO_BF16)
     return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: dtype %d not supported", dtype);
   if (!per_sample_ip || !acc) return fail(ctx, ADLOCO_EINVAL, "inner_products: NULL output");
