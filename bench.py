@@ -36,6 +36,9 @@ def parse():
     p.add_argument("--gram-variant", type=int, default=None)
     p.add_argument("--wgrad-variant", type=int, default=None)
     p.add_argument("--stream-blocks-per-cu", type=int, default=None)
+    p.add_argument("--stats-variant", default="tile", choices=["tile", "gram"],
+                   help="route of the statistics in the timed step: per-sample gradient tiles fused "
+                        "with the gradient sum (default), or Gram kernel + gradient-sum GEMM")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-blocks", type=int, default=12,
                    help="transformer blocks (of 12) the CPU oracle is timed on")
@@ -232,6 +235,7 @@ def main():
         ctx.set_tuning("wgrad_variant", args.wgrad_variant)
     if args.stream_blocks_per_cu is not None:
         ctx.set_tuning("stream_blocks_per_cu", args.stream_blocks_per_cu)
+    ctx.set_tuning("stats_variant", 1 if args.stats_variant == "tile" else 0)
     ctx.set_tuning("profile", 1)
 
     cfg = synth.CONFIGS[args.config]
@@ -319,7 +323,8 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    for k in ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge"):
+    PROF = ("tile_stats", "gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge")
+    for k in PROF:
         ctx.profile_read(k)                      # drop warm-up events
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -329,9 +334,36 @@ def main():
     ms_per_step = dt / args.steps * 1e3
 
     kern = {}
-    for k in ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge"):
+    for k in PROF:
         ms, n = ctx.profile_read(k)
         kern[k] = dict(avg_ms=(ms / n) if n else None, launches=n)
+
+    # the other route to the same statistics: Gram kernel + gradient-sum GEMM (what runs when a
+    # block does not qualify for the tile form, or with stats_variant = 0); timed apart, not part
+    # of `value` unless --stats-variant gram made it the step's route
+    alt_ms = None
+    if args.only in ("all", "stats") and args.stats_variant == "tile" and not args.grad_provided:
+        ctx.set_tuning("stats_variant", 0)
+
+        def stats_gram():
+            A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, per_sample, per_layer, acc, 0,
+                                descs=descs)
+        for _ in range(2):
+            stats_gram()
+        torch.cuda.synchronize()
+        for k in ("gram", "wgrad", "finalize", "sqnorm"):
+            ctx.profile_read(k)
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            stats_gram()
+        torch.cuda.synchronize()
+        alt_ms = (time.perf_counter() - t1) / args.steps * 1e3
+        for k in ("gram", "wgrad"):
+            ms, n = ctx.profile_read(k)
+            kern[k] = dict(avg_ms=(ms / n) if n else None, launches=n)
+        for k in ("finalize", "sqnorm"):
+            ctx.profile_read(k)
+        ctx.set_tuning("stats_variant", 1)
 
     # the same statistics with the gradient sum supplied by the caller (the training framework's
     # own weight gradient): Gram kernel + reductions + norm test only
@@ -353,7 +385,10 @@ def main():
             stats_provided()
         torch.cuda.synchronize()
         provided_ms = (time.perf_counter() - t1) / args.steps * 1e3
-        for k in ("gram", "finalize", "sqnorm"):
+        ms, n = ctx.profile_read("gram")
+        if kern["gram"]["avg_ms"] is None and n:
+            kern["gram"] = dict(avg_ms=ms / n, launches=n)
+        for k in ("finalize", "sqnorm"):
             ctx.profile_read(k)
 
     sym, full, executed = gram_flops(shapes, B, T)
@@ -378,16 +413,23 @@ def main():
                   if kern["gram"]["avg_ms"] else None)
     r_wgrad = roof("wgrad", "mfma", wgrad_flops, kern["wgrad"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
                    kernel="wgrad_bf16_x_kernel", flops_algorithmic=wgrad_flops)
+    r_tile = roof("tile_stats", "mfma", wgrad_flops, kern["tile_stats"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s",
+                  1e12, kernel="ip_tile_kernel<1, true> (+ split-tile and per-sample reductions)",
+                  flops_algorithmic=wgrad_flops)
     r_outer = roof("outer_step", "hbm", outer_bytes, kern["outer_step"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                    kernel="outer_step_vec_kernel", bytes_algorithmic=outer_bytes)
     r_merge = roof("merge", "hbm", merge_bytes, kern["merge"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                    kernel="merge_vec_kernel", bytes_algorithmic=merge_bytes)
     r_sq = roof("sqnorm", "hbm", sq_bytes, kern["sqnorm"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                 kernel="sqnorm_partial_kernel", bytes_algorithmic=sq_bytes)
-    roofs = dict(gram=r_gram, wgrad=r_wgrad, outer_step=r_outer, merge=r_merge, sqnorm=r_sq)
-    timed = {k: v["avg_ms"] for k, v in kern.items() if v["avg_ms"]}
+    roofs = dict(tile_stats=r_tile, gram=r_gram, wgrad=r_wgrad, outer_step=r_outer, merge=r_merge,
+                 sqnorm=r_sq)
+    # kernels of the timed step (the other route's kernels were timed apart)
+    in_step = ("tile_stats", "finalize", "sqnorm", "outer_step", "merge") if kern["tile_stats"]["avg_ms"] \
+        else ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge")
+    timed = {k: kern[k]["avg_ms"] for k in in_step if kern[k]["avg_ms"]}
     dominant = max(timed, key=timed.get) if timed else None
-    stats_ms = sum(kern[k]["avg_ms"] or 0.0 for k in ("gram", "wgrad", "finalize", "sqnorm"))
+    stats_ms = sum(kern[k]["avg_ms"] or 0.0 for k in in_step if k not in ("outer_step", "merge"))
 
     out = {
         "metric": "grad-stats tokens/s (MFMA util) + outer-step GB/s (frac HBM peak), 1 GPU",
@@ -400,12 +442,15 @@ def main():
                    "blocks_held": (len(shapes) // len(cfg["block"])), "blocks_of_model": cfg["n_blocks"],
                    "B": B, "T": T, "n_linears": len(shapes), "M": M, "N": N, "eta": eta,
                    "grad_sum": "caller-provided" if args.grad_provided else "computed by the library",
+                   "stats_route": args.stats_variant,
                    "timed_part": args.only},
         "roofline": (dict(roofs[dominant], dominant_kernel=dominant)
                      if dominant in roofs and roofs[dominant] else None),
         "kernels": {"avg_ms": {k: v["avg_ms"] for k, v in kern.items()},
-                    "gram": r_gram, "wgrad": r_wgrad, "outer_step": r_outer, "merge": r_merge,
-                    "sqnorm": r_sq},
+                    "tile_stats": r_tile, "gram": r_gram, "wgrad": r_wgrad, "outer_step": r_outer,
+                    "merge": r_merge, "sqnorm": r_sq,
+                    "in_timed_step": list(in_step)},
+        "grad_stats_ms_gram_plus_gradient_sum_route": alt_ms,
         "grad_stats_tokens_per_s": (B * T / (stats_ms * 1e-3)) if stats_ms else None,
         "grad_stats_tokens_per_s_gradient_supplied": (B * T / (provided_ms * 1e-3)) if provided_ms else None,
         "outer_step_GBps": r_outer["achieved"] if r_outer else None,

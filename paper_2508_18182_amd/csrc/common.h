@@ -108,6 +108,11 @@ struct adloco_ctx {
   std::vector<char> ip_use;    // host copy of ip_flags
   int ip_slots = 0, ip_group = 1, ip_B = -1, ip_T = -1;
   int ip_group_tuning = 0;     // 0: cost model; else samples per tile entry
+  // statistics by per-sample gradient tiles (explicit form fused with the gradient sum)
+  adloco::Scratch ts_tab, ts_part_idx, ts_split, ts_ptiles, ts_out, ts_csr;
+  int ts_slots = 0, ts_n_split = 0, ts_n_listed = 0, ts_idx_len = 0, ts_B = -1;
+  bool ts_ok = false;          // every linear block is aligned bf16 with its gradient sum formed here
+  int stats_variant = 1;       // 1: tile form when eligible; 0: Gram + gradient-sum kernels
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
   double* pinned = nullptr;    // 8 doubles of pinned host memory (read-back of the tests' sums)
@@ -146,7 +151,7 @@ inline int fail(adloco_ctx* ctx, int code, const char* fmt, ...) {
 
 // Event timing of one kernel launch when ctx->profile is set (no-ops otherwise).
 enum ProfKernel { kProfGram = 0, kProfWgrad, kProfFinalize, kProfSqnorm, kProfOuter, kProfMerge,
-                  kProfVecTab, kProfInner, kProfIp, kProfCount };
+                  kProfVecTab, kProfInner, kProfIp, kProfTileStats, kProfCount };
 hipEvent_t prof_begin(adloco_ctx* ctx, hipStream_t st);
 void prof_end(adloco_ctx* ctx, int kernel, hipEvent_t start, hipStream_t st);
 
@@ -197,6 +202,15 @@ int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& 
                   int forced_group, std::vector<int4>& out, int& group);
 hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots, int T, int group,
                            bool want_sq, float* ip_out, hipStream_t st);
+int make_stats_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B,
+                     std::vector<int4>& out, std::vector<int>& part, std::vector<int4>& split,
+                     std::vector<int>& lay, std::vector<int>& ptr, std::vector<int>& idx,
+                     int& n_pieces);
+hipError_t launch_stats_tiles(const LayerDev* layers, const void* tiles, const int* part, int slots,
+                              const void* split, int n_split, float* partial_tiles, int B, int T,
+                              int accumulate, float* tile_out, const int* lay, const int* ptr,
+                              const int* idx, int n_listed, float* partials, int n_pairs,
+                              hipStream_t st);
 hipError_t launch_ip_generic(const LayerDev& L, int layer, int B, int T, int dtype, double* part,
                              float* dot, float* sq, hipStream_t st);
 size_t ip_generic_part_doubles(const LayerDev& L, int B);

@@ -59,7 +59,7 @@ using namespace adloco;
 
 static const char* const kProfNames[kProfCount] = {"gram", "wgrad", "finalize", "sqnorm",
                                                    "outer_step", "merge", "vector_table",
-                                                   "inner_step", "inner_products"};
+                                                   "inner_step", "inner_products", "tile_stats"};
 
 extern "C" int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms,
                                    int* launches) {
@@ -135,7 +135,8 @@ extern "C" int adloco_destroy(adloco_ctx* ctx) {
                     &ctx->order_tab, &ctx->job_tab, &ctx->wgx_tab,
                     &ctx->wgx_split, &ctx->wgx_part, &ctx->vec_tab, &ctx->emb_tab,
                     &ctx->aux_vec, &ctx->aux_perm, &ctx->aux_part, &ctx->ip_tab, &ctx->ip_tile_out,
-                    &ctx->ip_dot, &ctx->ip_sq, &ctx->ip_part, &ctx->ip_flags};
+                    &ctx->ip_dot, &ctx->ip_sq, &ctx->ip_part, &ctx->ip_flags, &ctx->ts_tab,
+                    &ctx->ts_part_idx, &ctx->ts_split, &ctx->ts_ptiles, &ctx->ts_out, &ctx->ts_csr};
   for (Scratch* s : all)
     if (s->ptr) (void)hipFree(s->ptr);
   for (auto& r : ctx->prof) {
@@ -166,6 +167,8 @@ extern "C" int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value) {
     if (value < 0 || value > 0x7fff) return fail(ctx, ADLOCO_EINVAL, "ip_group out of range");
     ctx->ip_group_tuning = value;
     ctx->ip_B = ctx->ip_T = -1;
+  } else if (n == "stats_variant") {
+    ctx->stats_variant = value ? 1 : 0;
   } else if (n == "stream_variant") ctx->stream_variant = value;
   else if (n == "profile") ctx->profile = value ? 1 : 0;
   else return fail(ctx, ADLOCO_EINVAL, "unknown tuning knob '%s'", name);

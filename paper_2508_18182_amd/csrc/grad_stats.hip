@@ -114,6 +114,13 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   ctx->n_linear = int(order.size());
   ctx->aux_B = ctx->aux_T = -1;         // the vector / table descriptor lists follow the table
   ctx->ip_B = ctx->ip_T = -1;           // and so does the inner-product tile table
+  ctx->ts_B = -1;                       // and the statistics tile table
+  {
+    bool ok = need_inputs && dtype == ADLOCO_BF16 && !order.empty();
+    for (const LayerDev& L : tab)
+      if (L.kind == ADLOCO_KIND_LINEAR) ok = ok && !L.provided && L.fast;
+    ctx->ts_ok = ok;
+  }
   ctx->wgx_slots = 0;
   if (fast && dtype == ADLOCO_BF16 && wg > 0) {
     std::vector<int4> tiles, split;
@@ -257,6 +264,53 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   rc = ensure_scratch(ctx, ctx->sample_f64, size_t(B) * sizeof(double));
   if (rc) return rc;
 
+  // Per-sample gradient tiles (explicit form) when every linear block qualifies: the tiles that
+  // add up to the gradient sum are squared on the way, no Gram contraction is needed.
+  const bool tile_form = ctx->stats_variant != 0 && ctx->ts_ok && T % 32 == 0 && B <= 0x7fff;
+  if (tile_form && ctx->ts_B != B) {
+    const std::vector<LayerDev>& tab = ctx->layer_tab_host;
+    std::vector<char> use(n_layers, 0);
+    for (int l = 0; l < n_layers; ++l) use[l] = tab[l].kind == ADLOCO_KIND_LINEAR;
+    std::vector<int4> tiles, split;
+    std::vector<int> part, lay, ptr, idx;
+    int n_pieces = 0;
+    const int slots = make_stats_tiles(tab, use, B, tiles, part, split, lay, ptr, idx, n_pieces);
+    if ((long long)slots * kNumXcd > 0x7fffffffLL)
+      return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: too many tiles for one launch");
+    std::vector<int> csr;
+    csr.insert(csr.end(), lay.begin(), lay.end());
+    csr.insert(csr.end(), ptr.begin(), ptr.end());
+    csr.insert(csr.end(), idx.begin(), idx.end());
+    rc = ensure_scratch(ctx, ctx->ts_tab, tiles.size() * sizeof(int4));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->ts_part_idx, part.size() * sizeof(int));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->ts_split, std::max<size_t>(split.size(), 1) * sizeof(int4));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->ts_ptiles, std::max<size_t>(n_pieces, 1) * 256 * 128 * sizeof(float));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->ts_out, tiles.size() * size_t(B) * 16 * sizeof(float));
+    if (rc) return rc;
+    rc = ensure_scratch(ctx, ctx->ts_csr, csr.size() * sizeof(int));
+    if (rc) return rc;
+    ctx->ts_B = -1;
+    ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->ts_tab.ptr, tiles.data(), tiles.size() * sizeof(int4),
+                                         hipMemcpyHostToDevice, st));
+    ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->ts_part_idx.ptr, part.data(), part.size() * sizeof(int),
+                                         hipMemcpyHostToDevice, st));
+    if (!split.empty())
+      ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->ts_split.ptr, split.data(), split.size() * sizeof(int4),
+                                           hipMemcpyHostToDevice, st));
+    ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->ts_csr.ptr, csr.data(), csr.size() * sizeof(int),
+                                         hipMemcpyHostToDevice, st));
+    ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+    ctx->ts_slots = slots;
+    ctx->ts_n_split = int(split.size());
+    ctx->ts_n_listed = int(lay.size());
+    ctx->ts_idx_len = int(idx.size());
+    ctx->ts_B = B;
+  }
+
   GramLaunch g;
   g.layers = static_cast<const LayerDev*>(ctx->layer_tab.ptr);
   g.order = static_cast<const int*>(ctx->order_tab.ptr);
@@ -266,9 +320,23 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   g.partials = static_cast<float*>(ctx->partials.ptr);
   g.n_pairs = int(n_pairs);
   g.tile = tile;
-  hipEvent_t ev = ctx->n_linear > 0 ? prof_begin(ctx, st) : nullptr;
+  hipEvent_t ev = nullptr;
   hipError_t e = hipSuccess;
-  if (ctx->n_linear == 0)
+  if (tile_form) {
+    ev = prof_begin(ctx, st);
+    const int* csr = static_cast<const int*>(ctx->ts_csr.ptr);
+    const int nl = ctx->ts_n_listed;
+    e = launch_stats_tiles(g.layers, ctx->ts_tab.ptr, static_cast<const int*>(ctx->ts_part_idx.ptr),
+                           ctx->ts_slots, ctx->ts_split.ptr, ctx->ts_n_split,
+                           static_cast<float*>(ctx->ts_ptiles.ptr), B, T, accumulate,
+                           static_cast<float*>(ctx->ts_out.ptr), csr, csr + nl, csr + nl + nl + 1, nl,
+                           g.partials, int(n_pairs), st);
+    prof_end(ctx, kProfTileStats, ev, st);
+    if (e != hipSuccess)
+      return fail(ctx, ADLOCO_EHIP, "grad_stats: tile statistics launch failed: %s", hipGetErrorString(e));
+  }
+  ev = (!tile_form && ctx->n_linear > 0) ? prof_begin(ctx, st) : nullptr;
+  if (tile_form || ctx->n_linear == 0)
     ;
   else if (dual)
     e = launch_gram_bf16_dual(g, static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n,
@@ -280,9 +348,11 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   prof_end(ctx, kProfGram, ev, st);
   if (e != hipSuccess)
     return fail(ctx, ADLOCO_EHIP, "grad_stats: Gram launch failed: %s", hipGetErrorString(e));
-  ev = ctx->wgrad_blocks > 0 ? prof_begin(ctx, st) : nullptr;
+  ev = (!tile_form && ctx->wgrad_blocks > 0) ? prof_begin(ctx, st) : nullptr;
   const long long rows = (long long)B * T;
-  if (dtype == ADLOCO_BF16 && ctx->wgrad_variant >= 2 && ctx->wgx_slots > 0 && rows % 32 == 0)
+  if (tile_form)
+    ;
+  else if (dtype == ADLOCO_BF16 && ctx->wgrad_variant >= 2 && ctx->wgx_slots > 0 && rows % 32 == 0)
     e = launch_wgrad_x(g.layers, ctx->wgx_tab.ptr, ctx->wgx_slots, ctx->wgx_split.ptr,
                        ctx->wgx_n_split, static_cast<float*>(ctx->wgx_part.ptr), rows, accumulate,
                        ctx->wgrad_variant, st);

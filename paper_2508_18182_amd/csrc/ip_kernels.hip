@@ -60,7 +60,13 @@ struct IpTileArgs {
   const LayerDev* layers;
   const int4* tiles;      // [8][slots]: (layer, e0, c0, first sample | samples << 16); layer < 0: none
   float* out;             // [8 * slots][group][8 waves][2]: <tile_i, G tile>, sum of squares of tile_i
+                          // (statistics form: sum of squares, unused)
   int slots, T, group;
+  // statistics form only
+  const int* part;        // [8][slots]: -1: the entry covers all samples and owns its tile of G;
+                          // else index of the partial tile that receives its share of the sum
+  float* partials;        // [pieces][256][128] fp32
+  int accumulate;         // G += sum instead of G = sum
 };
 
 template <int N> __device__ __forceinline__ void ip_wait_vmcnt() {
@@ -69,7 +75,12 @@ template <int N> __device__ __forceinline__ void ip_wait_vmcnt() {
 __device__ __forceinline__ int ip_row_off_e(int row) { return (row & 15) * kIpBlk + (row >> 4) * 512; }
 __device__ __forceinline__ int ip_row_off_c(int row) { return (row & 7) * kIpBlk + (row >> 3) * 256; }
 
-template <bool SQ>
+// MODE 0: inner products (G tile read, <tile_i, G tile> written).
+// MODE 1: statistics: the per-sample tiles are squared and summed on the way to the gradient sum
+//         G = sum_i tile_i, which is written at the end (explicit form of the per-sample norms:
+//         when G has to be formed here anyway, its per-sample terms pass through the registers
+//         and the Gram contraction is not needed).
+template <int MODE, bool SQ>
 __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
@@ -95,9 +106,13 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         const int tr = e0 + wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
-        const bool ok = tr < L.d_out && tc < L.d_in;
-        const float v = L.grad_sum[ok ? (size_t)tr * L.d_in + tc : 0];
-        gt[m][n][j] = ok ? v : 0.f;
+        if (MODE == 0) {
+          const bool ok = tr < L.d_out && tc < L.d_in;
+          const float v = L.grad_sum[ok ? (size_t)tr * L.d_in + tc : 0];
+          gt[m][n][j] = ok ? v : 0.f;
+        } else {
+          gt[m][n][j] = 0.f;                       // running sum of the per-sample tiles
+        }
       }
     }
   const bool ragged = e0 + kIpE > L.d_out || c0 + kIpC > L.d_in;
@@ -185,12 +200,14 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
   if (nk > 2) issue_loads(2);
   // The G registers are needed only at the end of the first sample, but a wait placed there by the
   // compiler would drain the load pipeline at every sample; pin them down here, once.
+  if (MODE == 0) {
 #pragma unroll
-  for (int m = 0; m < 2; ++m)
+    for (int m = 0; m < 2; ++m)
 #pragma unroll
-    for (int n = 0; n < 2; ++n)
+      for (int n = 0; n < 2; ++n)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) asm volatile("" : "+v"(gt[m][n][j]));
+        for (int j = 0; j < 16; ++j) asm volatile("" : "+v"(gt[m][n][j]));
+  }
   if (nk > 2) ip_wait_vmcnt<6>(); else if (nk > 1) ip_wait_vmcnt<3>(); else ip_wait_vmcnt<0>();
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
@@ -225,7 +242,8 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
 #pragma unroll
           for (int j = 0; j < 16; ++j) {
             float v = acc[m][n][j];
-            dot = fmaf(v, gt[m][n][j], dot);
+            if (MODE == 0) dot = fmaf(v, gt[m][n][j], dot);
+            else gt[m][n][j] += v;
             if (SQ) {
               if (ragged) {
                 const int tr = e0 + wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
@@ -238,17 +256,87 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
         }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) {
-        dot += __shfl_xor(dot, o, 64);
+        if (MODE == 0) dot += __shfl_xor(dot, o, 64);
         if (SQ) sq += __shfl_xor(sq, o, 64);
       }
       if (lane == 0) {
-        dst[size_t(sample_out) * 16] = dot;
-        dst[size_t(sample_out) * 16 + 1] = sq;
+        if (MODE == 0) {
+          dst[size_t(sample_out) * 16] = dot;
+          dst[size_t(sample_out) * 16 + 1] = sq;
+        } else {
+          dst[size_t(sample_out) * 16] = sq;
+        }
       }
       ++sample_out;
       left = nk_sample;
     }
   }
+  if (MODE == 1) {
+    const int part = g.part[xcd * g.slots + slot];
+    float* pt = part >= 0 ? g.partials + (size_t)part * (kIpE * kIpC) : nullptr;
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int n = 0; n < 2; ++n) {
+        const int tc = wn * 64 + n * 32 + (lane & 31);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int tr = wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+          if (pt) {
+            pt[tr * kIpC + tc] = gt[m][n][j];
+          } else if (e0 + tr < L.d_out && c0 + tc < L.d_in) {
+            float* d = L.grad_sum + (size_t)(e0 + tr) * L.d_in + c0 + tc;
+            *d = g.accumulate ? *d + gt[m][n][j] : gt[m][n][j];
+          }
+        }
+      }
+  }
+}
+
+// Statistics form: sums the partial tiles of the entries that were split along the samples, in
+// piece order (fixed order: repeatable), into grad_sum.  One workgroup per 16 rows of a split tile;
+// split[t] = (layer, e0, c0, pieces << 16 | first partial tile).
+__global__ __launch_bounds__(kIpC) void stats_tile_reduce_kernel(const LayerDev* layers, const int4* split,
+                                                                const float* partials, int accumulate) {
+  const int t = blockIdx.x / (kIpE / 16), r0 = (blockIdx.x % (kIpE / 16)) * 16;
+  const int4 S = split[t];
+  const LayerDev L = layers[S.x];
+  const int pieces = S.w >> 16;
+  const float* base = partials + (size_t)(S.w & 0xffff) * (kIpE * kIpC);
+  for (int r = r0; r < r0 + 16; ++r) {
+    const int row = S.y + r, col = S.z + threadIdx.x;
+    if (row >= L.d_out || col >= L.d_in) continue;
+    float v = 0.f;
+    for (int p = 0; p < pieces; ++p) v += base[(size_t)p * (kIpE * kIpC) + r * kIpC + threadIdx.x];
+    float* d = L.grad_sum + (size_t)row * L.d_in + col;
+    *d = accumulate ? *d + v : v;
+  }
+}
+
+// Statistics form: ||g_i^l||^2 = sum over the layer's tile entries and waves of the tile's sum of
+// squares -> slot 0 of the layer's partial sums (the other slots are cleared), from where the
+// common reduction picks it up.  One workgroup per (listed layer, sample); the entries of layer
+// `lay[q]` are idx[ptr[q] .. ptr[q+1]).
+__global__ __launch_bounds__(64) void stats_tile_finalize_kernel(const int4* tiles, const float* out, int group,
+                                                                const int* lay, const int* ptr, const int* idx,
+                                                                int B, float* partials, int n_pairs) {
+  const int q = blockIdx.x / B, i = blockIdx.x % B;
+  const int l = lay[q];
+  double s = 0.0;
+  for (int k = ptr[q] + threadIdx.x; k < ptr[q + 1]; k += 64) {
+    const int e = idx[k];
+    const int4 t = tiles[e];
+    const int s0 = t.w & 0xffff, cnt = t.w >> 16;
+    if (i >= s0 && i < s0 + cnt) {
+      const float* o = out + ((size_t)e * group + (i - s0)) * 16;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) s += double(o[2 * w]);
+    }
+  }
+  s = ip_wave_sum(s);
+  float* p = partials + (size_t(l) * B + i) * n_pairs;
+  if (threadIdx.x == 0) p[0] = float(s);
+  for (int k = 1 + threadIdx.x; k < n_pairs; k += 64) p[k] = 0.f;
 }
 
 // Tile table.  All tiles of one (layer, run of samples) stream the same rows, so such a set
@@ -310,14 +398,112 @@ int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& 
 hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots, int T, int group,
                            bool want_sq, float* ip_out, hipStream_t st) {
   if (slots <= 0) return hipSuccess;
-  auto kern = want_sq ? ip_tile_kernel<true> : ip_tile_kernel<false>;
+  auto kern = want_sq ? ip_tile_kernel<0, true> : ip_tile_kernel<0, false>;
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kIpLds);
     if (e != hipSuccess) return e;
   }
-  IpTileArgs a{layers, static_cast<const int4*>(tiles), ip_out, slots, T, group};
+  IpTileArgs a{layers, static_cast<const int4*>(tiles), ip_out, slots, T, group, nullptr, nullptr, 0};
   hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(512), kIpLds, st, a);
+  return hipGetLastError();
+}
+
+// Tile table of the statistics form: one entry per 256 x 128 tile covering all B samples; the
+// tiles of a layer go to one XCD (they stream the same rows), layers to the least loaded XCD,
+// largest first.  The entries of an XCD's incomplete last round of 32 are split along the samples
+// into pieces whose partial sums a small kernel adds up in piece order.
+// lay / ptr / idx: for every listed layer the indices (into `out`) of its entries.
+int make_stats_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B,
+                     std::vector<int4>& out, std::vector<int>& part, std::vector<int4>& split,
+                     std::vector<int>& lay, std::vector<int>& ptr, std::vector<int>& idx,
+                     int& n_pieces) {
+  constexpr int kCuPerXcd = kNumCu / kNumXcd;
+  auto tiles_of = [&](const LayerDev& L) {
+    return (long long)((L.d_out + kIpE - 1) / kIpE) * ((L.d_in + kIpC - 1) / kIpC);
+  };
+  std::vector<int> order;
+  for (size_t l = 0; l < layers.size(); ++l)
+    if (use[l]) order.push_back(int(l));
+  std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+    return tiles_of(layers[x]) > tiles_of(layers[y]);
+  });
+  std::vector<std::vector<int4>> per(kNumXcd);
+  for (int l : order) {
+    int bx = 0;
+    for (int x = 1; x < kNumXcd; ++x)
+      if (per[x].size() < per[bx].size()) bx = x;
+    for (int e0 = 0; e0 < layers[l].d_out; e0 += kIpE)
+      for (int c0 = 0; c0 < layers[l].d_in; c0 += kIpC) per[bx].push_back(int4{l, e0, c0, B << 16});
+  }
+  split.clear();
+  n_pieces = 0;
+  std::vector<std::vector<int4>> fin(kNumXcd);
+  std::vector<std::vector<int>> finp(kNumXcd);
+  for (int x = 0; x < kNumXcd; ++x) {
+    const int n = int(per[x].size());
+    const int full = n / kCuPerXcd * kCuPerXcd, left = n - full;
+    const int S = left > 0 ? std::min(kCuPerXcd / left, B) : 1;
+    for (int i = 0; i < n; ++i) {
+      if (i < full || S < 2 || n_pieces + S > 0xffff) {
+        fin[x].push_back(per[x][i]);
+        finp[x].push_back(-1);
+        continue;
+      }
+      split.push_back(int4{per[x][i].x, per[x][i].y, per[x][i].z, (S << 16) | n_pieces});
+      for (int p = 0; p < S; ++p) {
+        const int s0 = int((long long)B * p / S), s1 = int((long long)B * (p + 1) / S);
+        int4 e = per[x][i];
+        e.w = s0 | ((s1 - s0) << 16);
+        fin[x].push_back(e);
+        finp[x].push_back(n_pieces + p);
+      }
+      n_pieces += S;
+    }
+  }
+  size_t slots = 0;
+  for (auto& v : fin) slots = std::max(slots, v.size());
+  out.assign(size_t(kNumXcd) * slots, int4{-1, 0, 0, 0});
+  part.assign(size_t(kNumXcd) * slots, -1);
+  for (int x = 0; x < kNumXcd; ++x)
+    for (size_t i = 0; i < fin[x].size(); ++i) {
+      out[x * slots + i] = fin[x][i];
+      part[x * slots + i] = finp[x][i];
+    }
+  std::vector<std::vector<int>> by_layer(layers.size());
+  for (size_t k = 0; k < out.size(); ++k)
+    if (out[k].x >= 0) by_layer[out[k].x].push_back(int(k));
+  lay.clear();
+  ptr.assign(1, 0);
+  idx.clear();
+  for (size_t l = 0; l < layers.size(); ++l) {
+    if (!use[l]) continue;
+    lay.push_back(int(l));
+    idx.insert(idx.end(), by_layer[l].begin(), by_layer[l].end());
+    ptr.push_back(int(idx.size()));
+  }
+  return int(slots);
+}
+
+hipError_t launch_stats_tiles(const LayerDev* layers, const void* tiles, const int* part, int slots,
+                              const void* split, int n_split, float* partial_tiles, int B, int T,
+                              int accumulate, float* tile_out, const int* lay, const int* ptr,
+                              const int* idx, int n_listed, float* partials, int n_pairs,
+                              hipStream_t st) {
+  if (slots <= 0) return hipSuccess;
+  auto kern = ip_tile_kernel<1, true>;
+  {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kIpLds);
+    if (e != hipSuccess) return e;
+  }
+  IpTileArgs a{layers, static_cast<const int4*>(tiles), tile_out, slots, T, B, part, partial_tiles, accumulate};
+  hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(512), kIpLds, st, a);
+  if (n_split > 0)
+    hipLaunchKernelGGL(stats_tile_reduce_kernel, dim3(unsigned(n_split) * (kIpE / 16)), dim3(kIpC), 0, st,
+                       layers, static_cast<const int4*>(split), partial_tiles, accumulate);
+  hipLaunchKernelGGL(stats_tile_finalize_kernel, dim3(unsigned(n_listed) * B), dim3(64), 0, st,
+                     static_cast<const int4*>(tiles), tile_out, B, lay, ptr, idx, B, partials, n_pairs);
   return hipGetLastError();
 }
 

@@ -10,10 +10,14 @@ from oracle import adloco_oracle as orc
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def ctx():
+# Every test runs twice: with the per-sample norms taken from the per-sample gradient tiles on
+# their way into the gradient sum (the default where the blocks qualify), and with the Gram and
+# gradient-sum kernels.
+@pytest.fixture(scope="module", params=[1, 0], ids=["tile_stats", "gram"])
+def ctx(request):
     import paper_2508_18182_amd as A
     c = A.Context(0)
+    c.set_tuning("stats_variant", request.param)
     yield c
     c.close()
 
