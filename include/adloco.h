@@ -70,13 +70,13 @@ int adloco_destroy(adloco_ctx* ctx);
 const char* adloco_last_error(const adloco_ctx* ctx);
 
 /* Tuning knob for benchmarking kernel variants ("gram_variant", "wgrad_variant",
- * "stream_blocks_per_cu", "ip_group", ...).  Unknown names give ADLOCO_EINVAL.  Results never depend on
+ * "stream_blocks_per_cu", "ip_group", "stats_variant", ...).  Unknown names give ADLOCO_EINVAL.  Results never depend on
  * a knob beyond floating-point summation order. */
 int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
 
 /* Measurement aid.  After adloco_set_tuning(ctx, "profile", 1) every launch of the named
  * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table",
- * "inner_step", "inner_products") is bracketed by HIP
+ * "inner_step", "inner_products", "tile_stats") is bracketed by HIP
  * events on the call's stream.  adloco_profile_read waits for the recorded events of that
  * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
 int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
@@ -142,7 +142,14 @@ typedef struct {
  *   flags    0 or ADLOCO_ACCUMULATE
  * bf16 inputs are multiplied exactly and accumulated in fp32 (MFMA); fp32 inputs in fp32.
  * bf16 rows must be 2-byte aligned; 16-byte aligned rows with d % 8 == 0 take the fast
- * path, anything else a slower guarded path (same results). */
+ * path, anything else a slower guarded path (same results).
+ * Two routes give the norms of the linear blocks.  With ADLOCO_GRAD_PROVIDED (the framework's
+ * backward already holds the weight gradient) only the Gram contractions run.  When grad_sum
+ * is formed here for every linear block and all of them are 16-byte aligned bf16 with
+ * T % 32 == 0, the 256 x 128 tiles of the per-sample gradients delta_i^T a_i that add up to
+ * grad_sum pass through the registers one sample after the other and are squared there, so the
+ * Gram contractions are not needed at all; adloco_set_tuning(ctx, "stats_variant", 0) keeps the
+ * Gram kernel plus a separate gradient-sum GEMM instead.  Same results up to fp32 rounding. */
 int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
                       int B, int T, int dtype,
                       float* per_sample_sqnorm, float* per_layer_sample_sqnorm,
