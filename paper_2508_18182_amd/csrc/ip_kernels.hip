@@ -69,6 +69,24 @@ struct IpTileArgs {
   int accumulate;         // G += sum instead of G = sum
 };
 
+// Sum over the 64 lanes without the LDS round trips of a shuffle chain: four DPP steps leave the
+// total of each row of 16 lanes in all of its lanes, the four row totals are then read as scalars.
+// (The per-sample reduction sits between two samples' MFMAs: its latency is not hidden.)
+__device__ __forceinline__ float ip_wave_sum_f32(float v) {
+#define IP_DPP(x, ctrl) \
+  __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (x)), (ctrl), 0xf, 0xf, true))
+  v += IP_DPP(v, 0xB1);    // quad_perm [1,0,3,2]
+  v += IP_DPP(v, 0x4E);    // quad_perm [2,3,0,1]
+  v += IP_DPP(v, 0x141);   // row_half_mirror
+  v += IP_DPP(v, 0x140);   // row_mirror
+#undef IP_DPP
+  const int b = __builtin_bit_cast(int, v);
+  return (__builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0)) +
+          __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16))) +
+         (__builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32)) +
+          __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48)));
+}
+
 template <int N> __device__ __forceinline__ void ip_wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | ((N >> 4) << 14));
 }
@@ -234,31 +252,44 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
     if (--left == 0) {
       // the sample's tile is complete: reduce it against the G tile, clear it
       float dot = 0.f, sq = 0.f;
+      if (!ragged) {
 #pragma unroll
-      for (int m = 0; m < 2; ++m)
+        for (int m = 0; m < 2; ++m)
 #pragma unroll
-        for (int n = 0; n < 2; ++n) {
-          const bool col_ok = c0 + wn * 64 + n * 32 + (lane & 31) < L.d_in;
+          for (int n = 0; n < 2; ++n)
 #pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            float v = acc[m][n][j];
-            if (MODE == 0) dot = fmaf(v, gt[m][n][j], dot);
-            else gt[m][n][j] += v;
-            if (SQ) {
-              if (ragged) {
-                const int tr = e0 + wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
-                v = (col_ok && tr < L.d_out) ? v : 0.f;
-              }
-              sq = fmaf(v, v, sq);
+            for (int j = 0; j < 16; ++j) {
+              const float v = acc[m][n][j];
+              if (MODE == 0) dot = fmaf(v, gt[m][n][j], dot);
+              else gt[m][n][j] += v;
+              if (SQ) sq = fmaf(v, v, sq);
+              acc[m][n][j] = 0.f;
             }
-            acc[m][n][j] = 0.f;
-          }
-        }
+      } else {
+        // tile on the edge of the layer: entries past the edge hold products of re-read columns;
+        // they meet zeros in the G registers (MODE 0) or are never stored (MODE 1), but must not
+        // enter the sum of squares
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        if (MODE == 0) dot += __shfl_xor(dot, o, 64);
-        if (SQ) sq += __shfl_xor(sq, o, 64);
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+          for (int n = 0; n < 2; ++n) {
+            const bool col_ok = c0 + wn * 64 + n * 32 + (lane & 31) < L.d_in;
+            const int tr0 = e0 + wm * 64 + m * 32 + (lane >> 5) * 4;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const float v = acc[m][n][j];
+              if (MODE == 0) dot = fmaf(v, gt[m][n][j], dot);
+              else gt[m][n][j] += v;
+              if (SQ) {
+                const float vm = (col_ok && tr0 + (j >> 2) * 8 + (j & 3) < L.d_out) ? v : 0.f;
+                sq = fmaf(vm, vm, sq);
+              }
+              acc[m][n][j] = 0.f;
+            }
+          }
       }
+      if (MODE == 0) dot = ip_wave_sum_f32(dot);
+      if (SQ) sq = ip_wave_sum_f32(sq);
       if (lane == 0) {
         if (MODE == 0) {
           dst[size_t(sample_out) * 16] = dot;
