@@ -441,8 +441,7 @@ hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots,
 }
 
 // Tile table of the statistics form: one entry per 256 x 128 tile covering all B samples; the
-// tiles of a layer go to one XCD (they stream the same rows), layers to the least loaded XCD,
-// largest first.  The entries of an XCD's incomplete last round of 32 are split along the samples
+// tiles of a layer go to one XCD where possible (they stream the same rows).  The entries of an XCD's incomplete last round of 32 are split along the samples
 // into pieces whose partial sums a small kernel adds up in piece order.
 // lay / ptr / idx: for every listed layer the indices (into `out`) of its entries.
 int make_stats_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B,
@@ -450,23 +449,18 @@ int make_stats_tiles(const std::vector<LayerDev>& layers, const std::vector<char
                      std::vector<int>& lay, std::vector<int>& ptr, std::vector<int>& idx,
                      int& n_pieces) {
   constexpr int kCuPerXcd = kNumCu / kNumXcd;
-  auto tiles_of = [&](const LayerDev& L) {
-    return (long long)((L.d_out + kIpE - 1) / kIpE) * ((L.d_in + kIpC - 1) / kIpC);
-  };
-  std::vector<int> order;
-  for (size_t l = 0; l < layers.size(); ++l)
-    if (use[l]) order.push_back(int(l));
-  std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
-    return tiles_of(layers[x]) > tiles_of(layers[y]);
-  });
-  std::vector<std::vector<int4>> per(kNumXcd);
-  for (int l : order) {
-    int bx = 0;
-    for (int x = 1; x < kNumXcd; ++x)
-      if (per[x].size() < per[bx].size()) bx = x;
+  // all tiles in layer order (within a layer: rows of tiles), cut into eight equal runs: a layer
+  // stays on one XCD unless it straddles a cut, and the XCDs get the same number of tiles
+  std::vector<int4> all;
+  for (size_t l = 0; l < layers.size(); ++l) {
+    if (!use[l]) continue;
     for (int e0 = 0; e0 < layers[l].d_out; e0 += kIpE)
-      for (int c0 = 0; c0 < layers[l].d_in; c0 += kIpC) per[bx].push_back(int4{l, e0, c0, B << 16});
+      for (int c0 = 0; c0 < layers[l].d_in; c0 += kIpC) all.push_back(int4{int(l), e0, c0, B << 16});
   }
+  std::vector<std::vector<int4>> per(kNumXcd);
+  for (int x = 0; x < kNumXcd; ++x)
+    for (size_t i = all.size() * x / kNumXcd; i < all.size() * (x + 1) / kNumXcd; ++i)
+      per[x].push_back(all[i]);
   split.clear();
   n_pieces = 0;
   std::vector<std::vector<int4>> fin(kNumXcd);

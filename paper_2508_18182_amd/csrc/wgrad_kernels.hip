@@ -449,31 +449,28 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs g) {
 
 int wgrad_tile_edge(int dtype) { return dtype == ADLOCO_BF16 ? kWt : kWtF; }
 
-// Tile table of the fast kernel: [8 XCDs][slots] entries (layer, e0, c0, split).  Layers go to
-// the XCD with the fewest tiles so far (largest layers first), so every XCD holds whole layers.
+// Tile table of the fast kernel: [8 XCDs][slots] entries (layer, e0, c0, split).  The tiles of
+// all layers, in layer order, are cut into eight equal runs, one per XCD: the tiles of a layer
+// stream the same rows out of one L2 (a layer that straddles a cut out of two), and no XCD has
+// more work than another.
 // All tiles cost the same, so an XCD's 32 CUs work in rounds; the tiles of an incomplete last
 // round are split along the contraction into as many pieces as fill the round, written to
 // partial tiles and summed afterwards by wgrad_reduce_kernel.
 int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out,
                        std::vector<int4>& split_tiles, int& n_pieces) {
   constexpr int kCuPerXcd = kNumCu / kNumXcd;
-  std::vector<int> idx;
-  std::vector<long long> cnt(layers.size(), 0);
+  // all tiles in layer order (within a layer: rows of tiles), cut into eight equal runs: a layer
+  // stays on one XCD unless it straddles a cut, and the XCDs get the same number of tiles
+  std::vector<int4> all;
   for (size_t l = 0; l < layers.size(); ++l) {
     if (layers[l].provided || layers[l].kind != ADLOCO_KIND_LINEAR) continue;
-    cnt[l] = (long long)((layers[l].d_out + kXt - 1) / kXt) * ((layers[l].d_in + kXt - 1) / kXt);
-    idx.push_back(int(l));
+    for (int e0 = 0; e0 < layers[l].d_out; e0 += kXt)
+      for (int c0 = 0; c0 < layers[l].d_in; c0 += kXt) all.push_back(int4{int(l), e0, c0, 0});
   }
-  std::stable_sort(idx.begin(), idx.end(), [&](int x, int y) { return cnt[x] > cnt[y]; });
   std::vector<std::vector<int4>> per(kNumXcd);
-  for (int l : idx) {
-    int best = 0;
-    for (int x = 1; x < kNumXcd; ++x)
-      if (per[x].size() < per[best].size()) best = x;
-    const int te = (layers[l].d_out + kXt - 1) / kXt, tc = (layers[l].d_in + kXt - 1) / kXt;
-    for (int a = 0; a < te; ++a)
-      for (int b = 0; b < tc; ++b) per[best].push_back(int4{l, a * kXt, b * kXt, 0});
-  }
+  for (int x = 0; x < kNumXcd; ++x)
+    for (size_t i = all.size() * x / kNumXcd; i < all.size() * (x + 1) / kNumXcd; ++i)
+      per[x].push_back(all[i]);
   split_tiles.clear();
   n_pieces = 0;
   std::vector<std::vector<int4>> fin(kNumXcd);
