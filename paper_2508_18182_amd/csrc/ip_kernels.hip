@@ -325,22 +325,30 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
 }
 
 // Statistics form: sums the partial tiles of the entries that were split along the samples, in
-// piece order (fixed order: repeatable), into grad_sum.  One workgroup per 16 rows of a split tile;
+// piece order (fixed order: repeatable), into grad_sum.  One workgroup per 4 rows of a split tile,
+// one thread per column, rows unrolled so that their loads are in flight together;
 // split[t] = (layer, e0, c0, pieces << 16 | first partial tile).
+constexpr int kIpRedRows = 4;
 __global__ __launch_bounds__(kIpC) void stats_tile_reduce_kernel(const LayerDev* layers, const int4* split,
                                                                 const float* partials, int accumulate) {
-  const int t = blockIdx.x / (kIpE / 16), r0 = (blockIdx.x % (kIpE / 16)) * 16;
+  const int t = blockIdx.x / (kIpE / kIpRedRows), r0 = (blockIdx.x % (kIpE / kIpRedRows)) * kIpRedRows;
   const int4 S = split[t];
   const LayerDev L = layers[S.x];
   const int pieces = S.w >> 16;
-  const float* base = partials + (size_t)(S.w & 0xffff) * (kIpE * kIpC);
-  for (int r = r0; r < r0 + 16; ++r) {
-    const int row = S.y + r, col = S.z + threadIdx.x;
+  const float* base = partials + (size_t)(S.w & 0xffff) * (kIpE * kIpC) + threadIdx.x;
+  const int col = S.z + threadIdx.x;
+  float v[kIpRedRows];
+#pragma unroll
+  for (int r = 0; r < kIpRedRows; ++r) v[r] = 0.f;
+  for (int p = 0; p < pieces; ++p)
+#pragma unroll
+    for (int r = 0; r < kIpRedRows; ++r) v[r] += base[(size_t)p * (kIpE * kIpC) + (r0 + r) * kIpC];
+#pragma unroll
+  for (int r = 0; r < kIpRedRows; ++r) {
+    const int row = S.y + r0 + r;
     if (row >= L.d_out || col >= L.d_in) continue;
-    float v = 0.f;
-    for (int p = 0; p < pieces; ++p) v += base[(size_t)p * (kIpE * kIpC) + r * kIpC + threadIdx.x];
     float* d = L.grad_sum + (size_t)row * L.d_in + col;
-    *d = accumulate ? *d + v : v;
+    *d = accumulate ? *d + v[r] : v[r];
   }
 }
 
@@ -525,7 +533,7 @@ hipError_t launch_stats_tiles(const LayerDev* layers, const void* tiles, const i
   IpTileArgs a{layers, static_cast<const int4*>(tiles), tile_out, slots, T, B, part, partial_tiles, accumulate};
   hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(512), kIpLds, st, a);
   if (n_split > 0)
-    hipLaunchKernelGGL(stats_tile_reduce_kernel, dim3(unsigned(n_split) * (kIpE / 16)), dim3(kIpC), 0, st,
+    hipLaunchKernelGGL(stats_tile_reduce_kernel, dim3(unsigned(n_split) * (kIpE / kIpRedRows)), dim3(kIpC), 0, st,
                        layers, static_cast<const int4*>(split), partial_tiles, accumulate);
   hipLaunchKernelGGL(stats_tile_finalize_kernel, dim3(unsigned(n_listed) * B), dim3(64), 0, st,
                      static_cast<const int4*>(tiles), tile_out, B, lay, ptr, idx, B, partials, n_pairs);

@@ -377,23 +377,31 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
 }
 
 // Sums the partial tiles of a split contraction in piece order (fixed order: repeatable) and
-// adds them to / stores them in grad_sum.  One workgroup per 16 rows of one split tile.
+// adds them to / stores them in grad_sum.  One workgroup per 4 rows of one split tile, one thread
+// per column, rows unrolled so that their loads are in flight together.
 struct WgradSplitTile { int layer, e0, c0, w; };   // w = (pieces << 16) | first partial tile
+constexpr int kXredRows = 4;
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const LayerDev* layers,
                                                            const WgradSplitTile* tiles,
                                                            const float* partials, int accumulate) {
-  const int t = blockIdx.x / 16, r0 = (blockIdx.x % 16) * 16;
+  const int t = blockIdx.x / (kXt / kXredRows), r0 = (blockIdx.x % (kXt / kXredRows)) * kXredRows;
   const WgradSplitTile S = tiles[t];
   const LayerDev L = layers[S.layer];
   const int pieces = S.w >> 16;
-  const float* base = partials + (size_t)(S.w & 0xffff) * (kXt * kXt);
-  for (int r = r0; r < r0 + 16; ++r) {
-    const int row = S.e0 + r, col = S.c0 + threadIdx.x;
+  const float* base = partials + (size_t)(S.w & 0xffff) * (kXt * kXt) + threadIdx.x;
+  const int col = S.c0 + threadIdx.x;
+  float v[kXredRows];
+#pragma unroll
+  for (int r = 0; r < kXredRows; ++r) v[r] = 0.f;
+  for (int p = 0; p < pieces; ++p)
+#pragma unroll
+    for (int r = 0; r < kXredRows; ++r) v[r] += base[(size_t)p * (kXt * kXt) + (r0 + r) * kXt];
+#pragma unroll
+  for (int r = 0; r < kXredRows; ++r) {
+    const int row = S.e0 + r0 + r;
     if (row >= L.d_out || col >= L.d_in) continue;
-    float v = 0.f;
-    for (int p = 0; p < pieces; ++p) v += base[(size_t)p * (kXt * kXt) + r * kXt + threadIdx.x];
     float* dst = L.grad_sum + (size_t)row * L.d_in + col;
-    *dst = accumulate ? *dst + v : v;
+    *dst = accumulate ? *dst + v[r] : v[r];
   }
 }
 
@@ -515,7 +523,7 @@ hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots,
   WgradXArgs a{layers, static_cast<const int4*>(tiles), partials, slots, rows, accumulate};
   hipLaunchKernelGGL(kern, dim3(unsigned(slots * kNumXcd)), dim3(512), kXlds, st, a);
   if (n_split > 0)
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(unsigned(n_split * 16)), dim3(256), 0, st, layers,
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(unsigned(n_split) * (kXt / kXredRows)), dim3(256), 0, st, layers,
                        static_cast<const WgradSplitTile*>(split_tiles), partials, accumulate);
   return hipGetLastError();
 }
