@@ -204,8 +204,9 @@ def measured_traffic():
         with open(path) as f:
             for ln in f:
                 parts = [p.strip() for p in ln.split("|")]
-                if len(parts) >= 5 and parts[1] in ("gram", "wgrad", "outer_step", "merge", "sqnorm",
-                                                     "vector_table", "inner_step", "inner_products"):
+                if len(parts) >= 5 and parts[1] in ("tile_stats", "gram", "wgrad", "outer_step", "merge",
+                                                     "sqnorm", "vector_table", "inner_step",
+                                                     "inner_products"):
                     out[parts[1]] = float(parts[2]) + float(parts[3])
     except OSError:
         pass
