@@ -273,12 +273,13 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
       t = t < T ? t : T - 1;
       row_off[s][i] = (long long)sample * T + t;
     }
-  auto issue_loads = [&](int c) {
+  // stage indices are carried along (no division in the loop): chunk c lives in stage c mod 3
+  auto issue_loads = [&](int c, int st) {
     const bool is_a = c < nka;
     const unsigned short* base = reinterpret_cast<const unsigned short*>(is_a ? L.a : L.delta);
     const long long stride = is_a ? L.a_stride : L.delta_stride;
     const int k0 = (is_a ? c : c - nka) * kKc + ld_col;
-    unsigned char* stage = lds + (c % kDualStages) * kDualStage;
+    unsigned char* stage = lds + st * kDualStage;
 #pragma unroll
     for (int s = 0; s < 3; ++s) {
       if (s < nblk) {
@@ -303,8 +304,8 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
     sw_a[m] = swz(ra, 0);
     sw_b[m] = swz(rb, 0);
   }
-  auto read_frags = [&](int c, int ks, bf16x8 (&fa)[2], bf16x8 (&fb)[2]) {
-    const unsigned char* stage = lds + (c % kDualStages) * kDualStage;
+  auto read_frags = [&](int st, int ks, bf16x8 (&fa)[2], bf16x8 (&fb)[2]) {
+    const unsigned char* stage = lds + st * kDualStage;
     const int chunk = ks * 2 + kg;
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
@@ -324,9 +325,9 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
       for (int j = 0; j < 16; ++j) { acc_a[m][n][j] = 0.f; acc_d[m][n][j] = 0.f; }
 
   // ---- prologue: chunks 0 and 1 in flight, chunk 0 landed for everybody
-  issue_loads(0);
+  issue_loads(0, 0);
   if (nk > 1) {
-    issue_loads(1);
+    issue_loads(1, 1);
     if (nblk == 3) wait_vmcnt<6>(); else if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
   } else {
     wait_vmcnt<0>();
@@ -348,25 +349,29 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
   };
+  int st_cur = 0, st_prev = kDualStages - 1;     // stages of chunk c and of chunk c-1
   auto chunk_step = [&](int c, f32x16 (&acc)[2][2]) {
+    const int st_next = st_cur + 1 == kDualStages ? 0 : st_cur + 1;
     // k-step 0
-    read_frags(c, 1, fa[1], fb[1]);
+    read_frags(st_cur, 1, fa[1], fb[1]);
     mfma4(fa[0], fb[0], acc);
     // k-step 1, with the barrier of this chunk in front of it
     if (c + 1 < nk) {
       wait_vmcnt<0>();        // my share of chunk c+1 (the only loads in flight) has landed
-      wg_barrier();           // ... and so has everybody's; stage (c-1)%3 is free
-      if (c + 2 < nk) issue_loads(c + 2);
+      wg_barrier();           // ... and so has everybody's; the stage of chunk c-1 is free
+      if (c + 2 < nk) issue_loads(c + 2, st_prev);
     }
-    read_frags(c, 2, fa[0], fb[0]);
+    read_frags(st_cur, 2, fa[0], fb[0]);
     mfma4(fa[1], fb[1], acc);
     // k-step 2
-    read_frags(c, 3, fa[1], fb[1]);
+    read_frags(st_cur, 3, fa[1], fb[1]);
     mfma4(fa[0], fb[0], acc);
     // k-step 3: fragments of the next chunk's first k-step (after the last chunk: a harmless
     // re-read of this chunk, so that the reads stay interleaved with the MFMAs)
-    read_frags(c + 1 < nk ? c + 1 : c, 0, fa[0], fb[0]);
+    read_frags(c + 1 < nk ? st_next : st_cur, 0, fa[0], fb[0]);
     mfma4(fa[1], fb[1], acc);
+    st_prev = st_cur;
+    st_cur = st_next;
   };
   int c = 0;
   for (; c < nka; ++c) chunk_step(c, acc_a);

@@ -54,7 +54,7 @@ constexpr int kIpOpE = 16 * kIpBlk;               // delta side of a stage
 constexpr int kIpOpC = 8 * kIpBlk;                // a side of a stage
 constexpr int kIpStage = kIpOpE + kIpOpC;         // 25.5 KiB
 constexpr int kIpStages = 4;
-constexpr int kIpLds = kIpStages * kIpStage;      // 102 KiB
+constexpr int kIpLds = kIpStages * kIpStage;      // 153 KiB
 
 struct IpTileArgs {
   const LayerDev* layers;
@@ -155,8 +155,9 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
     lds_off[i] = (is_a ? kIpOpE : 0) + j * kIpBlk;
   }
   const unsigned lds_base = lds_address(lds);       // LDS byte addresses are handled as integers
-  auto issue_loads = [&](long long c) {
-    const unsigned stage = lds_base + unsigned(c % kIpStages) * kIpStage;
+  // stage indices are carried along (no modulo in the loop: kIpStages need not be a power of two)
+  auto issue_loads = [&](long long c, int st) {
+    const unsigned stage = lds_base + unsigned(st) * kIpStage;
 #pragma unroll
     for (int i = 0; i < 3; ++i)
       direct_load_lds16(src_base[i] + c * kIpK * src_stride[i], stage + lds_off[i]);
@@ -176,8 +177,8 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
     ip_s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(ip_bf16x8, v);
   };
-  auto read_frags = [&](long long c, int ks, ip_bf16x8 (&fa)[2], ip_bf16x8 (&fb)[2]) {
-    const unsigned stage = lds_base + unsigned(c % kIpStages) * kIpStage;
+  auto read_frags = [&](int st, int ks, ip_bf16x8 (&fa)[2], ip_bf16x8 (&fb)[2]) {
+    const unsigned stage = lds_base + unsigned(st) * kIpStage;
     const int r0 = ks * 16 + krow, r1 = r0 + 4;
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
@@ -213,9 +214,10 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
     }
   };
 
-  if (nk > 0) issue_loads(0);
-  if (nk > 1) issue_loads(1);
-  if (nk > 2) issue_loads(2);
+  // prologue: chunks 0 .. kIpStages-2 in flight
+#pragma unroll
+  for (int s = 0; s < kIpStages - 1; ++s)
+    if (s < nk) issue_loads(s, s);
   // The G registers are needed only at the end of the first sample, but a wait placed there by the
   // compiler would drain the load pipeline at every sample; pin them down here, once.
   if (MODE == 0) {
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) asm volatile("" : "+v"(gt[m][n][j]));
   }
-  if (nk > 2) ip_wait_vmcnt<6>(); else if (nk > 1) ip_wait_vmcnt<3>(); else ip_wait_vmcnt<0>();
+  if (nk >= kIpStages - 1) ip_wait_vmcnt<3 * (kIpStages - 2)>(); else ip_wait_vmcnt<0>();
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -235,20 +237,24 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
   float* dst = g.out + ((size_t(xcd) * g.slots + slot) * g.group * 8 + wave) * 2;
   ip_bf16x8 fa[2][2], fb[2][2];
   read_frags(0, 0, fa[0], fb[0]);
+  int st_cur = 0, st_load = kIpStages - 1;        // stage of chunk c; stage that chunk c-1 frees
   for (long long c = 0; c < nk; ++c) {
-    read_frags(c, 1, fa[1], fb[1]);
+    const int st_next = st_cur + 1 == kIpStages ? 0 : st_cur + 1;
+    read_frags(st_cur, 1, fa[1], fb[1]);
     mfma4(fa[0], fb[0]);
     if (c + 1 < nk) {
-      // chunk c+1 has landed for me (chunk c+2 may still be in flight), then for everybody;
-      // every wave is done with chunk c-1, whose stage takes chunk c+3
-      if (c + 2 < nk) ip_wait_vmcnt<3>(); else ip_wait_vmcnt<0>();
+      // chunk c+1 has landed for me (the chunks behind it may still be in flight), then for
+      // everybody; every wave is done with chunk c-1, whose stage takes chunk c-1+kIpStages
+      if (c + kIpStages - 2 < nk) ip_wait_vmcnt<3 * (kIpStages - 3)>(); else ip_wait_vmcnt<0>();
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (c + 3 < nk) issue_loads(c + 3);
+      if (c + kIpStages - 1 < nk) issue_loads(c + kIpStages - 1, st_load);
     }
-    read_frags(c + 1 < nk ? c + 1 : c, 0, fa[0], fb[0]);
+    read_frags(c + 1 < nk ? st_next : st_cur, 0, fa[0], fb[0]);
     mfma4(fa[1], fb[1]);
+    st_load = st_cur;
+    st_cur = st_next;
     if (--left == 0) {
       // the sample's tile is complete: reduce it against the G tile, clear it
       float dot = 0.f, sq = 0.f;
