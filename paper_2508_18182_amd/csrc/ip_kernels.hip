@@ -53,6 +53,14 @@ constexpr int kIpBlk = 1024 + 64;                 // one load instruction + 64 B
 constexpr int kIpOpE = 16 * kIpBlk;               // delta side of a stage
 constexpr int kIpOpC = 8 * kIpBlk;                // a side of a stage
 constexpr int kIpStage = kIpOpE + kIpOpC;         // 25.5 KiB
+#ifndef IP_WM
+#define IP_WM 4
+#endif
+constexpr int kIpWM = IP_WM, kIpWN = 2;           // waves along d_out and d_in
+constexpr int kIpWaves = kIpWM * kIpWN;
+constexpr int kIpFM = kIpE / (32 * kIpWM);        // 32x32 MFMA blocks per wave along d_out
+constexpr int kIpFN = kIpC / (32 * kIpWN);        // ... along d_in
+constexpr int kIpLdE = 16 / kIpWaves, kIpLdC = 8 / kIpWaves, kIpLd = kIpLdE + kIpLdC;   // loads per wave
 constexpr int kIpStages = 4;
 constexpr int kIpLds = kIpStages * kIpStage;      // 153 KiB
 
@@ -99,7 +107,7 @@ __device__ __forceinline__ int ip_row_off_c(int row) { return (row & 7) * kIpBlk
 //         when G has to be formed here anyway, its per-sample terms pass through the registers
 //         and the Gram contraction is not needed).
 template <int MODE, bool SQ>
-__global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
+__global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
   const int4 tile = g.tiles[xcd * g.slots + slot];
@@ -108,22 +116,22 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
   const int e0 = tile.y, c0 = tile.z;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 1, wn = wave & 1;        // 4 x 2 waves; wave tile 64 (e) x 64 (c)
+  const int wm = wave / kIpWN, wn = wave % kIpWN;  // kIpWM x kIpWN waves
   const int nk_sample = g.T / kIpK;               // chunks per sample
   const long long ck0 = (long long)(tile.w & 0xffff) * nk_sample;
   const long long nk = (long long)(tile.w >> 16) * nk_sample;
 
   // ---- this lane's entries of the G tile.  Accumulator element j of a 32x32 block: row
   // (j/4)*8 + (lane/32)*4 + j%4, column lane%32.  Entries past the edge are zero.
-  float gt[2][2][16];
+  float gt[kIpFM][kIpFN][16];
 #pragma unroll
-  for (int m = 0; m < 2; ++m)
+  for (int m = 0; m < kIpFM; ++m)
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      const int tc = c0 + wn * 64 + n * 32 + (lane & 31);
+    for (int n = 0; n < kIpFN; ++n) {
+      const int tc = c0 + wn * (32 * kIpFN) + n * 32 + (lane & 31);
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const int tr = e0 + wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        const int tr = e0 + wm * (32 * kIpFM) + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
         if (MODE == 0) {
           const bool ok = tr < L.d_out && tc < L.d_in;
           const float v = L.grad_sum[ok ? (size_t)tr * L.d_in + tc : 0];
@@ -137,13 +145,13 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
 
   // ---- direct loads, three per wave and chunk: delta instructions wave and wave + 8 (rows j and
   // j + 16, 16-byte piece lane % 32), a instruction wave (rows j + 8 * (lane / 16), piece lane % 16)
-  const unsigned short* src_base[3];
-  long long src_stride[3];
-  int lds_off[3];
+  const unsigned short* src_base[kIpLd];
+  long long src_stride[kIpLd];
+  int lds_off[kIpLd];
 #pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    const bool is_a = i == 2;
-    const int j = is_a ? wave : wave + 8 * i;
+  for (int i = 0; i < kIpLd; ++i) {
+    const bool is_a = i >= kIpLdE;
+    const int j = wave + kIpWaves * (is_a ? i - kIpLdE : i);
     const int row = is_a ? j + 8 * (lane >> 4) : j + 16 * (lane >> 5);
     const int piece = is_a ? (lane & 15) : (lane & 31);
     const int d = is_a ? L.d_in : L.d_out;
@@ -159,7 +167,7 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
   auto issue_loads = [&](long long c, int st) {
     const unsigned stage = lds_base + unsigned(st) * kIpStage;
 #pragma unroll
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < kIpLd; ++i)
       direct_load_lds16(src_base[i] + c * kIpK * src_stride[i], stage + lds_off[i]);
   };
 
@@ -177,41 +185,43 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
     ip_s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(ip_bf16x8, v);
   };
-  auto read_frags = [&](int st, int ks, ip_bf16x8 (&fa)[2], ip_bf16x8 (&fb)[2]) {
+  auto read_frags = [&](int st, int ks, ip_bf16x8 (&fa)[kIpFM], ip_bf16x8 (&fb)[kIpFN]) {
     const unsigned stage = lds_base + unsigned(st) * kIpStage;
     const int r0 = ks * 16 + krow, r1 = r0 + 4;
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-      const int col = wm * 64 + m * 32 + ccol;
+    for (int m = 0; m < kIpFM; ++m) {
+      const int col = wm * (32 * kIpFM) + m * 32 + ccol;
       fa[m] = frag(stage + ip_row_off_e(r0) + col * 2, stage + ip_row_off_e(r1) + col * 2);
     }
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      const int col = wn * 64 + n * 32 + ccol;
+    for (int n = 0; n < kIpFN; ++n) {
+      const int col = wn * (32 * kIpFN) + n * 32 + ccol;
       fb[n] = frag(stage + kIpOpE + ip_row_off_c(r0) + col * 2, stage + kIpOpE + ip_row_off_c(r1) + col * 2);
     }
   };
 
-  ip_f32x16 acc[2][2];
+  ip_f32x16 acc[kIpFM][kIpFN];
 #pragma unroll
-  for (int m = 0; m < 2; ++m)
+  for (int m = 0; m < kIpFM; ++m)
 #pragma unroll
-    for (int n = 0; n < 2; ++n)
+    for (int n = 0; n < kIpFN; ++n)
 #pragma unroll
       for (int j = 0; j < 16; ++j) acc[m][n][j] = 0.f;
 
-  auto mfma4 = [&](const ip_bf16x8 (&a)[2], const ip_bf16x8 (&b)[2]) {
+  auto mfma4 = [&](const ip_bf16x8 (&a)[kIpFM], const ip_bf16x8 (&b)[kIpFN]) {
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+    for (int m = 0; m < kIpFM; ++m)
 #pragma unroll
-      for (int n = 0; n < 2; ++n)
+      for (int n = 0; n < kIpFN; ++n)
         acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
-    // the 8 LDS reads of the next k-step go out two at a time behind the MFMAs
+    // the LDS reads of the next k-step go out two at a time behind the first MFMAs
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kIpFM + kIpFN; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
     }
+    if (kIpFM * kIpFN > kIpFM + kIpFN)
+      __builtin_amdgcn_sched_group_barrier(0x008, kIpFM * kIpFN - kIpFM - kIpFN, 0);
   };
 
   // prologue: chunks 0 .. kIpStages-2 in flight
@@ -222,20 +232,20 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
   // compiler would drain the load pipeline at every sample; pin them down here, once.
   if (MODE == 0) {
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+    for (int m = 0; m < kIpFM; ++m)
 #pragma unroll
-      for (int n = 0; n < 2; ++n)
+      for (int n = 0; n < kIpFN; ++n)
 #pragma unroll
         for (int j = 0; j < 16; ++j) asm volatile("" : "+v"(gt[m][n][j]));
   }
-  if (nk >= kIpStages - 1) ip_wait_vmcnt<3 * (kIpStages - 2)>(); else ip_wait_vmcnt<0>();
+  if (nk >= kIpStages - 1) ip_wait_vmcnt<kIpLd * (kIpStages - 2)>(); else ip_wait_vmcnt<0>();
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
   int left = nk_sample, sample_out = 0;
-  float* dst = g.out + ((size_t(xcd) * g.slots + slot) * g.group * 8 + wave) * 2;
-  ip_bf16x8 fa[2][2], fb[2][2];
+  float* dst = g.out + ((size_t(xcd) * g.slots + slot) * g.group * kIpWaves + wave) * 2;
+  ip_bf16x8 fa[2][kIpFM], fb[2][kIpFN];
   read_frags(0, 0, fa[0], fb[0]);
   int st_cur = 0, st_load = kIpStages - 1;        // stage of chunk c; stage that chunk c-1 frees
   for (long long c = 0; c < nk; ++c) {
@@ -245,7 +255,7 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
     if (c + 1 < nk) {
       // chunk c+1 has landed for me (the chunks behind it may still be in flight), then for
       // everybody; every wave is done with chunk c-1, whose stage takes chunk c-1+kIpStages
-      if (c + kIpStages - 2 < nk) ip_wait_vmcnt<3 * (kIpStages - 3)>(); else ip_wait_vmcnt<0>();
+      if (c + kIpStages - 2 < nk) ip_wait_vmcnt<kIpLd * (kIpStages - 3)>(); else ip_wait_vmcnt<0>();
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
@@ -260,9 +270,9 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
       float dot = 0.f, sq = 0.f;
       if (!ragged) {
 #pragma unroll
-        for (int m = 0; m < 2; ++m)
+        for (int m = 0; m < kIpFM; ++m)
 #pragma unroll
-          for (int n = 0; n < 2; ++n)
+          for (int n = 0; n < kIpFN; ++n)
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
               const float v = acc[m][n][j];
@@ -276,11 +286,11 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
         // they meet zeros in the G registers (MODE 0) or are never stored (MODE 1), but must not
         // enter the sum of squares
 #pragma unroll
-        for (int m = 0; m < 2; ++m)
+        for (int m = 0; m < kIpFM; ++m)
 #pragma unroll
-          for (int n = 0; n < 2; ++n) {
-            const bool col_ok = c0 + wn * 64 + n * 32 + (lane & 31) < L.d_in;
-            const int tr0 = e0 + wm * 64 + m * 32 + (lane >> 5) * 4;
+          for (int n = 0; n < kIpFN; ++n) {
+            const bool col_ok = c0 + wn * (32 * kIpFN) + n * 32 + (lane & 31) < L.d_in;
+            const int tr0 = e0 + wm * (32 * kIpFM) + m * 32 + (lane >> 5) * 4;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
               const float v = acc[m][n][j];
@@ -298,10 +308,10 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
       if (SQ) sq = ip_wave_sum_f32(sq);
       if (lane == 0) {
         if (MODE == 0) {
-          dst[size_t(sample_out) * 16] = dot;
-          dst[size_t(sample_out) * 16 + 1] = sq;
+          dst[size_t(sample_out) * (2 * kIpWaves)] = dot;
+          dst[size_t(sample_out) * (2 * kIpWaves) + 1] = sq;
         } else {
-          dst[size_t(sample_out) * 16] = sq;
+          dst[size_t(sample_out) * (2 * kIpWaves)] = sq;
         }
       }
       ++sample_out;
@@ -312,13 +322,13 @@ __global__ __launch_bounds__(512, 1) void ip_tile_kernel(IpTileArgs g) {
     const int part = g.part[xcd * g.slots + slot];
     float* pt = part >= 0 ? g.partials + (size_t)part * (kIpE * kIpC) : nullptr;
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+    for (int m = 0; m < kIpFM; ++m)
 #pragma unroll
-      for (int n = 0; n < 2; ++n) {
-        const int tc = wn * 64 + n * 32 + (lane & 31);
+      for (int n = 0; n < kIpFN; ++n) {
+        const int tc = wn * (32 * kIpFN) + n * 32 + (lane & 31);
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-          const int tr = wm * 64 + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+          const int tr = wm * (32 * kIpFM) + m * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
           if (pt) {
             pt[tr * kIpC + tc] = gt[m][n][j];
           } else if (e0 + tr < L.d_out && c0 + tc < L.d_in) {
@@ -373,9 +383,9 @@ __global__ __launch_bounds__(64) void stats_tile_finalize_kernel(const int4* til
     const int4 t = tiles[e];
     const int s0 = t.w & 0xffff, cnt = t.w >> 16;
     if (i >= s0 && i < s0 + cnt) {
-      const float* o = out + ((size_t)e * group + (i - s0)) * 16;
+      const float* o = out + ((size_t)e * group + (i - s0)) * (2 * kIpWaves);
 #pragma unroll
-      for (int w = 0; w < 8; ++w) s += double(o[2 * w]);
+      for (int w = 0; w < kIpWaves; ++w) s += double(o[2 * w]);
     }
   }
   s = ip_wave_sum(s);
@@ -450,7 +460,7 @@ hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots,
     if (e != hipSuccess) return e;
   }
   IpTileArgs a{layers, static_cast<const int4*>(tiles), ip_out, slots, T, group, nullptr, nullptr, 0};
-  hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(512), kIpLds, st, a);
+  hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(64 * kIpWaves), kIpLds, st, a);
   return hipGetLastError();
 }
 
@@ -537,7 +547,7 @@ hipError_t launch_stats_tiles(const LayerDev* layers, const void* tiles, const i
     if (e != hipSuccess) return e;
   }
   IpTileArgs a{layers, static_cast<const int4*>(tiles), tile_out, slots, T, B, part, partial_tiles, accumulate};
-  hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(512), kIpLds, st, a);
+  hipLaunchKernelGGL(kern, dim3(unsigned(slots) * kNumXcd), dim3(64 * kIpWaves), kIpLds, st, a);
   if (n_split > 0)
     hipLaunchKernelGGL(stats_tile_reduce_kernel, dim3(unsigned(n_split) * (kIpE / kIpRedRows)), dim3(kIpC), 0, st,
                        layers, static_cast<const int4*>(split), partial_tiles, accumulate);
@@ -642,9 +652,9 @@ __global__ __launch_bounds__(kIpThreads) void ip_finalize_samples_kernel(
     const int4 t = tiles[k];
     const int s0 = t.w & 0xffff, cnt = t.w >> 16;
     if (t.x >= 0 && i >= s0 && i < s0 + cnt) {
-      const float* o = tile_out + ((size_t)k * group + (i - s0)) * 16;
+      const float* o = tile_out + ((size_t)k * group + (i - s0)) * (2 * kIpWaves);
 #pragma unroll
-      for (int w = 0; w < 8; ++w) {
+      for (int w = 0; w < kIpWaves; ++w) {
         c += double(o[2 * w]);
         q += double(o[2 * w + 1]);
       }
