@@ -143,7 +143,28 @@ def vector_table_leg(torch, synth, A, ctx, layers, B, T, dev, steps):
     torch.cuda.synchronize()
     ms, n = ctx.profile_read("vector_table")
     ms = ms / n if n else None
+    # the whole parameter list of the model in one call (linear weights + these blocks): the
+    # vector / table kernels run on a second stream next to the tile-statistics kernel
+    both = list(layers) + blocks
+    for l in layers:
+        l["provided"] = False
+    d_both = A.make_layer_descs(both, B, T, A.ADLOCO_BF16)
+    combined = {}
+    for overlap in (1, 0):
+        ctx.set_tuning("overlap_aux", overlap)
+        for _ in range(2):
+            A.adloco_grad_stats(ctx, both, B, T, A.ADLOCO_BF16, ps, None, acc, 0, descs=d_both)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            A.adloco_grad_stats(ctx, both, B, T, A.ADLOCO_BF16, ps, None, acc, 0, descs=d_both)
+        torch.cuda.synchronize()
+        combined["overlapped" if overlap else "serial"] = (time.perf_counter() - t0) / steps * 1e3
+    ctx.set_tuning("overlap_aux", 1)
+    for k in ("vector_table", "tile_stats", "gram", "wgrad", "finalize", "sqnorm"):
+        ctx.profile_read(k)
     return dict(bound="hbm", kernel="vector_rowsum_kernel + embed_rows_kernel (+ small reductions)",
+                all_blocks_of_the_model_ms=combined,
                 blocks=len(blocks), avg_kernel_ms=ms, bytes_algorithmic=nbytes,
                 achieved=(nbytes / (ms * 1e-3) / 1e9) if ms else None, peak=PEAK_HBM / 1e9, unit="GB/s",
                 frac=(nbytes / (ms * 1e-3) / PEAK_HBM) if ms else None, traffic=None)

@@ -70,7 +70,7 @@ int adloco_destroy(adloco_ctx* ctx);
 const char* adloco_last_error(const adloco_ctx* ctx);
 
 /* Tuning knob for benchmarking kernel variants ("gram_variant", "wgrad_variant",
- * "stream_blocks_per_cu", "ip_group", "stats_variant", ...).  Unknown names give ADLOCO_EINVAL.  Results never depend on
+ * "stream_blocks_per_cu", "ip_group", "stats_variant", "overlap_aux", ...).  Unknown names give ADLOCO_EINVAL.  Results never depend on
  * a knob beyond floating-point summation order. */
 int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
 
@@ -116,7 +116,9 @@ typedef struct {
  *     tokens with id v, so ||g_i||^2 = sum_{t,t'} [id_t = id_t'] delta_t . delta_t'.  The table
  *     gradient itself is the caller's: ADLOCO_GRAD_PROVIDED is required, grad_sum [V, d_out] is
  *     only read (by adloco_norm_test) and may be NULL in adloco_grad_stats.  T <= 8192.
- * Both kinds stream delta (and x) once; their sums run in a fixed order. */
+ * Both kinds stream delta (and x) once; their sums run in a fixed order.  In a call that also
+ * holds linear blocks their kernels run on a second stream owned by the context, forked from
+ * and joined to `stream` by events inside the call ("overlap_aux" = 0 keeps them in line). */
 
 /* Running accumulator of one (possibly accumulated) batch; lives in device memory, owned by
  * the caller (16 bytes, 8-byte aligned). */

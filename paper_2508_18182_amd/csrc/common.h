@@ -113,6 +113,11 @@ struct adloco_ctx {
   int ts_slots = 0, ts_n_split = 0, ts_n_listed = 0, ts_idx_len = 0, ts_B = -1;
   bool ts_ok = false;          // every linear block is aligned bf16 with its gradient sum formed here
   int stats_variant = 1;       // 1: tile form when eligible; 0: Gram + gradient-sum kernels
+  // the vector / table kernels (HBM-bound) run next to the kernels of the linear blocks (MFMA /
+  // L2-bound) on a second stream, forked from and joined to the caller's stream by events
+  hipStream_t side_stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  int overlap_aux = 1;
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
   double* pinned = nullptr;    // 8 doubles of pinned host memory (read-back of the tests' sums)

@@ -144,6 +144,9 @@ extern "C" int adloco_destroy(adloco_ctx* ctx) {
     (void)hipEventDestroy(r.stop);
   }
   for (hipEvent_t e : ctx->prof_free) (void)hipEventDestroy(e);
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  if (ctx->side_stream) (void)hipStreamDestroy(ctx->side_stream);
   if (ctx->dev_scalars) (void)hipFree(ctx->dev_scalars);
   if (ctx->pinned) (void)hipHostFree(ctx->pinned);
   delete ctx;
@@ -167,6 +170,8 @@ extern "C" int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value) {
     if (value < 0 || value > 0x7fff) return fail(ctx, ADLOCO_EINVAL, "ip_group out of range");
     ctx->ip_group_tuning = value;
     ctx->ip_B = ctx->ip_T = -1;
+  } else if (n == "overlap_aux") {
+    ctx->overlap_aux = value ? 1 : 0;
   } else if (n == "stats_variant") {
     ctx->stats_variant = value ? 1 : 0;
   } else if (n == "stream_variant") ctx->stream_variant = value;

@@ -320,6 +320,41 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   g.partials = static_cast<float*>(ctx->partials.ptr);
   g.n_pairs = int(n_pairs);
   g.tile = tile;
+  // ---- vector / table blocks.  With linear blocks in the same call they go to a second stream:
+  // they are HBM-bound, the kernels of the linear blocks MFMA / L2-bound, and both fit on a CU.
+  const bool have_aux = !ctx->vec_host.empty() || !ctx->emb_host.empty();
+  bool fork = have_aux && ctx->n_linear > 0 && ctx->overlap_aux != 0;
+  if (fork && !ctx->side_stream) {
+    if (hipStreamCreateWithFlags(&ctx->side_stream, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      fork = false;                      // no second stream: run in line
+    }
+  }
+  hipStream_t aux_st = fork ? ctx->side_stream : st;
+  auto launch_aux = [&]() -> int {
+    hipEvent_t ev_aux = prof_begin(ctx, aux_st);
+    hipError_t ea = launch_vector_stats(g.layers, static_cast<const AuxDesc*>(ctx->vec_tab.ptr),
+                                        int(ctx->vec_host.size()), ctx->vec_blocks, ctx->vec_blocks2, B, T,
+                                        dtype, static_cast<float*>(ctx->aux_vec.ptr), g.partials,
+                                        int(n_pairs), accumulate, true, aux_st);
+    if (ea == hipSuccess)
+      ea = launch_embed_stats(g.layers, static_cast<const AuxDesc*>(ctx->emb_tab.ptr),
+                              int(ctx->emb_host.size()), ctx->emb_blocks, B, T, dtype,
+                              static_cast<int*>(ctx->aux_perm.ptr),
+                              static_cast<double*>(ctx->aux_part.ptr), g.partials, int(n_pairs), aux_st);
+    prof_end(ctx, kProfVecTab, ev_aux, aux_st);
+    if (ea != hipSuccess)
+      return fail(ctx, ADLOCO_EHIP, "grad_stats: vector / table launch failed: %s", hipGetErrorString(ea));
+    return ADLOCO_OK;
+  };
+  if (fork) {
+    ADLOCO_HIP_CHECK(ctx, hipEventRecord(ctx->ev_fork, st));
+    ADLOCO_HIP_CHECK(ctx, hipStreamWaitEvent(aux_st, ctx->ev_fork, 0));
+    rc = launch_aux();
+    if (rc) return rc;
+  }
   hipEvent_t ev = nullptr;
   hipError_t e = hipSuccess;
   if (tile_form) {
@@ -362,21 +397,13 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   prof_end(ctx, kProfWgrad, ev, st);
   if (e != hipSuccess)
     return fail(ctx, ADLOCO_EHIP, "grad_stats: gradient-sum launch failed: %s", hipGetErrorString(e));
-  if (!ctx->vec_host.empty() || !ctx->emb_host.empty()) {
-    ev = prof_begin(ctx, st);
-    e = launch_vector_stats(g.layers, static_cast<const AuxDesc*>(ctx->vec_tab.ptr),
-                            int(ctx->vec_host.size()), ctx->vec_blocks, ctx->vec_blocks2, B, T, dtype,
-                            static_cast<float*>(ctx->aux_vec.ptr), g.partials, int(n_pairs),
-                            accumulate, true, st);
-    if (e == hipSuccess)
-      e = launch_embed_stats(g.layers, static_cast<const AuxDesc*>(ctx->emb_tab.ptr),
-                             int(ctx->emb_host.size()), ctx->emb_blocks, B, T, dtype,
-                             static_cast<int*>(ctx->aux_perm.ptr),
-                             static_cast<double*>(ctx->aux_part.ptr), g.partials, int(n_pairs), st);
-    prof_end(ctx, kProfVecTab, ev, st);
-    if (e != hipSuccess)
-      return fail(ctx, ADLOCO_EHIP, "grad_stats: vector / table launch failed: %s",
-                  hipGetErrorString(e));
+  if (have_aux && !fork) {
+    rc = launch_aux();
+    if (rc) return rc;
+  }
+  if (fork) {
+    ADLOCO_HIP_CHECK(ctx, hipEventRecord(ctx->ev_join, aux_st));
+    ADLOCO_HIP_CHECK(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
   }
   e = launch_finalize_stats(g.partials, n_layers, B, int(n_pairs), per_sample_sqnorm,
                             per_layer_sample_sqnorm, static_cast<double*>(ctx->sample_f64.ptr),
