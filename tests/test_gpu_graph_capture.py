@@ -1,0 +1,96 @@
+"""The device-only entry points can be captured into a HIP graph by the caller (here through
+torch.cuda.graph): after one eager call on the same layer list (descriptor tables and scratch are
+set up then; nothing is allocated or copied from the host afterwards) a captured adloco_grad_stats
+-- tile statistics, the vector / table kernels forked onto the context's second stream, reductions
+-- adloco_outer_step, adloco_merge and adloco_inner_step replay bit for bit.  Every replay is
+checked against the eager result, with eager work and synchronisations between the replays.
+(adloco_norm_test reads scalars back to the host and is not capturable.)"""
+import numpy as np
+import pytest
+
+import adloco_synth as synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_graph_replays_match_eager():
+    import torch
+    import paper_2508_18182_amd as A
+    from gpu_util import to_dev, DEV
+    ctx = A.Context(0)
+    B, T, d = 4, 64, 256
+    lin = synth.custom_grad_stats_inputs(7700, [(d, 2 * d), (2 * d, d)], B, T, "bf16", std_delta=0.1, rho=0.3)
+    aux = synth.vector_table_inputs(7701, B, T, "bf16", [(d, True), (d, False)], [(50, d)],
+                                    std_delta=0.1, rho=0.3)
+    layers = [dict(a=to_dev(e["a"]), delta=to_dev(e["delta"]),
+                   grad_sum=torch.zeros(e["d_out"], e["d_in"], device=DEV)) for e in lin]
+    for e in aux:
+        if e["kind"] == "vector":
+            layers.append(dict(kind="vector", x=None if e["x"] is None else to_dev(e["x"]),
+                               delta=to_dev(e["delta"]), grad_sum=torch.zeros(e["d"], device=DEV)))
+        else:
+            layers.append(dict(kind="embed", ids=torch.from_numpy(e["ids"]).to(DEV), vocab=e["vocab"],
+                               delta=to_dev(e["delta"]), grad_sum=None))
+    descs = A.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
+    ps = torch.zeros(B, device=DEV)
+    pl = torch.zeros(len(layers), B, device=DEV)
+    acc = torch.zeros(2, dtype=torch.float64, device=DEV)
+    N, M = 100_003, 3
+    theta0, insts0, mom0 = [x for x in synth.outer_inputs(1, N=N, M=M)][:3]
+    theta = torch.from_numpy(theta0).to(DEV)
+    insts = [torch.from_numpy(x).to(DEV) for x in insts0]
+    mom = torch.from_numpy(mom0).to(DEV)
+    m1 = torch.zeros(N, device=DEV)
+    m2 = torch.zeros(N, device=DEV)
+    grad = torch.from_numpy(synth.normal_f32(7702, (N,), 1.0)).to(DEV)
+    state0 = [t.clone() for t in (theta, mom, m1, m2, *insts)]
+
+    def run():
+        A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, ps, pl, acc, 0, descs=descs)
+        A.adloco_inner_step(ctx, insts[0], m1, m2, grad, step=1, lr=4e-4, weight_decay=0.1, grad_scale=0.25)
+        A.adloco_outer_step(ctx, theta, insts, mom, 0.7, 0.9, True)
+        A.adloco_merge(ctx, insts, [3.0, 1.0, 2.0])
+
+    def reset():
+        for t, t0 in zip((theta, mom, m1, m2, *insts), state0):
+            t.copy_(t0)
+        ps.fill_(-1.0)
+        pl.fill_(-1.0)
+        acc.fill_(-1.0)
+        for l in layers:
+            if l.get("grad_sum") is not None:
+                l["grad_sum"].fill_(7.0)
+
+    def snapshot():
+        return [t.clone() for t in (ps, pl, acc, theta, mom, m1, m2, *insts,
+                                    *[l["grad_sum"] for l in layers if l.get("grad_sum") is not None])]
+
+    reset()
+    run()
+    torch.cuda.synchronize()
+    want = snapshot()
+    s = torch.cuda.Stream()
+    reset()
+    with torch.cuda.stream(s):
+        run()                                   # eager once on the capture stream
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    reset()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        run()
+    for rep in range(4):
+        reset()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = snapshot()
+        for k, (a, b) in enumerate(zip(got, want)):
+            assert torch.equal(a, b), (rep, k)
+        # eager work of the program itself between the replays
+        reset()
+        run()
+        torch.cuda.synchronize()
+        for k, (a, b) in enumerate(zip(snapshot(), want)):
+            assert torch.equal(a, b), ("eager", rep, k)
+    ctx.close()
