@@ -1,9 +1,14 @@
-// Per-sample inner products c_i = <g_i, G> with the batch gradient sum G, the quantity whose
-// variance the inner-product test and the augmented inner-product test of Section 3.3.2 need.
-// For aligned bf16 linear layers the tiles of each per-sample gradient g_i = delta_i^T a_i are
-// formed in registers by MFMA and reduced against the fp32 tile of G on the spot (ip_tile_kernel);
-// a plain path covers everything else, and the vector / table blocks and reductions follow.  As a by-product every path also returns
-// the explicit ||g_i||^2, a second route to the Gram kernel's result.
+// Kernels that form the per-sample gradients g_i = delta_i^T a_i of the linear layers tile by tile
+// in registers (never in memory) and reduce each tile on the spot:
+//   * inner products c_i = <g_i, G> with the batch gradient sum G, whose variance the
+//     inner-product test and the augmented inner-product test of Section 3.3.2 need;
+//   * the statistics of the norm test (eq. 4, Section 3.3.1): ||g_i||^2 from the squares of the
+//     tiles while they are being added up to G -- the route of adloco_grad_stats where G is
+//     formed by the library.
+// Aligned bf16 layers take the MFMA tile kernel (ip_tile_kernel); a plain path covers every other
+// layer for the inner products, and the dot kernels of the vector / table blocks and the
+// reductions follow.  The inner-product paths also return the explicit ||g_i||^2, a second
+// route to the Gram kernel's result.
 #include "common.h"
 
 namespace adloco {
@@ -29,13 +34,17 @@ __device__ __forceinline__ double ip_block_sum(double v, double* lds4) {
 // ---------------------------------------------------------------------------------------
 // Tile path (aligned bf16 linear layers, T a multiple of 32).
 // Work item = one 256 (d_out) x 128 (d_in) tile of one layer for a run of consecutive samples.
-// The workgroup (8 waves as 4 x 2, wave tile 64 x 64) first loads its tile of G into registers
-// (64 per lane, in the MFMA accumulator layout), then streams the token rows of its samples
+// The workgroup (8 waves as 4 x 2, wave tile 64 x 64) streams the token rows of its samples
 // through one uninterrupted load pipeline: the rows of consecutive samples are consecutive in
-// memory.  Every T rows the accumulators hold that sample's gradient tile: it is multiplied
-// element-wise with the G registers, summed over the wave and cleared; only two floats per
-// (tile, sample, wave) leave the chip.  A 256 x 256 tile would need 128 accumulators + 128
-// registers of G per lane, the whole register file at two waves per SIMD.
+// memory.  Every T rows the accumulators hold that sample's gradient tile.  A second set of 64
+// registers per lane, in the MFMA accumulator layout, holds
+//   MODE 0 (inner products): the tile of G; the finished sample tile is multiplied element-wise
+//     with it, summed over the wave and cleared; two floats per (tile, sample, wave) leave the chip;
+//   MODE 1 (statistics): the running sum of the sample tiles; each finished tile is squared and
+//     summed (its share of ||g_i||^2), added to the running sum and cleared; the sum is stored as
+//     the tile of G at the end.
+// A 256 x 256 tile would need 128 accumulators + 128 registers of the second set per lane, the
+// whole register file at two waves per SIMD.
 //   Staging: global -> LDS directly, four stages of 32 token rows x (256 + 128) columns.  A load
 //   instruction moves 1 KiB: token rows j, j+16 of delta (2 x 512 B) or rows j, j+8, j+16, j+24 of
 //   a (4 x 256 B); the 1 KiB blocks are 1088 bytes apart so that the four consecutive rows of an
@@ -62,12 +71,12 @@ constexpr int kIpFM = kIpE / (32 * kIpWM);        // 32x32 MFMA blocks per wave 
 constexpr int kIpFN = kIpC / (32 * kIpWN);        // ... along d_in
 constexpr int kIpLdE = 16 / kIpWaves, kIpLdC = 8 / kIpWaves, kIpLd = kIpLdE + kIpLdC;   // loads per wave
 constexpr int kIpStages = 4;
-constexpr int kIpLds = kIpStages * kIpStage;      // 153 KiB
+constexpr int kIpLds = kIpStages * kIpStage;      // 102 KiB
 
 struct IpTileArgs {
   const LayerDev* layers;
   const int4* tiles;      // [8][slots]: (layer, e0, c0, first sample | samples << 16); layer < 0: none
-  float* out;             // [8 * slots][group][8 waves][2]: <tile_i, G tile>, sum of squares of tile_i
+  float* out;             // [8 * slots][group][kIpWaves][2]: <tile_i, G tile>, sum of squares of tile_i
                           // (statistics form: sum of squares, unused)
   int slots, T, group;
   // statistics form only
@@ -79,7 +88,6 @@ struct IpTileArgs {
 
 // Sum over the 64 lanes without the LDS round trips of a shuffle chain: four DPP steps leave the
 // total of each row of 16 lanes in all of its lanes, the four row totals are then read as scalars.
-// (The per-sample reduction sits between two samples' MFMAs: its latency is not hidden.)
 __device__ __forceinline__ float ip_wave_sum_f32(float v) {
 #define IP_DPP(x, ctrl) \
   __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (x)), (ctrl), 0xf, 0xf, true))
@@ -101,11 +109,9 @@ template <int N> __device__ __forceinline__ void ip_wait_vmcnt() {
 __device__ __forceinline__ int ip_row_off_e(int row) { return (row & 15) * kIpBlk + (row >> 4) * 512; }
 __device__ __forceinline__ int ip_row_off_c(int row) { return (row & 7) * kIpBlk + (row >> 3) * 256; }
 
-// MODE 0: inner products (G tile read, <tile_i, G tile> written).
-// MODE 1: statistics: the per-sample tiles are squared and summed on the way to the gradient sum
-//         G = sum_i tile_i, which is written at the end (explicit form of the per-sample norms:
-//         when G has to be formed here anyway, its per-sample terms pass through the registers
-//         and the Gram contraction is not needed).
+// MODE 1 is the explicit form of the per-sample norms: when G has to be formed here anyway, its
+// per-sample terms pass through the registers and the Gram contraction is not needed.
+// SQ: also return the tile's sum of squares (always in MODE 1).
 template <int MODE, bool SQ>
 __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -121,8 +127,9 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
   const long long ck0 = (long long)(tile.w & 0xffff) * nk_sample;
   const long long nk = (long long)(tile.w >> 16) * nk_sample;
 
-  // ---- this lane's entries of the G tile.  Accumulator element j of a 32x32 block: row
-  // (j/4)*8 + (lane/32)*4 + j%4, column lane%32.  Entries past the edge are zero.
+  // ---- second register set.  Accumulator element j of a 32x32 block: row
+  // (j/4)*8 + (lane/32)*4 + j%4, column lane%32.  MODE 0: this lane's entries of the G tile
+  // (zero past the edge); MODE 1: running sum of the sample tiles.
   float gt[kIpFM][kIpFN][16];
 #pragma unroll
   for (int m = 0; m < kIpFM; ++m)
@@ -143,8 +150,9 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
     }
   const bool ragged = e0 + kIpE > L.d_out || c0 + kIpC > L.d_in;
 
-  // ---- direct loads, three per wave and chunk: delta instructions wave and wave + 8 (rows j and
-  // j + 16, 16-byte piece lane % 32), a instruction wave (rows j + 8 * (lane / 16), piece lane % 16)
+  // ---- direct loads, kIpLd per wave and chunk: delta instructions j = wave, wave + kIpWaves, ..
+  // (rows j and j + 16, 16-byte piece lane % 32), then a instructions j = wave, .. (rows
+  // j + 8 * (lane / 16), piece lane % 16).  Columns past the edge re-read the last valid piece.
   const unsigned short* src_base[kIpLd];
   long long src_stride[kIpLd];
   int lds_off[kIpLd];
