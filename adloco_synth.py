@@ -82,6 +82,16 @@ def normal_f32(seed: int, shape, std: float = 1.0) -> np.ndarray:
     return x
 
 
+def to_dtype(x: np.ndarray, dtype: str) -> np.ndarray:
+    """fp32 draws in the storage type of a workload: "f32" as is, "bf16" as uint16 bit patterns
+    (round to nearest even), "f16" as numpy float16."""
+    if dtype == "f32":
+        return x
+    if dtype == "f16":
+        return x.astype(np.float16)
+    return f32_to_bf16_bits(x)
+
+
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns (finite inputs)."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
@@ -123,7 +133,7 @@ def grad_stats_inputs(config: int, linears=None, B=None, T=None, dtype=None, rho
                 eps = normal_f32(seed, (B + 1, T, d), std)
                 x = (np.float32(rho) * eps[:1]
                      + np.float32(np.sqrt(1.0 - rho * rho)) * eps[1:])
-            tensors[key] = x if dtype == "f32" else f32_to_bf16_bits(x)
+            tensors[key] = to_dtype(x, dtype)
         out.append(dict(name=nm, d_in=di, d_out=do, a=tensors["a"], delta=tensors["delta"]))
     return out
 
@@ -142,7 +152,7 @@ def custom_grad_stats_inputs(seed: int, shapes, B: int, T: int, dtype: str,
                 eps = normal_f32(s, (B + 1, T, d), std)
                 x = (np.float32(rho) * eps[:1]
                      + np.float32(np.sqrt(1.0 - rho * rho)) * eps[1:])
-            tensors[key] = x if dtype == "f32" else f32_to_bf16_bits(x)
+            tensors[key] = to_dtype(x, dtype)
         out.append(dict(name=f"lin{li}", d_in=di, d_out=do, a=tensors["a"],
                         delta=tensors["delta"]))
     return out
@@ -172,7 +182,7 @@ def vector_table_inputs(seed: int, B: int, T: int, dtype: str, vectors=(), table
         else:
             eps = normal_f32(sd, (B + 1, T, d), std)
             v = np.float32(rho) * eps[:1] + np.float32(np.sqrt(1.0 - rho * rho)) * eps[1:]
-        return v if dtype == "f32" else f32_to_bf16_bits(v)
+        return to_dtype(v, dtype)
     out = []
     for j, (d, has_x) in enumerate(vectors):
         e = dict(kind="vector", d=d, delta=draw(seed + 10 * j + 1, d, std_delta), x=None)
@@ -219,8 +229,9 @@ def device_normal(seed: int, shape, std: float, dtype, device):
 
 
 def device_grad_stats_inputs(config: int, device, linears=None, B=None, T=None, rho=0.0,
-                             share=False):
-    """Device tensors (torch) with the recipe of grad_stats_inputs; bf16 or fp32 per config.
+                             share=False, dtype=None):
+    """Device tensors (torch) with the recipe of grad_stats_inputs; bf16 or fp32 per config,
+    or the storage type named by dtype ("f32" / "bf16" / "f16").
 
     share=True reuses one activation tensor for linears of a block that read the same
     input (q/k/v and gate/up in the Llama-shaped workload), as a real model would.
@@ -229,7 +240,7 @@ def device_grad_stats_inputs(config: int, device, linears=None, B=None, T=None, 
     c = CONFIGS[config]
     B = c["B"] if B is None else B
     T = c["T"] if T is None else T
-    tdt = torch.float32 if c["dtype"] == "f32" else torch.bfloat16
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype or c["dtype"]]
     shapes = linear_shapes(config)
     idx = list(range(len(shapes))) if linears is None else list(linears)
     out = []

@@ -23,6 +23,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+DT = None                    # element type code / torch dtype of a and delta, set from --dtype
+TDT = None
 PEAK_BF16_MFMA = 2.5e15     # dense bf16 MFMA flop/s, MI355X
 PEAK_HBM = 8.0e12           # bytes/s
 TILE = 128                  # T-tile edge of the Gram kernel (executed-flop accounting)
@@ -39,6 +41,9 @@ def parse():
     p.add_argument("--stats-variant", default="tile", choices=["tile", "gram"],
                    help="route of the statistics in the timed step: per-sample gradient tiles fused "
                         "with the gradient sum (default), or Gram kernel + gradient-sum GEMM")
+    p.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
+                   help="storage type of activations and output gradients (both run the same "
+                        "kernels; the metric is quoted on bf16)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-blocks", type=int, default=12,
                    help="transformer blocks (of 12) the CPU oracle is timed on")
@@ -120,26 +125,26 @@ def vector_table_leg(torch, synth, A, ctx, layers, B, T, dev, steps):
                            grad_sum=torch.zeros(l["d_out"], device=dev)))
         nbytes += 2 * B * T * l["d_out"]
     for j in range(25):                                # LayerNorm gains and biases
-        x = synth.device_normal(7000 + 2 * j, (B, T, d), 1.0, torch.bfloat16, dev)
-        dl = synth.device_normal(7001 + 2 * j, (B, T, d), 1e-2, torch.bfloat16, dev)
+        x = synth.device_normal(7000 + 2 * j, (B, T, d), 1.0, TDT, dev)
+        dl = synth.device_normal(7001 + 2 * j, (B, T, d), 1e-2, TDT, dev)
         blocks.append(dict(kind="vector", x=x, delta=dl, grad_sum=torch.zeros(d, device=dev)))
         blocks.append(dict(kind="vector", x=None, delta=dl, grad_sum=torch.zeros(d, device=dev)))
         nbytes += 3 * 2 * B * T * d
     ids = torch.from_numpy(synth.token_ids(7100, B, T, V)).to(dev)
     pos = torch.arange(T, dtype=torch.int32, device=dev).repeat(B, 1).contiguous()
-    de = synth.device_normal(7101, (B, T, d), 1e-2, torch.bfloat16, dev)
+    de = synth.device_normal(7101, (B, T, d), 1e-2, TDT, dev)
     blocks.append(dict(kind="embed", ids=ids, vocab=V, delta=de, grad_sum=None))
     blocks.append(dict(kind="embed", ids=pos, vocab=T, delta=de, grad_sum=None))
     nbytes += 2 * (2 * B * T * d + 4 * B * T)
-    descs = A.make_layer_descs(blocks, B, T, A.ADLOCO_BF16)
+    descs = A.make_layer_descs(blocks, B, T, DT)
     ps = torch.zeros(B, dtype=torch.float32, device=dev)
     acc = torch.zeros(2, dtype=torch.float64, device=dev)
     for _ in range(2):
-        A.adloco_grad_stats(ctx, blocks, B, T, A.ADLOCO_BF16, ps, None, acc, 0, descs=descs)
+        A.adloco_grad_stats(ctx, blocks, B, T, DT, ps, None, acc, 0, descs=descs)
     torch.cuda.synchronize()
     ctx.profile_read("vector_table")
     for _ in range(steps):
-        A.adloco_grad_stats(ctx, blocks, B, T, A.ADLOCO_BF16, ps, None, acc, 0, descs=descs)
+        A.adloco_grad_stats(ctx, blocks, B, T, DT, ps, None, acc, 0, descs=descs)
     torch.cuda.synchronize()
     ms, n = ctx.profile_read("vector_table")
     ms = ms / n if n else None
@@ -148,16 +153,16 @@ def vector_table_leg(torch, synth, A, ctx, layers, B, T, dev, steps):
     both = list(layers) + blocks
     for l in layers:
         l["provided"] = False
-    d_both = A.make_layer_descs(both, B, T, A.ADLOCO_BF16)
+    d_both = A.make_layer_descs(both, B, T, DT)
     combined = {}
     for overlap in (1, 0):
         ctx.set_tuning("overlap_aux", overlap)
         for _ in range(2):
-            A.adloco_grad_stats(ctx, both, B, T, A.ADLOCO_BF16, ps, None, acc, 0, descs=d_both)
+            A.adloco_grad_stats(ctx, both, B, T, DT, ps, None, acc, 0, descs=d_both)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            A.adloco_grad_stats(ctx, both, B, T, A.ADLOCO_BF16, ps, None, acc, 0, descs=d_both)
+            A.adloco_grad_stats(ctx, both, B, T, DT, ps, None, acc, 0, descs=d_both)
         torch.cuda.synchronize()
         combined["overlapped" if overlap else "serial"] = (time.perf_counter() - t0) / steps * 1e3
     ctx.set_tuning("overlap_aux", 1)
@@ -175,15 +180,15 @@ def inner_products_leg(torch, A, ctx, layers, B, T, dev, steps):
     the timed step left in place (Section 3.3.2's tests).  Each 256 x 256 tile of each per-sample
     gradient is one T-deep bf16 contraction: 2 * d_in * d_out * T flop per (block, sample)."""
     flops = sum(2.0 * l["d_in"] * l["d_out"] * T * B for l in layers)
-    descs = A.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
+    descs = A.make_layer_descs(layers, B, T, DT)
     c = torch.zeros(B, dtype=torch.float32, device=dev)
     acc = torch.zeros(4, dtype=torch.float64, device=dev)
     for _ in range(2):
-        A.adloco_inner_products(ctx, layers, B, T, A.ADLOCO_BF16, c, None, acc, 0, descs=descs)
+        A.adloco_inner_products(ctx, layers, B, T, DT, c, None, acc, 0, descs=descs)
     torch.cuda.synchronize()
     ctx.profile_read("inner_products")
     for _ in range(steps):
-        A.adloco_inner_products(ctx, layers, B, T, A.ADLOCO_BF16, c, None, acc, 0, descs=descs)
+        A.adloco_inner_products(ctx, layers, B, T, DT, c, None, acc, 0, descs=descs)
     torch.cuda.synchronize()
     ms, n = ctx.profile_read("inner_products")
     ms = ms / n if n else None
@@ -248,6 +253,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    global DT, TDT
+    DT, TDT = {"bf16": (A.ADLOCO_BF16, torch.bfloat16), "f16": (A.ADLOCO_F16, torch.float16)}[args.dtype]
     dev = "cuda:0"
     torch.cuda.set_device(0)
     ctx = A.Context(0)
@@ -274,7 +281,7 @@ def main():
             args.only = "stats"
     ocfg = synth.CONFIGS[5 if args.config == 5 else 3]["outer"]
     N, M = ocfg["N"], ocfg["M"]
-    workload = {2: "GPT-2-small-shaped grad stats (48 linears, B=32, T=512, bf16) + norm test + "
+    workload = {2: "GPT-2-small-shaped grad stats (48 linears, B=32, T=512, " + args.dtype + ") + norm test + "
                    "outer step and merge (M=4 x 124M fp32)",
                 4: f"Llama-1B-shaped grad stats, {len(shapes)} linears of {len(shapes) // 7} blocks "
                    f"(B=64, T=1024, bf16, q/k/v and gate/up share their input) + norm test",
@@ -282,11 +289,12 @@ def main():
                    f"T=1024, bf16) + norm test + outer step and merge (M=8 x 350M fp32)"}[args.config]
 
     # ---- inputs, resident in HBM
-    layers = synth.device_grad_stats_inputs(args.config, dev, linears=linears, share=args.config == 4)
+    layers = synth.device_grad_stats_inputs(args.config, dev, linears=linears, share=args.config == 4,
+                                            dtype=args.dtype)
     for l in layers:
         l["grad_sum"] = torch.zeros(l["d_out"], l["d_in"], dtype=torch.float32, device=dev)
         l["provided"] = bool(args.grad_provided)
-    descs = A.binding.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
+    descs = A.binding.make_layer_descs(layers, B, T, DT)
     per_sample = torch.zeros(B, dtype=torch.float32, device=dev)
     per_layer = torch.zeros(len(layers), B, dtype=torch.float32, device=dev)
     acc = torch.zeros(2, dtype=torch.float64, device=dev)
@@ -296,8 +304,8 @@ def main():
         # the caller's own weight gradient: any values do; computed once, outside the timed region
         for l in layers:
             l["provided"] = False
-        d2 = A.binding.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
-        A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, per_sample, per_layer, acc, 0,
+        d2 = A.binding.make_layer_descs(layers, B, T, DT)
+        A.adloco_grad_stats(ctx, layers, B, T, DT, per_sample, per_layer, acc, 0,
                             descs=d2)
         for l in layers:
             l["provided"] = True
@@ -308,7 +316,7 @@ def main():
 
     def step():
         if args.only in ("all", "stats"):
-            A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, per_sample, per_layer, acc, 0,
+            A.adloco_grad_stats(ctx, layers, B, T, DT, per_sample, per_layer, acc, 0,
                                 descs=descs)
             res = A.adloco_norm_test(ctx, None, acc, eta, B, 32, 2, 256, descs=descs)
             last.update(res)
@@ -368,7 +376,7 @@ def main():
         ctx.set_tuning("stats_variant", 0)
 
         def stats_gram():
-            A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, per_sample, per_layer, acc, 0,
+            A.adloco_grad_stats(ctx, layers, B, T, DT, per_sample, per_layer, acc, 0,
                                 descs=descs)
         for _ in range(2):
             stats_gram()
@@ -393,10 +401,10 @@ def main():
     if args.only in ("all", "stats") and not args.grad_provided:
         for l in layers:
             l["provided"] = True
-        d_prov = A.binding.make_layer_descs(layers, B, T, A.ADLOCO_BF16)
+        d_prov = A.binding.make_layer_descs(layers, B, T, DT)
 
         def stats_provided():
-            A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, per_sample, per_layer, acc, 0,
+            A.adloco_grad_stats(ctx, layers, B, T, DT, per_sample, per_layer, acc, 0,
                                 descs=d_prov)
             A.adloco_norm_test(ctx, None, acc, eta, B, 32, 2, 256, descs=d_prov)
         for _ in range(2):
@@ -429,14 +437,14 @@ def main():
                     traffic=traffic.get(name), avg_kernel_ms=ms, **extra)
 
     r_gram = roof("gram", "mfma", sym, kern["gram"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
-                  kernel="gram_bf16_dual_kernel", flops_algorithmic_symmetric=sym, flops_full=full,
+                  kernel="gram_bf16_dual_kernel<false>", flops_algorithmic_symmetric=sym, flops_full=full,
                   flops_executed=executed,
                   frac_executed=(executed / (kern["gram"]["avg_ms"] * 1e-3) / PEAK_BF16_MFMA)
                   if kern["gram"]["avg_ms"] else None)
     r_wgrad = roof("wgrad", "mfma", wgrad_flops, kern["wgrad"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
-                   kernel="wgrad_bf16_x_kernel", flops_algorithmic=wgrad_flops)
+                   kernel="wgrad_bf16_x_kernel<false>", flops_algorithmic=wgrad_flops)
     r_tile = roof("tile_stats", "mfma", wgrad_flops, kern["tile_stats"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s",
-                  1e12, kernel="ip_tile_kernel<1, true> (+ split-tile and per-sample reductions)",
+                  1e12, kernel="ip_tile_kernel<1, true, false> (+ split-tile and per-sample reductions)",
                   flops_algorithmic=wgrad_flops)
     r_outer = roof("outer_step", "hbm", outer_bytes, kern["outer_step"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                    kernel="outer_step_vec_kernel", bytes_algorithmic=outer_bytes)
@@ -459,7 +467,7 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": workload,
                    "blocks_held": (len(shapes) // len(cfg["block"])), "blocks_of_model": cfg["n_blocks"],
                    "B": B, "T": T, "n_linears": len(shapes), "M": M, "N": N, "eta": eta,

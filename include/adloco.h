@@ -45,6 +45,7 @@ extern "C" {
 /* ---- element types of a and delta --------------------------------------------------- */
 #define ADLOCO_F32   0
 #define ADLOCO_BF16  1
+#define ADLOCO_F16   2   /* IEEE half: the mixed-precision setting of the paper's experiments (Section 6) */
 
 /* ---- flags -------------------------------------------------------------------------- */
 #define ADLOCO_ACCUMULATE       0x1u  /* grad_stats: continue a batch (switch mode micro-batch) */
@@ -134,7 +135,7 @@ typedef struct {
  *
  *   layers   host array of n_layers descriptors (read before return), 1 <= n_layers <= 4096
  *   B, T     samples in this micro-batch and tokens per sample, >= 1 (all layers share them)
- *   dtype    ADLOCO_F32 or ADLOCO_BF16: element type of every a and delta
+ *   dtype    ADLOCO_F32, ADLOCO_BF16 or ADLOCO_F16: element type of every a and delta
  *   per_sample_sqnorm        device [B] fp32, overwritten: sum_l ||g_i^l||^2 of this micro-batch
  *   per_layer_sample_sqnorm  device [n_layers, B] fp32, overwritten; or NULL
  *   acc      device accumulator.  Without ADLOCO_ACCUMULATE it is reset first (and grad_sum
@@ -142,12 +143,12 @@ typedef struct {
  *            (ADLOCO_ESTATE is NOT detected on the device: the flag is the caller's promise
  *            that acc and grad_sum hold the earlier micro-batches of the same batch).
  *   flags    0 or ADLOCO_ACCUMULATE
- * bf16 inputs are multiplied exactly and accumulated in fp32 (MFMA); fp32 inputs in fp32.
- * bf16 rows must be 2-byte aligned; 16-byte aligned rows with d % 8 == 0 take the fast
+ * bf16 and fp16 inputs are multiplied exactly and accumulated in fp32 (MFMA); fp32 inputs in
+ * fp32.  16-bit rows must be 2-byte aligned; 16-byte aligned rows with d % 8 == 0 take the fast
  * path, anything else a slower guarded path (same results).
  * Two routes give the norms of the linear blocks.  With ADLOCO_GRAD_PROVIDED (the framework's
  * backward already holds the weight gradient) only the Gram contractions run.  When grad_sum
- * is formed here for every linear block and all of them are 16-byte aligned bf16 with
+ * is formed here for every linear block and all of them are 16-byte aligned bf16 / fp16 with
  * T % 32 == 0, the 256 x 128 tiles of the per-sample gradients delta_i^T a_i that add up to
  * grad_sum pass through the registers one sample after the other and are squared there, so the
  * Gram contractions are not needed at all; adloco_set_tuning(ctx, "stats_variant", 0) keeps the
@@ -348,7 +349,7 @@ typedef struct {
 
 typedef struct {
   int32_t T;             /* tokens per sample                                                  */
-  int32_t dtype;         /* ADLOCO_F32 / ADLOCO_BF16 of every a, delta                         */
+  int32_t dtype;         /* ADLOCO_F32 / ADLOCO_BF16 / ADLOCO_F16 of every a, delta            */
   int32_t inner_steps;   /* H >= 1                                                             */
   int32_t n_switch;      /* SwitchMode multiplier n (the paper uses 2)                         */
   int32_t merge_w;       /* w of CheckMerge; 0: no merging in this call                        */

@@ -45,11 +45,11 @@ INT64_MAX = (1 << 63) - 1
 # --------------------------------------------------------------------------------------
 
 def widen(x) -> np.ndarray:
-    """fp32 array, or uint16 array of bf16 bit patterns  ->  fp64, exactly."""
+    """fp32 / fp16 array, or uint16 array of bf16 bit patterns  ->  fp64, exactly."""
     x = np.asarray(x)
     if x.dtype == np.uint16:
         return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
-    if x.dtype in (np.float32, np.float64):
+    if x.dtype in (np.float16, np.float32, np.float64):
         return x.astype(np.float64)
     raise TypeError(f"unsupported input dtype {x.dtype}")
 

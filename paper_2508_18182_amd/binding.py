@@ -12,7 +12,7 @@ from typing import Optional, Sequence
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("ADLOCO_LIBRARY_PATH") or os.path.join(_PKG, "libadloco.so")
 
-ADLOCO_F32, ADLOCO_BF16 = 0, 1
+ADLOCO_F32, ADLOCO_BF16, ADLOCO_F16 = 0, 1, 2
 ADLOCO_ACCUMULATE = 0x1
 ADLOCO_GRAD_PROVIDED = 0x1
 ADLOCO_KIND_LINEAR, ADLOCO_KIND_VECTOR, ADLOCO_KIND_EMBED = 0x00, 0x10, 0x20
@@ -240,7 +240,7 @@ def make_layer_descs(layers: Sequence[dict], B: int, T: int, dtype: int):
     kind="embed": an embedding table, ids int32 [B,T], delta [B,T,d], vocab=V, grad_sum [V,d]
     (maintained by the caller)."""
     import torch
-    tdt = torch.bfloat16 if dtype == ADLOCO_BF16 else torch.float32
+    tdt = {ADLOCO_BF16: torch.bfloat16, ADLOCO_F16: torch.float16}.get(dtype, torch.float32)
     arr = (LinearDesc * len(layers))()
 
     def check_rows(i, nm, t):

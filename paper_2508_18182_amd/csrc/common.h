@@ -14,6 +14,22 @@
 
 namespace adloco {
 
+// 16-bit element types: bf16 and IEEE half share every data path (they are moved as 16-bit lanes);
+// only the MFMA instruction and the conversion to fp32 differ.
+inline bool is_16bit(int dtype) { return dtype == ADLOCO_BF16 || dtype == ADLOCO_F16; }
+typedef __attribute__((ext_vector_type(8))) __bf16 mfma_bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 mfma_f16x8;
+typedef __attribute__((ext_vector_type(16))) float mfma_f32x16;
+// One 32x32x16 MFMA on fragments held as bf16x8 bit patterns; F16 reinterprets them as halves.
+template <bool F16>
+__device__ __forceinline__ mfma_f32x16 mfma_32x32x16(mfma_bf16x8 a, mfma_bf16x8 b, mfma_f32x16 c) {
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(mfma_f16x8, a),
+                                                  __builtin_bit_cast(mfma_f16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
 // MI355X: 256 compute units in 8 XCDs; consecutive workgroup ids are dealt round-robin to
 // the XCDs, each of which has its own L2.
 constexpr int kNumXcd = 8;
@@ -171,6 +187,7 @@ struct GramLaunch {
   float* partials;          // [n_layers][B][n_pairs]
   int n_pairs;              // tile pairs per (layer, sample)
   int tile;                 // T-tile edge used by the kernel
+  int dtype = ADLOCO_BF16;  // element type of a and delta
 };
 // One workgroup of the dual-tile Gram kernel: up to two 128x128 tile pairs (A-block, B-block)
 // drawn from at most three distinct 128-row blocks.
@@ -191,7 +208,7 @@ int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& o
                        std::vector<int4>& split_tiles, int& n_pieces);
 hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots,
                           const void* split_tiles, int n_split, float* partials, long long rows,
-                          int accumulate, int variant, hipStream_t st);
+                          int accumulate, int dtype, hipStream_t st);
 hipError_t launch_wgrad(const LayerDev* layers, int n_layers, int n_blocks, long long rows,
                         int dtype, int accumulate, int variant, hipStream_t st);
 hipError_t launch_finalize_stats(const float* partials, int n_layers, int B, int n_pairs,
@@ -206,14 +223,14 @@ hipError_t launch_vector_stats(const LayerDev* layers, const AuxDesc* tab, int n
 int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B, int T,
                   int forced_group, std::vector<int4>& out, int& group);
 hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots, int T, int group,
-                           bool want_sq, float* ip_out, hipStream_t st);
+                           int dtype, bool want_sq, float* ip_out, hipStream_t st);
 int make_stats_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& use, int B,
                      std::vector<int4>& out, std::vector<int>& part, std::vector<int4>& split,
                      std::vector<int>& lay, std::vector<int>& ptr, std::vector<int>& idx,
                      int& n_pieces);
 hipError_t launch_stats_tiles(const LayerDev* layers, const void* tiles, const int* part, int slots,
                               const void* split, int n_split, float* partial_tiles, int B, int T,
-                              int accumulate, float* tile_out, const int* lay, const int* ptr,
+                              int dtype, int accumulate, float* tile_out, const int* lay, const int* ptr,
                               const int* idx, int n_listed, float* partials, int n_pairs,
                               hipStream_t st);
 hipError_t launch_ip_generic(const LayerDev& L, int layer, int B, int T, int dtype, double* part,

@@ -15,7 +15,7 @@ constexpr int kMaxLayers = 4096;
 // Build the device view of the layer list and upload it when it differs from the cached copy.
 int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers, int dtype,
                    bool need_inputs, hipStream_t st) {
-  const size_t esize = dtype == ADLOCO_BF16 ? 2 : 4;
+  const size_t esize = is_16bit(dtype) ? 2 : 4;
   std::vector<LayerDev> tab(n_layers);
   const int wt = wgrad_tile_edge(dtype);
   const int chunk = sqnorm_chunk();
@@ -116,13 +116,13 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   ctx->ip_B = ctx->ip_T = -1;           // and so does the inner-product tile table
   ctx->ts_B = -1;                       // and the statistics tile table
   {
-    bool ok = need_inputs && dtype == ADLOCO_BF16 && !order.empty();
+    bool ok = need_inputs && is_16bit(dtype) && !order.empty();
     for (const LayerDev& L : tab)
       if (L.kind == ADLOCO_KIND_LINEAR) ok = ok && !L.provided && L.fast;
     ctx->ts_ok = ok;
   }
   ctx->wgx_slots = 0;
-  if (fast && dtype == ADLOCO_BF16 && wg > 0) {
+  if (fast && is_16bit(dtype) && wg > 0) {
     std::vector<int4> tiles, split;
     int n_pieces = 0;
     const int slots = make_wgrad_x_tiles(tab, tiles, split, n_pieces);
@@ -223,7 +223,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   if (n_layers > kMaxLayers)
     return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: n_layers = %d exceeds %d", n_layers, kMaxLayers);
   if (B < 1 || T < 1) return fail(ctx, ADLOCO_EINVAL, "grad_stats: B = %d, T = %d must be >= 1", B, T);
-  if (dtype != ADLOCO_F32 && dtype != ADLOCO_BF16)
+  if (dtype != ADLOCO_F32 && !is_16bit(dtype))
     return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: dtype %d not supported", dtype);
   if (!per_sample_sqnorm || !acc) return fail(ctx, ADLOCO_EINVAL, "grad_stats: NULL output");
   if (reinterpret_cast<uintptr_t>(acc) % 8)
@@ -240,7 +240,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   const int tile = gram_tile_edge(dtype, ctx->gram_variant);
   const long long nt = (T + tile - 1) / tile;
   if (nt > 4096) return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: T = %d gives too many tiles", T);
-  const bool dual = dtype == ADLOCO_BF16 && ctx->gram_variant != 0 && ctx->all_fast64;
+  const bool dual = is_16bit(dtype) && ctx->gram_variant != 0 && ctx->all_fast64;
   long long n_pairs = nt * (nt + 1) / 2;      // partial sums per (layer, sample)
   if (dual) {
     if (ctx->job_tab_nt != int(nt)) {
@@ -320,6 +320,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   g.partials = static_cast<float*>(ctx->partials.ptr);
   g.n_pairs = int(n_pairs);
   g.tile = tile;
+  g.dtype = dtype;
   // ---- vector / table blocks.  With linear blocks in the same call they go to a second stream:
   // they are HBM-bound, the kernels of the linear blocks MFMA / L2-bound, and both fit on a CU.
   const bool have_aux = !ctx->vec_host.empty() || !ctx->emb_host.empty();
@@ -363,7 +364,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
     const int nl = ctx->ts_n_listed;
     e = launch_stats_tiles(g.layers, ctx->ts_tab.ptr, static_cast<const int*>(ctx->ts_part_idx.ptr),
                            ctx->ts_slots, ctx->ts_split.ptr, ctx->ts_n_split,
-                           static_cast<float*>(ctx->ts_ptiles.ptr), B, T, accumulate,
+                           static_cast<float*>(ctx->ts_ptiles.ptr), B, T, dtype, accumulate,
                            static_cast<float*>(ctx->ts_out.ptr), csr, csr + nl, csr + nl + nl + 1, nl,
                            g.partials, int(n_pairs), st);
     prof_end(ctx, kProfTileStats, ev, st);
@@ -376,7 +377,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   else if (dual)
     e = launch_gram_bf16_dual(g, static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n,
                               ctx->gram_variant, st);
-  else if (dtype == ADLOCO_BF16)
+  else if (is_16bit(dtype))
     e = launch_gram_bf16(g, ctx->gram_variant, st);
   else
     e = launch_gram_f32(g, st);
@@ -387,10 +388,10 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   const long long rows = (long long)B * T;
   if (tile_form)
     ;
-  else if (dtype == ADLOCO_BF16 && ctx->wgrad_variant >= 2 && ctx->wgx_slots > 0 && rows % 32 == 0)
+  else if (is_16bit(dtype) && ctx->wgrad_variant >= 2 && ctx->wgx_slots > 0 && rows % 32 == 0)
     e = launch_wgrad_x(g.layers, ctx->wgx_tab.ptr, ctx->wgx_slots, ctx->wgx_split.ptr,
                        ctx->wgx_n_split, static_cast<float*>(ctx->wgx_part.ptr), rows, accumulate,
-                       ctx->wgrad_variant, st);
+                       dtype, st);
   else
     e = launch_wgrad(g.layers, n_layers, ctx->wgrad_blocks, rows, dtype, accumulate,
                      ctx->wgrad_variant >= 2 ? 1 : ctx->wgrad_variant, st);
@@ -478,7 +479,7 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
     return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: n_layers = %d exceeds %d", n_layers, kMaxLayers);
   if (B < 1 || T < 1) return fail(ctx, ADLOCO_EINVAL, "inner_products: B = %d, T = %d must be >= 1", B, T);
   if (B > 0x7fff) return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: B = %d exceeds 32767", B);
-  if (dtype != ADLOCO_F32 && dtype != ADLOCO_BF16)
+  if (dtype != ADLOCO_F32 && !is_16bit(dtype))
     return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_products: dtype %d not supported", dtype);
   if (!per_sample_ip || !acc) return fail(ctx, ADLOCO_EINVAL, "inner_products: NULL output");
   if (reinterpret_cast<uintptr_t>(acc) % 8)
@@ -499,7 +500,7 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
     std::vector<char> use(n_layers, 0);
     bool any = false;
     for (int l = 0; l < n_layers; ++l) {
-      use[l] = tab[l].kind == ADLOCO_KIND_LINEAR && dtype == ADLOCO_BF16 && tab[l].fast && T % 32 == 0;
+      use[l] = tab[l].kind == ADLOCO_KIND_LINEAR && is_16bit(dtype) && tab[l].fast && T % 32 == 0;
       any = any || use[l];
     }
     std::vector<int4> tiles;
@@ -544,7 +545,7 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
   float* dot = static_cast<float*>(ctx->ip_dot.ptr);
   float* sq = static_cast<float*>(ctx->ip_sq.ptr);
   hipEvent_t ev = prof_begin(ctx, st);
-  hipError_t e = launch_ip_tiles(dl, ctx->ip_tab.ptr, ctx->ip_slots, T, ctx->ip_group,
+  hipError_t e = launch_ip_tiles(dl, ctx->ip_tab.ptr, ctx->ip_slots, T, ctx->ip_group, dtype,
                                  per_sample_sqnorm != nullptr,
                                  static_cast<float*>(ctx->ip_tile_out.ptr), st);
   for (int l = 0; l < n_layers && e == hipSuccess; ++l)

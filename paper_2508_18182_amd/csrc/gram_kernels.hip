@@ -121,6 +121,7 @@ __device__ __forceinline__ bf16x8 read_frag(const unsigned char* tile_base, int 
   return __builtin_bit_cast(bf16x8, v);
 }
 
+template <bool F16>
 __device__ __forceinline__ void mma_stage(const unsigned char* stage, int wm, int wn, int lane,
                                           f32x16 (&acc)[2][2]) {
   const unsigned char* ptile = stage;
@@ -137,10 +138,11 @@ __device__ __forceinline__ void mma_stage(const unsigned char* stage, int wm, in
     for (int m = 0; m < 2; ++m)
 #pragma unroll
       for (int n = 0; n < 2; ++n)
-        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m], fb[n], acc[m][n], 0, 0, 0);
+        acc[m][n] = mfma_32x32x16<F16>(fa[m], fb[n], acc[m][n]);
   }
 }
 
+template <bool F16>
 __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(GramArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   int layer, sample, p, q, pair;
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(GramArgs g) {
     unsigned char* nxt = lds + ((c + 1) & 1) * kStageBytes;
     const bool more = c + 1 < nk;
     if (more) load_chunk(L, T, samp_row0, p, q, c + 1, nka, regs);
-    mma_stage(cur, wm, wn, lane, acc);
+    mma_stage<F16>(cur, wm, wn, lane, acc);
     if (more) store_chunk(nxt, regs);
     __syncthreads();
   };
@@ -235,6 +237,7 @@ __device__ __forceinline__ void wg_barrier() {
   asm volatile("" ::: "memory");
 }
 
+template <bool F16>
 __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int bid = blockIdx.x;
@@ -341,7 +344,7 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
     for (int m = 0; m < 2; ++m)
 #pragma unroll
       for (int n = 0; n < 2; ++n)
-        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
+        acc[m][n] = mfma_32x32x16<F16>(a[m], b[n], acc[m][n]);
     // issue order: MFMA, LDS read, MFMA, LDS read, ...
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -477,7 +480,7 @@ __global__ __launch_bounds__(256) void gram_f32_kernel(GramArgs g) {
   }
 }
 
-int gram_tile_edge(int dtype, int /*variant*/) { return dtype == ADLOCO_BF16 ? kTile : kTileF; }
+int gram_tile_edge(int dtype, int /*variant*/) { return is_16bit(dtype) ? kTile : kTileF; }
 
 static GramArgs make_args(const GramLaunch& l) {
   GramArgs a;
@@ -495,17 +498,16 @@ static GramArgs make_args(const GramLaunch& l) {
 }
 
 hipError_t launch_gram_bf16(const GramLaunch& l, int /*variant*/, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gram_bf16_kernel),
+  auto kern = l.dtype == ADLOCO_F16 ? gram_bf16_kernel<true> : gram_bf16_kernel<false>;
+  {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kGramLds);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   GramArgs a = make_args(l);
   const long long grid = (long long)a.units_padded * a.n_pairs;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gram_bf16_kernel, dim3(unsigned(grid)), dim3(256), kGramLds, st, a);
+  hipLaunchKernelGGL(kern, dim3(unsigned(grid)), dim3(256), kGramLds, st, a);
   return hipGetLastError();
 }
 
@@ -547,7 +549,7 @@ std::vector<GramJob> make_gram_jobs(int nt) {
 
 hipError_t launch_gram_bf16_dual(const GramLaunch& l, const GramJob* jobs, int n_jobs,
                                  int variant, hipStream_t st) {
-  auto kern = gram_bf16_dual_kernel;
+  auto kern = l.dtype == ADLOCO_F16 ? gram_bf16_dual_kernel<true> : gram_bf16_dual_kernel<false>;
   (void)variant;
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

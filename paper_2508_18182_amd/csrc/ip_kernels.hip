@@ -16,6 +16,7 @@ namespace adloco {
 constexpr int kIpThreads = 256;
 
 __device__ __forceinline__ float ip_elem(unsigned short h) { return __uint_as_float(unsigned(h) << 16); }
+__device__ __forceinline__ float ip_elem(_Float16 h) { return float(h); }
 __device__ __forceinline__ float ip_elem(float f) { return f; }
 
 __device__ __forceinline__ double ip_wave_sum(double v) {
@@ -112,7 +113,7 @@ __device__ __forceinline__ int ip_row_off_c(int row) { return (row & 7) * kIpBlk
 // MODE 1 is the explicit form of the per-sample norms: when G has to be formed here anyway, its
 // per-sample terms pass through the registers and the Gram contraction is not needed.
 // SQ: also return the tile's sum of squares (always in MODE 1).
-template <int MODE, bool SQ>
+template <int MODE, bool SQ, bool F16>
 __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
     for (int m = 0; m < kIpFM; ++m)
 #pragma unroll
       for (int n = 0; n < kIpFN; ++n)
-        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
+        acc[m][n] = mfma_32x32x16<F16>(a[m], b[n], acc[m][n]);
     // the LDS reads of the next k-step go out two at a time behind the first MFMAs
 #pragma unroll
     for (int i = 0; i < kIpFM + kIpFN; ++i) {
@@ -459,9 +460,11 @@ int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& 
 }
 
 hipError_t launch_ip_tiles(const LayerDev* layers, const void* tiles, int slots, int T, int group,
-                           bool want_sq, float* ip_out, hipStream_t st) {
+                           int dtype, bool want_sq, float* ip_out, hipStream_t st) {
   if (slots <= 0) return hipSuccess;
-  auto kern = want_sq ? ip_tile_kernel<0, true> : ip_tile_kernel<0, false>;
+  const bool h = dtype == ADLOCO_F16;
+  auto kern = want_sq ? (h ? ip_tile_kernel<0, true, true> : ip_tile_kernel<0, true, false>)
+                      : (h ? ip_tile_kernel<0, false, true> : ip_tile_kernel<0, false, false>);
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kIpLds);
@@ -544,11 +547,11 @@ int make_stats_tiles(const std::vector<LayerDev>& layers, const std::vector<char
 
 hipError_t launch_stats_tiles(const LayerDev* layers, const void* tiles, const int* part, int slots,
                               const void* split, int n_split, float* partial_tiles, int B, int T,
-                              int accumulate, float* tile_out, const int* lay, const int* ptr,
+                              int dtype, int accumulate, float* tile_out, const int* lay, const int* ptr,
                               const int* idx, int n_listed, float* partials, int n_pairs,
                               hipStream_t st) {
   if (slots <= 0) return hipSuccess;
-  auto kern = ip_tile_kernel<1, true>;
+  auto kern = dtype == ADLOCO_F16 ? ip_tile_kernel<1, true, true> : ip_tile_kernel<1, true, false>;
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kIpLds);
@@ -722,6 +725,9 @@ hipError_t launch_ip_generic(const LayerDev& L, int layer, int B, int T, int dty
   if (dtype == ADLOCO_BF16)
     hipLaunchKernelGGL(ip_generic_kernel<unsigned short>, dim3(unsigned(B) * slabs), dim3(kIpThreads), 0,
                        st, L, T, slabs, part);
+  else if (dtype == ADLOCO_F16)
+    hipLaunchKernelGGL(ip_generic_kernel<_Float16>, dim3(unsigned(B) * slabs), dim3(kIpThreads), 0,
+                       st, L, T, slabs, part);
   else
     hipLaunchKernelGGL(ip_generic_kernel<float>, dim3(unsigned(B) * slabs), dim3(kIpThreads), 0, st, L, T,
                        slabs, part);
@@ -742,6 +748,9 @@ hipError_t launch_ip_vector_table(const LayerDev* layers, const AuxDesc* vec_tab
   if (n_emb > 0) {
     if (dtype == ADLOCO_BF16)
       hipLaunchKernelGGL(embed_ip_kernel<unsigned short>, dim3(unsigned(n_emb) * B), dim3(kIpThreads), 0,
+                         st, layers, emb_tab, B, T, dot);
+    else if (dtype == ADLOCO_F16)
+      hipLaunchKernelGGL(embed_ip_kernel<_Float16>, dim3(unsigned(n_emb) * B), dim3(kIpThreads), 0,
                          st, layers, emb_tab, B, T, dot);
     else
       hipLaunchKernelGGL(embed_ip_kernel<float>, dim3(unsigned(n_emb) * B), dim3(kIpThreads), 0, st,

@@ -5,6 +5,8 @@
 //   vector p [d]:  g_i = sum_t delta_{i,t} * x_{i,t}   (x = 1 for a bias)      -> ||g_i||^2
 //   table  E [V,d]: row v of g_i = sum_{t: id_t = v} delta_{i,t}               -> ||g_i||^2
 // All of it streams delta (and x) once: HBM-bound.  Sums run in a fixed order (repeatable).
+#include <type_traits>
+
 #include "common.h"
 
 namespace adloco {
@@ -15,6 +17,7 @@ constexpr int kSlab = 256;       // columns per workgroup
 constexpr int kVtThreads = 256;
 
 __device__ __forceinline__ float elem_to_f32(unsigned short h) { return __uint_as_float(unsigned(h) << 16); }
+__device__ __forceinline__ float elem_to_f32(_Float16 h) { return float(h); }
 __device__ __forceinline__ float elem_to_f32(float f) { return f; }
 
 __device__ __forceinline__ double vt_wave_sum(double v) {
@@ -45,7 +48,12 @@ __device__ __forceinline__ int find_aux(const AuxDesc* tab, int n, int b) {
 template <typename E>
 __device__ __forceinline__ void load8(const E* row, int c, int d, bool fast, float (&v)[8]) {
   if (fast && c + 8 <= d) {
-    if (sizeof(E) == 2) {
+    if constexpr (std::is_same<E, _Float16>::value) {
+      typedef __attribute__((ext_vector_type(8))) _Float16 h8;
+      const h8 r = *reinterpret_cast<const h8*>(row + c);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = float(r[j]);
+    } else if constexpr (sizeof(E) == 2) {
       const u32x4 r = *reinterpret_cast<const u32x4*>(row + c);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -285,6 +293,9 @@ hipError_t launch_vector_stats(const LayerDev* layers, const AuxDesc* tab, int n
   if (dtype == ADLOCO_BF16)
     hipLaunchKernelGGL(vector_rowsum_kernel<unsigned short>, dim3(blocks_rowsum), dim3(kVtThreads), 0,
                        st, layers, tab, n_tab, B, T, vec);
+  else if (dtype == ADLOCO_F16)
+    hipLaunchKernelGGL(vector_rowsum_kernel<_Float16>, dim3(blocks_rowsum), dim3(kVtThreads), 0,
+                       st, layers, tab, n_tab, B, T, vec);
   else
     hipLaunchKernelGGL(vector_rowsum_kernel<float>, dim3(blocks_rowsum), dim3(kVtThreads), 0, st,
                        layers, tab, n_tab, B, T, vec);
@@ -308,6 +319,9 @@ hipError_t launch_embed_stats(const LayerDev* layers, const AuxDesc* tab, int n_
                      P, perm);
   if (dtype == ADLOCO_BF16)
     hipLaunchKernelGGL(embed_rows_kernel<unsigned short>, dim3(blocks_rows), dim3(kVtThreads), 0, st,
+                       layers, tab, n_tab, B, T, perm, part);
+  else if (dtype == ADLOCO_F16)
+    hipLaunchKernelGGL(embed_rows_kernel<_Float16>, dim3(blocks_rows), dim3(kVtThreads), 0, st,
                        layers, tab, n_tab, B, T, perm, part);
   else
     hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(blocks_rows), dim3(kVtThreads), 0, st, layers,

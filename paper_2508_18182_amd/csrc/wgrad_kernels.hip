@@ -120,7 +120,7 @@ __device__ __forceinline__ bf16x8 wgrad_frag(const unsigned char* op_base, int m
   }
 }
 
-template <int VARIANT>
+template <int VARIANT, bool F16>
 __device__ __forceinline__ void wgrad_mma(const unsigned char* stage, int wm, int wn, int lane,
                                           f32x16 (&acc)[2][2]) {
   const unsigned char* dt = stage;               // delta tile: rows = tokens, cols = d_out
@@ -136,11 +136,11 @@ __device__ __forceinline__ void wgrad_mma(const unsigned char* stage, int wm, in
     for (int m = 0; m < 2; ++m)
 #pragma unroll
       for (int n = 0; n < 2; ++n)
-        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m], fb[n], acc[m][n], 0, 0, 0);
+        acc[m][n] = mfma_32x32x16<F16>(fa[m], fb[n], acc[m][n]);
   }
 }
 
-template <int VARIANT>
+template <int VARIANT, bool F16>
 __global__ __launch_bounds__(256, 2) void wgrad_bf16_kernel(WgradArgs g) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWlds];
   const int layer = find_layer_wg(g.layers, g.n_layers, blockIdx.x);
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_bf16_kernel(WgradArgs g) {
     unsigned char* nxt = lds + ((c + 1) & 1) * kWstage;
     const bool more = c + 1 < nk;
     if (more) wgrad_load(L, g.rows, (c + 1) * kWk, e0, c0, regs);
-    wgrad_mma<VARIANT>(cur, wm, wn, lane, acc);
+    wgrad_mma<VARIANT, F16>(cur, wm, wn, lane, acc);
     if (more) wgrad_store(nxt, regs);
     __syncthreads();
   }
@@ -237,6 +237,7 @@ template <int N> __device__ __forceinline__ void wgx_wait_vmcnt() {
 // 256 distinct bytes.  Global addresses stay linear: 512 contiguous bytes per half wave.
 __device__ __forceinline__ int wgx_row_off(int row) { return (row & 15) * kXblk + (row >> 4) * kXrowB; }
 
+template <bool F16>
 __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int xcd = blockIdx.x % kNumXcd, slot = blockIdx.x / kNumXcd;
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
     for (int m = 0; m < 4; ++m)
 #pragma unroll
       for (int n = 0; n < 2; ++n)
-        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
+        acc[m][n] = mfma_32x32x16<F16>(a[m], b[n], acc[m][n]);
     // issue order: the 12 LDS reads of the next k-step go out two at a time behind the first
     // six MFMAs, so that the last of them has two MFMAs to land before the next k-step starts
 #pragma unroll
@@ -455,7 +456,7 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs g) {
     }
 }
 
-int wgrad_tile_edge(int dtype) { return dtype == ADLOCO_BF16 ? kWt : kWtF; }
+int wgrad_tile_edge(int dtype) { return is_16bit(dtype) ? kWt : kWtF; }
 
 // Tile table of the fast kernel: [8 XCDs][slots] entries (layer, e0, c0, split).  The tiles of
 // all layers, in layer order, are cut into eight equal runs, one per XCD: the tiles of a layer
@@ -511,10 +512,9 @@ int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& o
 
 hipError_t launch_wgrad_x(const LayerDev* layers, const void* tiles, int slots,
                           const void* split_tiles, int n_split, float* partials, long long rows,
-                          int accumulate, int variant, hipStream_t st) {
+                          int accumulate, int dtype, hipStream_t st) {
   if (slots <= 0) return hipSuccess;
-  auto kern = wgrad_bf16_x_kernel;
-  (void)variant;
+  auto kern = dtype == ADLOCO_F16 ? wgrad_bf16_x_kernel<true> : wgrad_bf16_x_kernel<false>;
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kXlds);
@@ -532,11 +532,11 @@ hipError_t launch_wgrad(const LayerDev* layers, int n_layers, int n_blocks, long
                         int dtype, int accumulate, int variant, hipStream_t st) {
   if (n_blocks <= 0) return hipSuccess;
   WgradArgs a{layers, n_layers, rows, accumulate};
-  if (dtype == ADLOCO_BF16) {
-    if (variant == 0)
-      hipLaunchKernelGGL(wgrad_bf16_kernel<0>, dim3(n_blocks), dim3(256), 0, st, a);
-    else
-      hipLaunchKernelGGL(wgrad_bf16_kernel<1>, dim3(n_blocks), dim3(256), 0, st, a);
+  if (is_16bit(dtype)) {
+    const bool h = dtype == ADLOCO_F16;
+    auto kern = variant == 0 ? (h ? wgrad_bf16_kernel<0, true> : wgrad_bf16_kernel<0, false>)
+                             : (h ? wgrad_bf16_kernel<1, true> : wgrad_bf16_kernel<1, false>);
+    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(256), 0, st, a);
   } else {
     hipLaunchKernelGGL(wgrad_f32_kernel, dim3(n_blocks), dim3(256), 0, st, a);
   }

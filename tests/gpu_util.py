@@ -9,13 +9,20 @@ DEV = "cuda:0"
 
 
 def to_dev(x: np.ndarray):
-    """fp32 array -> fp32 tensor; uint16 bf16 bit patterns -> bf16 tensor (same bits)."""
+    """fp32 / fp16 array -> tensor of that type; uint16 bf16 bit patterns -> bf16 tensor (same bits)."""
     if x.dtype == np.uint16:
         return torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.bfloat16)
     return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
 
 
+def code_of(name: str) -> int:
+    """"f32" / "bf16" / "f16" -> the library's element type code."""
+    return {"f32": A.ADLOCO_F32, "bf16": A.ADLOCO_BF16, "f16": A.ADLOCO_F16}[name]
+
+
 def dtype_code(x: np.ndarray) -> int:
+    if x.dtype == np.float16:
+        return A.ADLOCO_F16
     return A.ADLOCO_BF16 if x.dtype == np.uint16 else A.ADLOCO_F32
 
 

@@ -16,7 +16,7 @@ from oracle import adloco_oracle as orc
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-3}
+TOL = {"f32": 1e-4, "bf16": 2e-3, "f16": 2e-3}
 
 
 @pytest.fixture(scope="module")
@@ -96,7 +96,8 @@ def _run_case(ctx, micro_batches, B, T, dtype, vartheta=0.01, nu=0.3, b_cur=None
     import torch
     import paper_2508_18182_amd as A
     from gpu_util import new_acc, read_acc, DEV
-    code = A.ADLOCO_BF16 if dtype == "bf16" else A.ADLOCO_F32
+    from gpu_util import code_of
+    code = code_of(dtype)
     tol = TOL[dtype]
     oracle_mbs = [[_oracle_entry(e) for e in mb] for mb in micro_batches]
     whole = orc.concat_micro_batches(oracle_mbs) if len(oracle_mbs) > 1 else oracle_mbs[0]
@@ -146,7 +147,7 @@ def _run_case(ctx, micro_batches, B, T, dtype, vartheta=0.01, nu=0.3, b_cur=None
     return res, ref
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("B,T,shapes", [
     (3, 5, [(3, 2), (1, 4)]),                          # tiny
     (4, 37, [(40, 24), (17, 33), (8, 8)]),             # odd widths, ragged T: plain path
@@ -164,9 +165,10 @@ def test_inner_products_small_linear(ctx, dtype, B, T, shapes):
     (4, 96, [(512, 256), (256, 776)]),                 # three chunks (pipeline tail)
     (2, 256, [(768, 768)]),                            # deeper pipeline
 ])
-def test_inner_products_tile_path_bf16(ctx, B, T, shapes):
-    entries = synth.custom_grad_stats_inputs(5100 + B + T, shapes, B, T, "bf16", std_delta=0.1, rho=0.5)
-    _run_case(ctx, [entries], B, T, "bf16")
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_inner_products_tile_path_16bit(ctx, dtype, B, T, shapes):
+    entries = synth.custom_grad_stats_inputs(5100 + B + T, shapes, B, T, dtype, std_delta=0.1, rho=0.5)
+    _run_case(ctx, [entries], B, T, dtype)
 
 
 def test_inner_products_mixed_paths_and_kinds(ctx):
@@ -179,7 +181,7 @@ def test_inner_products_mixed_paths_and_kinds(ctx):
     _run_case(ctx, [list(lin) + list(aux)], B, T, "bf16")
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_inner_products_over_micro_batches(ctx, dtype):
     # switch mode: G and S1 accumulate over three micro-batches, then the inner products of each
     B, T = 4, 64

@@ -99,6 +99,20 @@ def test_bf16_ragged_and_edges(ctx, variant, B, T, shapes):
     _check_grad_stats(ctx, layers, TOL_BF16, wgrad_variant=variant)
 
 
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("B,T,shapes", [
+    (5, 133, [(100, 52), (72, 200), (8, 8), (136, 264)]),   # ragged T tile, guarded loads
+    (4, 257, [(7, 5), (1, 1), (9, 130)]),                    # odd widths: 2-byte path
+    (4, 64, [(8, 16), (264, 520), (256, 256)]),              # 256-tile gradient kernel
+    (2, 512, [(64, 320), (320, 64)]),                        # four T tiles, many k-chunks
+])
+def test_fp16_shapes(ctx, variant, B, T, shapes):
+    # fp16 inputs (the mixed-precision setting of Section 6): same kernels, the other MFMA
+    layers = synth.custom_grad_stats_inputs(750 + B + T, shapes, B, T, "f16", std_delta=0.05,
+                                            rho=0.5)
+    _check_grad_stats(ctx, layers, TOL_BF16, wgrad_variant=variant)
+
+
 def test_bf16_strided_rows(ctx):
     # a and delta as column slices of wider buffers (fused qkv-style storage)
     import torch

@@ -24,7 +24,7 @@ def ctx(request):
 
 def _draw_case(seed):
     r = np.random.Generator(np.random.PCG64(seed))
-    dtype = "bf16" if r.random() < 0.6 else "f32"
+    dtype = str(r.choice(["bf16", "bf16", "f16", "f32"]))
     B = int(r.integers(1, 10))
     T = int(r.choice([1, 2, 7, 31, 64, 100, 128, 129, 200, 257, 300]))
     aligned = r.random() < 0.5
@@ -64,8 +64,8 @@ def test_random_case(ctx, seed):
     from gpu_util import to_dev, new_acc, read_acc, rel_err, DEV
     case = _draw_case(seed)
     B, T = case["B"], case["T"]
-    dt = A.ADLOCO_BF16 if case["dtype"] == "bf16" else A.ADLOCO_F32
-    tol = 2e-3 if case["dtype"] == "bf16" else 1e-4
+    dt = {"bf16": A.ADLOCO_BF16, "f16": A.ADLOCO_F16, "f32": A.ADLOCO_F32}[case["dtype"]]
+    tol = 1e-4 if case["dtype"] == "f32" else 2e-3
     mbs = [_host_blocks(case, seed, k) for k in range(case["micro"])]
     want = orc.grad_stats(orc.concat_micro_batches([[_oracle_entry(e) for e in mb] for mb in mbs]),
                           two_pass=False)

@@ -45,8 +45,9 @@ def _compare(got, want):
     (40, 32, [(128, 256)]),                # more samples than pieces: uneven sample runs
     (3, 160, [(136, 72), (264, 8), (16, 392)]),
 ])
-def test_tile_route_small(ctx, B, T, shapes):
-    layers = synth.custom_grad_stats_inputs(6000 + B + T, shapes, B, T, "bf16", std_delta=0.2, rho=0.4)
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_tile_route_small(ctx, dtype, B, T, shapes):
+    layers = synth.custom_grad_stats_inputs(6000 + B + T, shapes, B, T, dtype, std_delta=0.2, rho=0.4)
     want = orc.grad_stats([(l["a"], l["delta"]) for l in layers], two_pass=False)
     ctx.set_tuning("stats_variant", 1)
     got = _check(ctx, layers)

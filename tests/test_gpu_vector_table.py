@@ -9,7 +9,7 @@ from oracle import adloco_oracle as orc
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-3}
+TOL = {"f32": 1e-4, "bf16": 2e-3, "f16": 2e-3}
 
 
 # Every test runs twice: with the per-sample norms taken from the per-sample gradient tiles on
@@ -37,7 +37,7 @@ def _run(ctx, entries, B, T, dtype, flags=0, acc=None, grad_sums=None, table_gra
     """entries: host dicts (linear dicts from synth.custom_grad_stats_inputs carry no 'kind')."""
     import torch
     import paper_2508_18182_amd as A
-    from gpu_util import to_dev, new_acc, read_acc, DEV
+    from gpu_util import to_dev, new_acc, read_acc, code_of, DEV
     layers = []
     for i, e in enumerate(entries):
         kind = e.get("kind", "linear")
@@ -55,7 +55,7 @@ def _run(ctx, entries, B, T, dtype, flags=0, acc=None, grad_sums=None, table_gra
     ps = torch.full((B,), float("nan"), dtype=torch.float32, device=DEV)
     pl = torch.full((len(layers), B), float("nan"), dtype=torch.float32, device=DEV)
     acc = new_acc() if acc is None else acc
-    A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16 if dtype == "bf16" else A.ADLOCO_F32, ps, pl,
+    A.adloco_grad_stats(ctx, layers, B, T, code_of(dtype), ps, pl,
                         acc, flags)
     torch.cuda.synchronize()
     S1, n = read_acc(acc)
@@ -82,7 +82,7 @@ def _check(ctx, entries, B, T, dtype):
     return got, want
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("B,T,vectors,tables", [
     (3, 37, [(40, True), (40, False), (7, True), (1, False)], [(11, 24), (50, 5)]),   # odd widths
     (2, 1, [(8, True)], [(4, 8)]),                                                     # one token

@@ -281,6 +281,21 @@ def test_bf16_widening_is_exact():
     np.testing.assert_array_equal(orc.widen(bits), t.to(torch.float64).numpy())
 
 
+def test_fp16_widening_is_exact():
+    # fp16 storage (the mixed-precision setting of Section 6): values decoded from their bit fields
+    # (sign, 5-bit exponent with bias 15, 10-bit fraction; subnormals scale by 2^-24)
+    x = synth.to_dtype(synth.normal_f32(12, (2000,), 1e-2), "f16")
+    x[:4] = np.array([6e-8, -3e-5, 65504.0, -0.0], dtype=np.float16)
+    u = x.view(np.uint16).astype(np.int64)
+    sign = np.where(u >> 15, -1.0, 1.0)
+    e, f = (u >> 10) & 31, u & 1023
+    want = sign * np.where(e == 0, f * 2.0 ** -24, (1024 + f) * 2.0 ** (e - 25.0))
+    np.testing.assert_array_equal(orc.widen(x), want)
+    import torch
+    np.testing.assert_array_equal(synth.to_dtype(synth.normal_f32(13, (500,), 1.0), "f16"),
+                                  torch.from_numpy(synth.normal_f32(13, (500,), 1.0)).to(torch.float16).numpy())
+
+
 # ------------------------------------------------------------------ S2, variance, identity
 
 def test_identical_samples():
