@@ -35,6 +35,24 @@ __device__ __forceinline__ mfma_f32x16 mfma_32x32x16(mfma_bf16x8 a, mfma_bf16x8 
 constexpr int kNumXcd = 8;
 constexpr int kNumCu = 256;
 
+// Order of the ne x nc output tiles of one layer for the tile tables of the MFMA kernels: blocks of
+// about 32 tiles (one round of an XCD's workgroups, which share that XCD's L2) whose shape streams
+// the fewest distinct rows of a and delta -- as many tile columns as tile rows for square tiles,
+// `aspect` times as many when a tile is `aspect` times as high as wide.  f(e, c) is called once per
+// tile, e = tile row (d_out side), c = tile column (d_in side).
+template <typename F>
+inline void for_tiles_blocked(int ne, int nc, int aspect, F f) {
+  const int per_round = kNumCu / kNumXcd;
+  int nc_blk = 1;
+  while (nc_blk * nc_blk < per_round * aspect) ++nc_blk;            // ~ sqrt(32 * aspect)
+  nc_blk = nc_blk < nc ? nc_blk : nc;
+  const int ne_blk = per_round / nc_blk > 1 ? per_round / nc_blk : 1;
+  for (int eb = 0; eb < ne; eb += ne_blk)
+    for (int cb = 0; cb < nc; cb += nc_blk)
+      for (int e = eb; e < eb + ne_blk && e < ne; ++e)
+        for (int c = cb; c < cb + nc_blk && c < nc; ++c) f(e, c);
+}
+
 // Device-side view of one linear layer (built on the host, uploaded once per change).
 struct LayerDev {
   const void* a;

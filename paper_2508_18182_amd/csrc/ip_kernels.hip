@@ -448,8 +448,9 @@ int make_ip_tiles(const std::vector<LayerDev>& layers, const std::vector<char>& 
       if (load[x] < load[bx]) bx = x;
     load[bx] += S.n * S.cnt;
     const LayerDev& L = layers[S.layer];
-    for (int e0 = 0; e0 < L.d_out; e0 += kIpE)
-      for (int c0 = 0; c0 < L.d_in; c0 += kIpC) per[bx].push_back(int4{S.layer, e0, c0, S.s0 | (S.cnt << 16)});
+    for_tiles_blocked((L.d_out + kIpE - 1) / kIpE, (L.d_in + kIpC - 1) / kIpC, kIpE / kIpC, [&](int e, int c) {
+      per[bx].push_back(int4{S.layer, e * kIpE, c * kIpC, S.s0 | (S.cnt << 16)});
+    });
   }
   size_t slots = 0;
   for (auto& v : per) slots = std::max(slots, v.size());
@@ -484,13 +485,14 @@ int make_stats_tiles(const std::vector<LayerDev>& layers, const std::vector<char
                      std::vector<int>& lay, std::vector<int>& ptr, std::vector<int>& idx,
                      int& n_pieces) {
   constexpr int kCuPerXcd = kNumCu / kNumXcd;
-  // all tiles in layer order (within a layer: rows of tiles), cut into eight equal runs: a layer
-  // stays on one XCD unless it straddles a cut, and the XCDs get the same number of tiles
+  // all tiles in layer order (within a layer: blocks of tiles that share rows), cut into eight
+  // equal runs: a layer stays on one XCD unless it straddles a cut, and the XCDs get the same
+  // number of tiles
   std::vector<int4> all;
   for (size_t l = 0; l < layers.size(); ++l) {
     if (!use[l]) continue;
-    for (int e0 = 0; e0 < layers[l].d_out; e0 += kIpE)
-      for (int c0 = 0; c0 < layers[l].d_in; c0 += kIpC) all.push_back(int4{int(l), e0, c0, B << 16});
+    for_tiles_blocked((layers[l].d_out + kIpE - 1) / kIpE, (layers[l].d_in + kIpC - 1) / kIpC, kIpE / kIpC,
+                      [&](int e, int c) { all.push_back(int4{int(l), e * kIpE, c * kIpC, B << 16}); });
   }
   std::vector<std::vector<int4>> per(kNumXcd);
   for (int x = 0; x < kNumXcd; ++x)

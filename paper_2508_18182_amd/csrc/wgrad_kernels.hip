@@ -468,13 +468,14 @@ int wgrad_tile_edge(int dtype) { return is_16bit(dtype) ? kWt : kWtF; }
 int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out,
                        std::vector<int4>& split_tiles, int& n_pieces) {
   constexpr int kCuPerXcd = kNumCu / kNumXcd;
-  // all tiles in layer order (within a layer: rows of tiles), cut into eight equal runs: a layer
-  // stays on one XCD unless it straddles a cut, and the XCDs get the same number of tiles
+  // all tiles in layer order (within a layer: blocks of tiles that share rows), cut into eight
+  // equal runs: a layer stays on one XCD unless it straddles a cut, and the XCDs get the same
+  // number of tiles
   std::vector<int4> all;
   for (size_t l = 0; l < layers.size(); ++l) {
     if (layers[l].provided || layers[l].kind != ADLOCO_KIND_LINEAR) continue;
-    for (int e0 = 0; e0 < layers[l].d_out; e0 += kXt)
-      for (int c0 = 0; c0 < layers[l].d_in; c0 += kXt) all.push_back(int4{int(l), e0, c0, 0});
+    for_tiles_blocked((layers[l].d_out + kXt - 1) / kXt, (layers[l].d_in + kXt - 1) / kXt, 1,
+                      [&](int e, int c) { all.push_back(int4{int(l), e * kXt, c * kXt, 0}); });
   }
   std::vector<std::vector<int4>> per(kNumXcd);
   for (int x = 0; x < kNumXcd; ++x)
