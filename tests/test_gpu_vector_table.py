@@ -39,6 +39,15 @@ def _run(ctx, entries, B, T, dtype, flags=0, acc=None, grad_sums=None, table_gra
     import paper_2508_18182_amd as A
     from gpu_util import to_dev, new_acc, read_acc, code_of, DEV
     layers = []
+    on_dev = {}
+
+    def to_dev(x, _up=to_dev):
+        # one device tensor per host array: a bias that names its linear layer's delta passes the
+        # same pointer, as a framework would
+        if id(x) not in on_dev:
+            on_dev[id(x)] = _up(x)
+        return on_dev[id(x)]
+
     for i, e in enumerate(entries):
         kind = e.get("kind", "linear")
         if kind == "linear":
@@ -153,6 +162,49 @@ def test_vector_accumulation_over_micro_batches(ctx):
         w = want["G"][l]
         g = gs[l].cpu().numpy().astype(np.float64)
         assert float(np.max(np.abs(g - w))) / (float(np.sqrt(np.mean(w * w))) + 1e-300) < 1e-4
+
+
+def _with_biases(lin, extra=()):
+    """linear entries followed by one bias per linear layer on the same delta array."""
+    return list(lin) + [dict(kind="vector", d=l["d_out"], x=None, delta=l["delta"]) for l in lin] + list(extra)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,T,shapes", [
+    (5, 64, [(72, 264), (128, 256), (320, 520), (8, 8)]),     # ragged tile rows, several tile columns
+    (40, 32, [(128, 256)]),                                   # one tile split along the samples
+    (3, 96, [(264, 72), (16, 392)]),
+])
+def test_biases_on_their_linear_layers_delta(ctx, dtype, B, T, shapes):
+    # every linear layer with a bias on the same delta tensor (one pointer, as a framework passes it)
+    lin = synth.custom_grad_stats_inputs(3500 + B + T, shapes, B, T, dtype, std_delta=0.2, rho=0.4)
+    own = synth.vector_table_inputs(3550 + B, B, T, dtype, [(shapes[0][1], False), (64, True)], [],
+                                    std_delta=0.2, rho=0.4)    # a bias with a delta of its own, a gain
+    _check(ctx, _with_biases(lin, own), B, T, dtype)
+
+
+def test_biases_with_whole_and_split_tile_entries_accumulate(ctx):
+    # 288 tiles: whole entries and entries split along the samples; two micro-batches accumulate
+    import torch
+    import paper_2508_18182_amd as A
+    from gpu_util import DEV, new_acc, rel_err
+    B, T = 3, 32
+    shapes = [(2048, 2048), (2048, 2048), (2048, 264)]
+    mbs = [_with_biases(synth.custom_grad_stats_inputs(3600 + 50 * k, shapes, B, T, "bf16", std_delta=0.05,
+                                                       rho=0.3)) for k in range(2)]
+    gs = [torch.zeros(do, di, device=DEV) for di, do in shapes] + [torch.zeros(do, device=DEV) for _, do in shapes]
+    acc = new_acc()
+    first = _run(ctx, mbs[0], B, T, "bf16", acc=acc, grad_sums=gs)
+    got = _run(ctx, mbs[1], B, T, "bf16", flags=A.ADLOCO_ACCUMULATE, acc=acc, grad_sums=gs)
+    want = orc.grad_stats(orc.concat_micro_batches([[_oracle_entry(e) for e in mb] for mb in mbs]),
+                          two_pass=False)
+    assert got["n_samples"] == 2 * B
+    per_layer = np.concatenate([first["per_layer"], got["per_layer"]], axis=1)
+    assert rel_err(per_layer, want["n_layer_sample"]) < 2e-3
+    assert rel_err(got["S1"], want["S1"]) < 2e-3
+    for l, w in enumerate(want["G"]):
+        g = gs[l].cpu().numpy().astype(np.float64)
+        assert float(np.max(np.abs(g - w))) / (float(np.sqrt(np.mean(w * w))) + 1e-300) < 1e-4, l
 
 
 def test_strided_bias_of_fused_projection(ctx):
