@@ -266,7 +266,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
 
   // Per-sample gradient tiles (explicit form) when every linear block qualifies: the tiles that
   // add up to the gradient sum are squared on the way, no Gram contraction is needed.
-  const bool tile_form = ctx->stats_variant != 0 && ctx->ts_ok && T % 32 == 0 && B <= 0x7fff;
+  const bool tile_form = ctx->stats_variant != 0 && ctx->ts_ok && T % 32 == 0 && T <= (1 << 20) && B <= 0x7fff;
   if (tile_form && ctx->ts_B != B) {
     const std::vector<LayerDev>& tab = ctx->layer_tab_host;
     std::vector<char> use(n_layers, 0);
@@ -500,7 +500,8 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
     std::vector<char> use(n_layers, 0);
     bool any = false;
     for (int l = 0; l < n_layers; ++l) {
-      use[l] = tab[l].kind == ADLOCO_KIND_LINEAR && is_16bit(dtype) && tab[l].fast && T % 32 == 0;
+      use[l] = tab[l].kind == ADLOCO_KIND_LINEAR && is_16bit(dtype) && tab[l].fast && T % 32 == 0 &&
+               T <= (1 << 20);       // the tile kernel counts an entry's chunks of 32 rows in 32 bits
       any = any || use[l];
     }
     std::vector<int4> tiles;

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
   const int wm = wave / kIpWN, wn = wave % kIpWN;  // kIpWM x kIpWN waves
   const int nk_sample = g.T / kIpK;               // chunks per sample
   const long long ck0 = (long long)(tile.w & 0xffff) * nk_sample;
-  const long long nk = (long long)(tile.w >> 16) * nk_sample;
+  const int nk = (tile.w >> 16) * nk_sample;       // chunks of this entry: the host keeps it below 2^31
 
   // ---- second register set.  Accumulator element j of a 32x32 block: row
   // (j/4)*8 + (lane/32)*4 + j%4, column lane%32.  MODE 0: this lane's entries of the G tile
@@ -173,11 +173,11 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
   }
   const unsigned lds_base = lds_address(lds);       // LDS byte addresses are handled as integers
   // stage indices are carried along (no modulo in the loop: kIpStages need not be a power of two)
-  auto issue_loads = [&](long long c, int st) {
+  auto issue_loads = [&](int c, int st) {
     const unsigned stage = lds_base + unsigned(st) * kIpStage;
 #pragma unroll
     for (int i = 0; i < kIpLd; ++i)
-      direct_load_lds16(src_base[i] + c * kIpK * src_stride[i], stage + lds_off[i]);
+      direct_load_lds16(src_base[i] + (long long)c * kIpK * src_stride[i], stage + lds_off[i]);
   };
 
   // ---- fragments by LDS transpose reads.  Within a group of 16 lanes, lane s points at the 4
@@ -187,26 +187,31 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
   const int i16 = lane & 15;
   const int krow = (lane >> 5) * 8 + (i16 >> 2);              // + ks*16 (+4 for the upper half)
   const int ccol = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;    // column within a 32-wide block
+  // Every read address of a k-step is stage + (a part that depends on the lane) + (a constant of the
+  // fragment): three lane parts -- delta side; a side, rows r and r + 4, which wrap differently in
+  // its 8-row blocks -- are kept in registers, the constants ride in the offset field of the read.
   typedef __attribute__((address_space(3))) ip_s16x4* lds_ptr;
-  auto frag = [&](unsigned p0, unsigned p1) -> ip_bf16x8 {
-    ip_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(size_t)p0);
-    ip_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(size_t)p1);
+  const unsigned lane_e = unsigned(ip_row_off_e(krow) + (wm * (32 * kIpFM) + ccol) * 2);
+  const unsigned lane_c0 = unsigned(kIpOpE + ip_row_off_c(krow) + (wn * (32 * kIpFN) + ccol) * 2);
+  const unsigned lane_c1 = unsigned(kIpOpE + ip_row_off_c(krow + 4) + (wn * (32 * kIpFN) + ccol) * 2);
+  auto frag = [&](lds_ptr p0, lds_ptr p1) -> ip_bf16x8 {
+    ip_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p0);
+    ip_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p1);
     ip_s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(ip_bf16x8, v);
   };
+  // token rows ks*16 + krow (+4) of the stage: row blocks of 16 (delta) and 8 (a) rows make ks * 512
+  // bytes on both sides; 32 columns are 64 bytes; offsets in units of the 8-byte read
   auto read_frags = [&](int st, int ks, ip_bf16x8 (&fa)[kIpFM], ip_bf16x8 (&fb)[kIpFN]) {
     const unsigned stage = lds_base + unsigned(st) * kIpStage;
-    const int r0 = ks * 16 + krow, r1 = r0 + 4;
+    const lds_ptr be = (lds_ptr)(size_t)(stage + lane_e);
+    const lds_ptr bc0 = (lds_ptr)(size_t)(stage + lane_c0), bc1 = (lds_ptr)(size_t)(stage + lane_c1);
 #pragma unroll
-    for (int m = 0; m < kIpFM; ++m) {
-      const int col = wm * (32 * kIpFM) + m * 32 + ccol;
-      fa[m] = frag(stage + ip_row_off_e(r0) + col * 2, stage + ip_row_off_e(r1) + col * 2);
-    }
+    for (int m = 0; m < kIpFM; ++m)
+      fa[m] = frag(be + (ks * 512 + m * 64) / 8, be + (ks * 512 + m * 64 + 4 * kIpBlk) / 8);
 #pragma unroll
-    for (int n = 0; n < kIpFN; ++n) {
-      const int col = wn * (32 * kIpFN) + n * 32 + ccol;
-      fb[n] = frag(stage + kIpOpE + ip_row_off_c(r0) + col * 2, stage + kIpOpE + ip_row_off_c(r1) + col * 2);
-    }
+    for (int n = 0; n < kIpFN; ++n)
+      fb[n] = frag(bc0 + (ks * 512 + n * 64) / 8, bc1 + (ks * 512 + n * 64) / 8);
   };
 
   ip_f32x16 acc[kIpFM][kIpFN];
@@ -257,7 +262,7 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
   ip_bf16x8 fa[2][kIpFM], fb[2][kIpFN];
   read_frags(0, 0, fa[0], fb[0]);
   int st_cur = 0, st_load = kIpStages - 1;        // stage of chunk c; stage that chunk c-1 frees
-  for (long long c = 0; c < nk; ++c) {
+  for (int c = 0; c < nk; ++c) {
     const int st_next = st_cur + 1 == kIpStages ? 0 : st_cur + 1;
     read_frags(st_cur, 1, fa[1], fb[1]);
     mfma4(fa[0], fb[0]);
