@@ -90,6 +90,13 @@ __device__ __forceinline__ void direct_load_lds16(const void* src, unsigned lds_
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :: "v"(src), "s"(lds_addr) : "m0");
 }
+// The same with the address split into a wave-uniform 64-bit base (scalar registers) and a 32-bit
+// byte offset per lane: a kernel that walks along its rows bumps the base on the scalar unit and
+// keeps the lane offsets constant, so that no vector instruction is spent on addresses.
+__device__ __forceinline__ void direct_load_lds16_s(unsigned lane_off, const void* base, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(lane_off), "s"(base), "s"(lds_addr) : "m0");
+}
 // LDS byte address of a pointer into the workgroup's dynamic shared memory, as a scalar.
 __device__ __forceinline__ unsigned lds_address(const void* p) {
   return __builtin_amdgcn_readfirstlane(
@@ -154,6 +161,7 @@ struct adloco_ctx {
   int overlap_aux = 1;
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
+  long long max_lin_stride = 0;  // widest row stride (elements) among the linear blocks of the table
   double* pinned = nullptr;    // 8 doubles of pinned host memory (read-back of the tests' sums)
   double* dev_scalars = nullptr;  // 4 doubles on the device (S2, ...)
   // optional per-kernel event timing ("profile" knob)

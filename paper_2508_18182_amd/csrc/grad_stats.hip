@@ -107,6 +107,10 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   for (const LayerDev& L : tab)
     if (L.kind == ADLOCO_KIND_LINEAR) f64 = f64 && L.fast && L.d_in % 64 == 0 && L.d_out % 64 == 0;
   ctx->all_fast64 = f64;
+  long long widest = 0;
+  for (const LayerDev& L : tab)
+    if (L.kind == ADLOCO_KIND_LINEAR) widest = std::max(widest, std::max(L.a_stride, L.delta_stride));
+  ctx->max_lin_stride = widest;
   bool fast = need_inputs;
   for (const LayerDev& L : tab)
     if (L.kind == ADLOCO_KIND_LINEAR) fast = fast && (L.provided || L.fast);
@@ -240,7 +244,9 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   const int tile = gram_tile_edge(dtype, ctx->gram_variant);
   const long long nt = (T + tile - 1) / tile;
   if (nt > 4096) return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: T = %d gives too many tiles", T);
-  const bool dual = is_16bit(dtype) && ctx->gram_variant != 0 && ctx->all_fast64;
+  // (the dual-tile kernel addresses a sample's rows with 32-bit byte offsets)
+  const bool dual = is_16bit(dtype) && ctx->gram_variant != 0 && ctx->all_fast64 &&
+                    (long long)T * ctx->max_lin_stride < (1LL << 31) - 64;
   long long n_pairs = nt * (nt + 1) / 2;      // partial sums per (layer, sample)
   if (dual) {
     if (ctx->job_tab_nt != int(nt)) {
@@ -388,7 +394,8 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   const long long rows = (long long)B * T;
   if (tile_form)
     ;
-  else if (is_16bit(dtype) && ctx->wgrad_variant >= 2 && ctx->wgx_slots > 0 && rows % 32 == 0)
+  else if (is_16bit(dtype) && ctx->wgrad_variant >= 2 && ctx->wgx_slots > 0 && rows % 32 == 0 &&
+           rows / 32 <= 0x7fffffffLL)
     e = launch_wgrad_x(g.layers, ctx->wgx_tab.ptr, ctx->wgx_slots, ctx->wgx_split.ptr,
                        ctx->wgx_n_split, static_cast<float*>(ctx->wgx_part.ptr), rows, accumulate,
                        dtype, st);

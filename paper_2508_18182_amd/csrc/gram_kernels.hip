@@ -267,55 +267,76 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   // are masked in the epilogue).
   const int ld_row = wave * 8 + (lane >> 3);         // row within the block for i = 0; +64 for i = 1
   const int ld_col = swz(ld_row, lane & 7) * 8;      // element offset within the 64-wide chunk
-  long long row_off[3][2];
+  // Address = (sample's first row + chunk's first column: wave-uniform, scalar registers) + (row
+  // within the sample, position within the chunk: a 32-bit byte offset per lane, computed once for
+  // each operand; the host keeps T * row stride below 2^31 elements).
+  int t_row[3][2];
 #pragma unroll
   for (int s = 0; s < 3; ++s)
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      int t = J.blk[s < nblk ? s : 0] * kTile + ld_row + 64 * i;
-      t = t < T ? t : T - 1;
-      row_off[s][i] = (long long)sample * T + t;
+      const int t = J.blk[s < nblk ? s : 0] * kTile + ld_row + 64 * i;
+      t_row[s][i] = t < T ? t : T - 1;
     }
+  unsigned off_pa[3][2], off_pd[3][2];
+#pragma unroll
+  for (int s = 0; s < 3; ++s)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      off_pa[s][i] = unsigned((long long)t_row[s][i] * L.a_stride + ld_col) * 2u;
+      off_pd[s][i] = unsigned((long long)t_row[s][i] * L.delta_stride + ld_col) * 2u;
+    }
+  const unsigned short* const samp_a =
+      reinterpret_cast<const unsigned short*>(L.a) + (long long)sample * T * L.a_stride;
+  const unsigned short* const samp_d =
+      reinterpret_cast<const unsigned short*>(L.delta) + (long long)sample * T * L.delta_stride;
+  const unsigned lds_base = lds_address(lds);
   // stage indices are carried along (no division in the loop): chunk c lives in stage c mod 3
   auto issue_loads = [&](int c, int st) {
-    const bool is_a = c < nka;
-    const unsigned short* base = reinterpret_cast<const unsigned short*>(is_a ? L.a : L.delta);
-    const long long stride = is_a ? L.a_stride : L.delta_stride;
-    const int k0 = (is_a ? c : c - nka) * kKc + ld_col;
-    unsigned char* stage = lds + st * kDualStage;
+    const unsigned stage = lds_base + unsigned(st) * kDualStage;
+    if (c < nka) {
+      const unsigned short* base = samp_a + c * kKc;
 #pragma unroll
-    for (int s = 0; s < 3; ++s) {
-      if (s < nblk) {
+      for (int s = 0; s < 3; ++s)
+        if (s < nblk) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const unsigned short* src = base + row_off[s][i] * stride + k0;
-          direct_load_lds16(src, lds_address(stage + (s * kTile + (wave + 8 * i) * 8) * ROWB));
+          for (int i = 0; i < 2; ++i)
+            direct_load_lds16_s(off_pa[s][i], base, stage + (s * kTile + (wave + 8 * i) * 8) * ROWB);
         }
-      }
+    } else {
+      const unsigned short* base = samp_d + (c - nka) * kKc;
+#pragma unroll
+      for (int s = 0; s < 3; ++s)
+        if (s < nblk) {
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            direct_load_lds16_s(off_pd[s][i], base, stage + (s * kTile + (wave + 8 * i) * 8) * ROWB);
+        }
     }
   };
 
   // ---- fragment addressing
   const int r32 = lane & 31, kg = lane >> 5;
-  int off_a[2], off_b[2], sw_a[2], sw_b[2];
+  // byte offset within a stage of this lane's 16 bytes for every (k-step, fragment): computed once,
+  // so that a k-step spends one vector add per fragment on addresses
+  unsigned pre_a[4][2], pre_b[4][2];
 #pragma unroll
   for (int m = 0; m < 2; ++m) {
     const int ra = slot_a * kTile + wm * 64 + m * 32 + r32;
     const int rb = slot_b * kTile + wn * 64 + m * 32 + r32;
-    off_a[m] = ra * ROWB;
-    off_b[m] = rb * ROWB;
-    sw_a[m] = swz(ra, 0);
-    sw_b[m] = swz(rb, 0);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      pre_a[ks][m] = unsigned(ra * ROWB + ((ks * 2 + kg) ^ swz(ra, 0)) * 16);
+      pre_b[ks][m] = unsigned(rb * ROWB + ((ks * 2 + kg) ^ swz(rb, 0)) * 16);
+    }
   }
+  typedef __attribute__((address_space(3))) const u32x4* lds_v4;
   auto read_frags = [&](int st, int ks, bf16x8 (&fa)[2], bf16x8 (&fb)[2]) {
-    const unsigned char* stage = lds + st * kDualStage;
-    const int chunk = ks * 2 + kg;
+    const unsigned stage = lds_base + unsigned(st) * kDualStage;
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
-      fa[m] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
-                                             stage + off_a[m] + ((chunk ^ sw_a[m]) * 16)));
-      fb[m] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
-                                             stage + off_b[m] + ((chunk ^ sw_b[m]) * 16)));
+      fa[m] = __builtin_bit_cast(bf16x8, *(lds_v4)(size_t)(stage + pre_a[ks][m]));
+      fb[m] = __builtin_bit_cast(bf16x8, *(lds_v4)(size_t)(stage + pre_b[ks][m]));
     }
   };
 

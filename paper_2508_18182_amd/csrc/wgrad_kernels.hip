@@ -250,9 +250,10 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 2, wn = wave & 3;        // 2 x 4 waves; wave tile 128 (e) x 64 (c)
   // chunk range of this workgroup: everything, or piece split_p of split_s equal parts
+  // (32-bit counters keep the loop's compares on the scalar unit; the host keeps rows / 32 < 2^31)
   const long long nk_all = g.rows / kXk;
   const long long ck0 = split_s ? nk_all * split_p / split_s : 0;
-  const long long nk = (split_s ? nk_all * (split_p + 1) / split_s : nk_all) - ck0;
+  const int nk = int((split_s ? nk_all * (split_p + 1) / split_s : nk_all) - ck0);
 
   // ---- direct loads: instruction j = wave + 8*i (i = 0..3): operand j/16, rows j%16 (lanes 0-31)
   // and j%16 + 16 (lanes 32-63), 16-byte piece lane%32
@@ -273,11 +274,12 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
     src_base[i] = base + (ck0 * kXk + row) * src_stride[i] + col;
     lds_off[i] = op * kXop + (j & 15) * kXblk;
   }
-  auto issue_loads = [&](long long c) {
-    unsigned char* stage = lds + (c % kXstages) * kXstage;
+  const unsigned lds_base = lds_address(lds);       // LDS byte addresses are handled as integers
+  auto issue_loads = [&](int c, int st) {
+    const unsigned stage = lds_base + unsigned(st) * kXstage;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      direct_load_lds16(src_base[i] + c * kXk * src_stride[i], lds_address(stage + lds_off[i]));
+      direct_load_lds16(src_base[i] + (long long)c * kXk * src_stride[i], stage + lds_off[i]);
   };
 
   // ---- fragments by LDS transpose reads.  Within a group of 16 lanes, lane s points at the 4
@@ -287,25 +289,27 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
   const int i16 = lane & 15;
   const int krow = (lane >> 5) * 8 + (i16 >> 2);              // + ks*16 (+4 for the upper half)
   const int ccol = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;    // column within a 32-wide block
+  // Every read address of a k-step is stage + (a part that depends on the lane) + (a constant of
+  // the fragment): one lane part per operand is kept in a register, the constants ride in the
+  // offset field of the read.  Token rows ks*16 + krow and + 4 stay inside one 16-row block.
   typedef __attribute__((address_space(3))) s16x4* lds_ptr;
-  auto frag = [&](const unsigned char* op_base, int m0, int ks) -> bf16x8 {
-    const int col = m0 + ccol;
-    const int r0 = ks * 16 + krow, r1 = r0 + 4;
-    const unsigned char* p0 = op_base + wgx_row_off(r0) + col * 2;
-    const unsigned char* p1 = op_base + wgx_row_off(r1) + col * 2;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p1));
+  const unsigned lane_e = unsigned(wgx_row_off(krow) + (wm * 128 + ccol) * 2);
+  const unsigned lane_c = unsigned(kXop + wgx_row_off(krow) + (wn * 64 + ccol) * 2);
+  auto frag = [&](lds_ptr base, int byte_off) -> bf16x8 {
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(base + byte_off / 8);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(base + (byte_off + 4 * kXblk) / 8);
     s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, v);
   };
-  auto read_frags = [&](long long c, int ks, bf16x8 (&fa)[4], bf16x8 (&fb)[2]) {
-    const unsigned char* stage = lds + (c % kXstages) * kXstage;
-    // in the order the MFMAs need them
-    fa[0] = frag(stage, wm * 128, ks);
-    fb[0] = frag(stage + kXop, wn * 64, ks);
-    fb[1] = frag(stage + kXop, wn * 64 + 32, ks);
+  auto read_frags = [&](int st, int ks, bf16x8 (&fa)[4], bf16x8 (&fb)[2]) {
+    const unsigned stage = lds_base + unsigned(st) * kXstage;
+    const lds_ptr be = (lds_ptr)(size_t)(stage + lane_e), bc = (lds_ptr)(size_t)(stage + lane_c);
+    // in the order the MFMAs need them; 32 columns are 64 bytes
+    fa[0] = frag(be, ks * kXrowB);
+    fb[0] = frag(bc, ks * kXrowB);
+    fb[1] = frag(bc, ks * kXrowB + 64);
 #pragma unroll
-    for (int m = 1; m < 4; ++m) fa[m] = frag(stage, wm * 128 + m * 32, ks);
+    for (int m = 1; m < 4; ++m) fa[m] = frag(be, ks * kXrowB + m * 64);
   };
 
   f32x16 acc[4][2];
@@ -332,17 +336,20 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
   };
 
-  if (nk > 0) issue_loads(0);
-  if (nk > 1) issue_loads(1);
-  if (nk > 2) issue_loads(2);
+  if (nk > 0) issue_loads(0, 0);
+  if (nk > 1) issue_loads(1, 1);
+  if (nk > 2) issue_loads(2, 2);
   if (nk > 2) wgx_wait_vmcnt<8>(); else if (nk > 1) wgx_wait_vmcnt<4>(); else wgx_wait_vmcnt<0>();
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   bf16x8 fa[2][4], fb[2][2];
   read_frags(0, 0, fa[0], fb[0]);
-  for (long long c = 0; c < nk; ++c) {
-    read_frags(c, 1, fa[1], fb[1]);
+  static_assert(kXstages == 4, "the stage of chunk c+3 is the stage of chunk c-1");
+  int st_cur = 0, st_load = kXstages - 1;         // stage of chunk c; stage that chunk c-1 frees
+  for (int c = 0; c < nk; ++c) {
+    const int st_next = st_cur + 1 == kXstages ? 0 : st_cur + 1;
+    read_frags(st_cur, 1, fa[1], fb[1]);
     mfma8(fa[0], fb[0]);
     if (c + 1 < nk) {
       // chunk c+1 has landed for me (chunk c+2 may still be in flight), then for everybody;
@@ -351,10 +358,12 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (c + 3 < nk) issue_loads(c + 3);
+      if (c + 3 < nk) issue_loads(c + 3, st_load);
     }
-    read_frags(c + 1 < nk ? c + 1 : c, 0, fa[0], fb[0]);
+    read_frags(c + 1 < nk ? st_next : st_cur, 0, fa[0], fb[0]);
     mfma8(fa[1], fb[1]);
+    st_load = st_cur;
+    st_cur = st_next;
   }
 
   // accumulator element j of a 32x32 block: row (j/4)*8 + (lane/32)*4 + j%4, column lane%32
