@@ -120,13 +120,14 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   ctx->ip_B = ctx->ip_T = -1;           // and so does the inner-product tile table
   ctx->ts_B = -1;                       // and the statistics tile table
   {
-    bool ok = need_inputs && is_16bit(dtype) && !order.empty();
+    // (the tile kernels address the rows of a chunk with 32-bit byte offsets)
+    bool ok = need_inputs && is_16bit(dtype) && !order.empty() && widest < (1 << 25);
     for (const LayerDev& L : tab)
       if (L.kind == ADLOCO_KIND_LINEAR) ok = ok && !L.provided && L.fast;
     ctx->ts_ok = ok;
   }
   ctx->wgx_slots = 0;
-  if (fast && is_16bit(dtype) && wg > 0) {
+  if (fast && is_16bit(dtype) && wg > 0 && widest < (1 << 25)) {
     std::vector<int4> tiles, split;
     int n_pieces = 0;
     const int slots = make_wgrad_x_tiles(tab, tiles, split, n_pieces);
@@ -507,8 +508,10 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
     std::vector<char> use(n_layers, 0);
     bool any = false;
     for (int l = 0; l < n_layers; ++l) {
+      // the tile kernel counts an entry's chunks of 32 rows in 32 bits and addresses the rows of a
+      // chunk with 32-bit byte offsets
       use[l] = tab[l].kind == ADLOCO_KIND_LINEAR && is_16bit(dtype) && tab[l].fast && T % 32 == 0 &&
-               T <= (1 << 20);       // the tile kernel counts an entry's chunks of 32 rows in 32 bits
+               T <= (1 << 20) && tab[l].a_stride < (1 << 25) && tab[l].delta_stride < (1 << 25);
       any = any || use[l];
     }
     std::vector<int4> tiles;

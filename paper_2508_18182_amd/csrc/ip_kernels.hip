@@ -154,8 +154,9 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
   // ---- direct loads, kIpLd per wave and chunk: delta instructions j = wave, wave + kIpWaves, ..
   // (rows j and j + 16, 16-byte piece lane % 32), then a instructions j = wave, .. (rows
   // j + 8 * (lane / 16), piece lane % 16).  Columns past the edge re-read the last valid piece.
-  const unsigned short* src_base[kIpLd];
-  long long src_stride[kIpLd];
+  // Address = (first row of the chunk: wave-uniform, scalar registers) + (row within the chunk and
+  // column: a 32-bit byte offset per lane, computed once; the host keeps row strides below 2^25).
+  unsigned lane_off[kIpLd];
   int lds_off[kIpLd];
 #pragma unroll
   for (int i = 0; i < kIpLd; ++i) {
@@ -166,18 +167,20 @@ __global__ __launch_bounds__(64 * kIpWaves, 1) void ip_tile_kernel(IpTileArgs g)
     const int d = is_a ? L.d_in : L.d_out;
     int col = (is_a ? c0 : e0) + piece * 8;
     col = col < d ? col : d - 8;
-    const unsigned short* base = reinterpret_cast<const unsigned short*>(is_a ? L.a : L.delta);
-    src_stride[i] = is_a ? L.a_stride : L.delta_stride;
-    src_base[i] = base + (ck0 * kIpK + row) * src_stride[i] + col;
+    lane_off[i] = unsigned(row * (is_a ? L.a_stride : L.delta_stride) + col) * 2u;
     lds_off[i] = (is_a ? kIpOpE : 0) + j * kIpBlk;
   }
+  const unsigned short* const run_e = reinterpret_cast<const unsigned short*>(L.delta) + ck0 * kIpK * L.delta_stride;
+  const unsigned short* const run_c = reinterpret_cast<const unsigned short*>(L.a) + ck0 * kIpK * L.a_stride;
   const unsigned lds_base = lds_address(lds);       // LDS byte addresses are handled as integers
   // stage indices are carried along (no modulo in the loop: kIpStages need not be a power of two)
   auto issue_loads = [&](int c, int st) {
     const unsigned stage = lds_base + unsigned(st) * kIpStage;
+    const unsigned short* const pe = run_e + (long long)c * kIpK * L.delta_stride;
+    const unsigned short* const pc = run_c + (long long)c * kIpK * L.a_stride;
 #pragma unroll
     for (int i = 0; i < kIpLd; ++i)
-      direct_load_lds16(src_base[i] + (long long)c * kIpK * src_stride[i], stage + lds_off[i]);
+      direct_load_lds16_s(lane_off[i], i >= kIpLdE ? pc : pe, stage + lds_off[i]);
   };
 
   // ---- fragments by LDS transpose reads.  Within a group of 16 lanes, lane s points at the 4

@@ -257,29 +257,33 @@ __global__ __launch_bounds__(512, 1) void wgrad_bf16_x_kernel(WgradXArgs g) {
 
   // ---- direct loads: instruction j = wave + 8*i (i = 0..3): operand j/16, rows j%16 (lanes 0-31)
   // and j%16 + 16 (lanes 32-63), 16-byte piece lane%32
-  const unsigned short* src_base[4];
-  long long src_stride[4];
+  // Address = (first row of the chunk: wave-uniform, scalar registers) + (row within the chunk and
+  // column: a 32-bit byte offset per lane, computed once; the host keeps row strides below 2^25).
+  // j = wave + 8*i < 16 for i = 0, 1 (delta) and >= 16 for i = 2, 3 (a).
+  unsigned lane_off[4];
   int lds_off[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int j = wave + 8 * i;
-    const int op = j >> 4;                        // 0: delta (d_out side), 1: a (d_in side)
+    const int op = i >> 1;                        // 0: delta (d_out side), 1: a (d_in side)
     const int row = (j & 15) + 16 * (lane >> 5);
     const int piece = lane & 31;
     const int d = op ? L.d_in : L.d_out;
     int col = (op ? c0 : e0) + piece * 8;
     col = col < d ? col : d - 8;
-    const unsigned short* base = reinterpret_cast<const unsigned short*>(op ? L.a : L.delta);
-    src_stride[i] = op ? L.a_stride : L.delta_stride;
-    src_base[i] = base + (ck0 * kXk + row) * src_stride[i] + col;
+    lane_off[i] = unsigned(row * (op ? L.a_stride : L.delta_stride) + col) * 2u;
     lds_off[i] = op * kXop + (j & 15) * kXblk;
   }
+  const unsigned short* const run_e = reinterpret_cast<const unsigned short*>(L.delta) + ck0 * kXk * L.delta_stride;
+  const unsigned short* const run_c = reinterpret_cast<const unsigned short*>(L.a) + ck0 * kXk * L.a_stride;
   const unsigned lds_base = lds_address(lds);       // LDS byte addresses are handled as integers
   auto issue_loads = [&](int c, int st) {
     const unsigned stage = lds_base + unsigned(st) * kXstage;
+    const unsigned short* const pe = run_e + (long long)c * kXk * L.delta_stride;
+    const unsigned short* const pc = run_c + (long long)c * kXk * L.a_stride;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      direct_load_lds16(src_base[i] + (long long)c * kXk * src_stride[i], stage + lds_off[i]);
+      direct_load_lds16_s(lane_off[i], i >= 2 ? pc : pe, stage + lds_off[i]);
   };
 
   // ---- fragments by LDS transpose reads.  Within a group of 16 lanes, lane s points at the 4
