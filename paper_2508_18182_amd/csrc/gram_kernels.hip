@@ -208,7 +208,9 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(GramArgs g) {
 //   distinct 128-row blocks have to be staged: less L2 and LDS-write traffic per MFMA than one
 //   tile pair per workgroup, with the same executed flops.
 //   Staging: global -> LDS directly (16 bytes per lane, no registers in between), three stages
-//   of (3 blocks x 128 rows x 64 bf16).  One workgroup barrier per k-chunk, placed in the middle
+//   of (3 blocks x 128 rows x 64 bf16), or four stages of 36 KiB for a job that has only two
+//   distinct blocks (most jobs of a short sequence: 4 of the 5 at T = 512), which then has one
+//   more chunk in flight.  One workgroup barrier per k-chunk, placed in the middle
 //   of the chunk: by then every wave's loads of the next chunk have landed and every wave has
 //   finished with the previous chunk's stage, so the chunk after next is requested right there
 //   and the fragment reads never drain across a chunk boundary.
@@ -291,9 +293,13 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   const unsigned short* const samp_d =
       reinterpret_cast<const unsigned short*>(L.delta) + (long long)sample * T * L.delta_stride;
   const unsigned lds_base = lds_address(lds);
-  // stage indices are carried along (no division in the loop): chunk c lives in stage c mod 3
+  // A job with three row blocks runs three stages of 48 KiB, one with at most two blocks four stages
+  // of 36 KiB (32 used): one more chunk in flight out of the same 144 KiB.
+  const int n_st = nblk == 3 ? 3 : 4;
+  const unsigned st_bytes = nblk == 3 ? unsigned(kDualStage) : unsigned(kDualLds / 4);
+  // stage indices are carried along (no division in the loop): chunk c lives in stage c mod n_st
   auto issue_loads = [&](int c, int st) {
-    const unsigned stage = lds_base + unsigned(st) * kDualStage;
+    const unsigned stage = lds_base + unsigned(st) * st_bytes;
     if (c < nka) {
       const unsigned short* base = samp_a + c * kKc;
 #pragma unroll
@@ -332,7 +338,7 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   }
   typedef __attribute__((address_space(3))) const u32x4* lds_v4;
   auto read_frags = [&](int st, int ks, bf16x8 (&fa)[2], bf16x8 (&fb)[2]) {
-    const unsigned stage = lds_base + unsigned(st) * kDualStage;
+    const unsigned stage = lds_base + unsigned(st) * st_bytes;
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
       fa[m] = __builtin_bit_cast(bf16x8, *(lds_v4)(size_t)(stage + pre_a[ks][m]));
@@ -348,13 +354,17 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
 #pragma unroll
       for (int j = 0; j < 16; ++j) { acc_a[m][n][j] = 0.f; acc_d[m][n][j] = 0.f; }
 
-  // ---- prologue: chunks 0 and 1 in flight, chunk 0 landed for everybody
+  // ---- prologue: chunks 0 .. n_st-2 in flight, chunk 0 landed for everybody (a wave issues
+  // 2 * nblk loads per chunk)
   issue_loads(0, 0);
-  if (nk > 1) {
-    issue_loads(1, 1);
-    if (nblk == 3) wait_vmcnt<6>(); else if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
+  if (nk > 1) issue_loads(1, 1);
+  if (n_st == 4 && nk > 2) issue_loads(2, 2);
+  if (nblk == 3) {
+    if (nk > 1) wait_vmcnt<6>(); else wait_vmcnt<0>();
+  } else if (nblk == 2) {
+    if (nk > 2) wait_vmcnt<8>(); else if (nk > 1) wait_vmcnt<4>(); else wait_vmcnt<0>();
   } else {
-    wait_vmcnt<0>();
+    if (nk > 2) wait_vmcnt<4>(); else if (nk > 1) wait_vmcnt<2>(); else wait_vmcnt<0>();
   }
   wg_barrier();
   bf16x8 fa[2][2], fb[2][2];
@@ -373,17 +383,23 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
   };
-  int st_cur = 0, st_prev = kDualStages - 1;     // stages of chunk c and of chunk c-1
+  int st_cur = 0, st_prev = n_st - 1;            // stages of chunk c and of chunk c-1
+  const int ahead = n_st - 1;                    // the chunk requested at chunk c's barrier is c + ahead
   auto chunk_step = [&](int c, f32x16 (&acc)[2][2]) {
-    const int st_next = st_cur + 1 == kDualStages ? 0 : st_cur + 1;
+    const int st_next = st_cur + 1 == n_st ? 0 : st_cur + 1;
     // k-step 0
     read_frags(st_cur, 1, fa[1], fb[1]);
     mfma4(fa[0], fb[0], acc);
     // k-step 1, with the barrier of this chunk in front of it
     if (c + 1 < nk) {
-      wait_vmcnt<0>();        // my share of chunk c+1 (the only loads in flight) has landed
+      // my share of chunk c+1 has landed (with four stages chunk c+2 may still be in flight) ...
+      if (n_st == 4 && c + 2 < nk) {
+        if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
+      } else {
+        wait_vmcnt<0>();
+      }
       wg_barrier();           // ... and so has everybody's; the stage of chunk c-1 is free
-      if (c + 2 < nk) issue_loads(c + 2, st_prev);
+      if (c + ahead < nk) issue_loads(c + ahead, st_prev);
     }
     read_frags(st_cur, 2, fa[0], fb[0]);
     mfma4(fa[1], fb[1], acc);
