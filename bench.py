@@ -69,14 +69,16 @@ def gram_flops(shapes, B, T):
     """(symmetric-half algorithmic, full, executed by the tile-pair kernel) flops per launch."""
     dsum = sum(di + do for _, di, do in shapes)
     nt = -(-T // TILE)
-    pairs = nt * (nt + 1) // 2
+    # 128 x 128 tile pairs: nt(nt-1)/2 off the diagonal, nt on it, where one of the four 64 x 64
+    # wave tiles mirrors another and is not computed
+    pairs = nt * (nt - 1) / 2 + 0.75 * nt
     sym = B * T * (T + 1) * dsum
     full = 2 * B * T * T * dsum
     executed = 0
     for _, di, do in shapes:
         kp = -(-di // 64) * 64 + -(-do // 64) * 64      # k-chunks of 64 are zero padded
         executed += B * pairs * 2 * TILE * TILE * kp
-    return sym, full, executed
+    return sym, full, int(executed)
 
 
 def cpu_baseline(synth, orc, shapes, B, T, N, M, blocks):

@@ -215,6 +215,7 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(GramArgs g) {
 //   finished with the previous chunk's stage, so the chunk after next is requested right there
 //   and the fragment reads never drain across a chunk boundary.
 //   Fragments for the next k-step are read from LDS while the MFMAs of the current one run.
+//   A tile pair on the diagonal is symmetric: three of its four 64x64 wave tiles are computed.
 // ---------------------------------------------------------------------------------------
 constexpr int kDualStageRows = 3 * kTile;
 constexpr int kDualStage = kDualStageRows * kKc * 2;          // 48 KiB
@@ -413,12 +414,33 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
     st_prev = st_cur;
     st_cur = st_next;
   };
-  int c = 0;
-  for (; c < nka; ++c) chunk_step(c, acc_a);
-  for (; c < nk; ++c) chunk_step(c, acc_d);
+  // A tile pair on the diagonal (both sides the same row block) is symmetric: its wave tile (1, 0)
+  // mirrors (0, 1), which counts twice instead.  The mirror wave only takes part in the loads and
+  // barriers.
+  const bool diag = slot_a == slot_b;
+  const bool mirror = diag && wm == 1 && wn == 0;
+  if (mirror) {
+    for (int c = 0; c < nk; ++c) {
+      if (c + 1 < nk) {
+        if (n_st == 4 && c + 2 < nk) {
+          if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
+        } else {
+          wait_vmcnt<0>();
+        }
+        wg_barrier();
+        if (c + ahead < nk) issue_loads(c + ahead, st_prev);
+      }
+      st_prev = st_cur;
+      st_cur = st_cur + 1 == n_st ? 0 : st_cur + 1;
+    }
+  } else {
+    int c = 0;
+    for (; c < nka; ++c) chunk_step(c, acc_a);
+    for (; c < nk; ++c) chunk_step(c, acc_d);
+  }
 
   // ---- epilogue: < A A^T , D D^T > over this wave's 64x64 part, masked beyond T
-  const float w = grp ? J.w[1] : J.w[0];
+  const float w = (grp ? J.w[1] : J.w[0]) * ((diag && wm == 0 && wn == 1) ? 2.f : 1.f);
   float s = 0.f;
   const int blk_a = J.blk[slot_a], blk_b = J.blk[slot_b];
   if ((blk_a + 1) * kTile <= T && (blk_b + 1) * kTile <= T) {
