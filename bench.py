@@ -70,8 +70,9 @@ def gram_flops(shapes, B, T):
     dsum = sum(di + do for _, di, do in shapes)
     nt = -(-T // TILE)
     # 128 x 128 tile pairs: nt(nt-1)/2 off the diagonal, nt on it, where one of the four 64 x 64
-    # wave tiles mirrors another and is not computed
-    pairs = nt * (nt - 1) / 2 + 0.75 * nt
+    # wave tiles mirrors another and is not computed and the two on the diagonal leave out one of
+    # their four 32 x 32 blocks: (0.75 + 0.75 + 1 + 0) / 4 of a pair
+    pairs = nt * (nt - 1) / 2 + 0.625 * nt
     sym = B * T * (T + 1) * dsum
     full = 2 * B * T * T * dsum
     executed = 0

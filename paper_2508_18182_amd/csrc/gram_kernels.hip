@@ -10,6 +10,7 @@
 // tile of D D^T over d_out in two sets of MFMA accumulators that share one register layout,
 // multiplies them element-wise in registers and reduces to one float.
 #include "common.h"
+#include <type_traits>
 
 namespace adloco {
 
@@ -215,7 +216,8 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(GramArgs g) {
 //   finished with the previous chunk's stage, so the chunk after next is requested right there
 //   and the fragment reads never drain across a chunk boundary.
 //   Fragments for the next k-step are read from LDS while the MFMAs of the current one run.
-//   A tile pair on the diagonal is symmetric: three of its four 64x64 wave tiles are computed.
+//   A tile pair on the diagonal is symmetric: three of its four 64x64 wave tiles are computed,
+//   and the two of them that lie on the diagonal three of their four 32x32 blocks.
 // ---------------------------------------------------------------------------------------
 constexpr int kDualStageRows = 3 * kTile;
 constexpr int kDualStage = kDualStageRows * kKc * 2;          // 48 KiB
@@ -371,12 +373,15 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   bf16x8 fa[2][2], fb[2][2];
   read_frags(0, 0, fa[0], fb[0]);
 
-  auto mfma4 = [&](const bf16x8 (&a)[2], const bf16x8 (&b)[2], f32x16 (&acc)[2][2]) {
+  // SYM: this wave's 64x64 tile lies on the diagonal of the Gram matrix, its 32x32 block (1, 0)
+  // mirrors (0, 1) and is left out
+  auto mfma4 = [&](auto sym, const bf16x8 (&a)[2], const bf16x8 (&b)[2], f32x16 (&acc)[2][2]) {
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
       for (int n = 0; n < 2; ++n)
-        acc[m][n] = mfma_32x32x16<F16>(a[m], b[n], acc[m][n]);
+        if (!(decltype(sym)::value && m == 1 && n == 0))
+          acc[m][n] = mfma_32x32x16<F16>(a[m], b[n], acc[m][n]);
     // issue order: MFMA, LDS read, MFMA, LDS read, ...
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -386,11 +391,11 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   };
   int st_cur = 0, st_prev = n_st - 1;            // stages of chunk c and of chunk c-1
   const int ahead = n_st - 1;                    // the chunk requested at chunk c's barrier is c + ahead
-  auto chunk_step = [&](int c, f32x16 (&acc)[2][2]) {
+  auto chunk_step = [&](auto sym, int c, f32x16 (&acc)[2][2]) {
     const int st_next = st_cur + 1 == n_st ? 0 : st_cur + 1;
     // k-step 0
     read_frags(st_cur, 1, fa[1], fb[1]);
-    mfma4(fa[0], fb[0], acc);
+    mfma4(sym, fa[0], fb[0], acc);
     // k-step 1, with the barrier of this chunk in front of it
     if (c + 1 < nk) {
       // my share of chunk c+1 has landed (with four stages chunk c+2 may still be in flight) ...
@@ -403,14 +408,14 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
       if (c + ahead < nk) issue_loads(c + ahead, st_prev);
     }
     read_frags(st_cur, 2, fa[0], fb[0]);
-    mfma4(fa[1], fb[1], acc);
+    mfma4(sym, fa[1], fb[1], acc);
     // k-step 2
     read_frags(st_cur, 3, fa[1], fb[1]);
-    mfma4(fa[0], fb[0], acc);
+    mfma4(sym, fa[0], fb[0], acc);
     // k-step 3: fragments of the next chunk's first k-step (after the last chunk: a harmless
     // re-read of this chunk, so that the reads stay interleaved with the MFMAs)
     read_frags(c + 1 < nk ? st_next : st_cur, 0, fa[0], fb[0]);
-    mfma4(fa[1], fb[1], acc);
+    mfma4(sym, fa[1], fb[1], acc);
     st_prev = st_cur;
     st_cur = st_next;
   };
@@ -433,34 +438,45 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
       st_prev = st_cur;
       st_cur = st_cur + 1 == n_st ? 0 : st_cur + 1;
     }
+  } else if (diag && wm == wn) {
+    int c = 0;
+    for (; c < nka; ++c) chunk_step(std::true_type{}, c, acc_a);
+    for (; c < nk; ++c) chunk_step(std::true_type{}, c, acc_d);
   } else {
     int c = 0;
-    for (; c < nka; ++c) chunk_step(c, acc_a);
-    for (; c < nk; ++c) chunk_step(c, acc_d);
+    for (; c < nka; ++c) chunk_step(std::false_type{}, c, acc_a);
+    for (; c < nk; ++c) chunk_step(std::false_type{}, c, acc_d);
   }
 
   // ---- epilogue: < A A^T , D D^T > over this wave's 64x64 part, masked beyond T
   const float w = (grp ? J.w[1] : J.w[0]) * ((diag && wm == 0 && wn == 1) ? 2.f : 1.f);
   float s = 0.f;
   const int blk_a = J.blk[slot_a], blk_b = J.blk[slot_b];
+  // in a wave tile on the diagonal block (0, 1) stands for (1, 0) as well (whose accumulators stayed 0)
+  const float w01 = (diag && wm == wn) ? 2.f : 1.f;
   if ((blk_a + 1) * kTile <= T && (blk_b + 1) * kTile <= T) {
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
-      for (int n = 0; n < 2; ++n)
+      for (int n = 0; n < 2; ++n) {
+        float sb = 0.f;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) s += acc_a[m][n][j] * acc_d[m][n][j];
+        for (int j = 0; j < 16; ++j) sb += acc_a[m][n][j] * acc_d[m][n][j];
+        s += (m == 0 && n == 1) ? sb * w01 : sb;
+      }
   } else {
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
       for (int n = 0; n < 2; ++n) {
         const int col = blk_b * kTile + wn * 64 + n * 32 + r32;
+        float sb = 0.f;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
           const int row = blk_a * kTile + wm * 64 + m * 32 + (j >> 2) * 8 + kg * 4 + (j & 3);
-          if (row < T && col < T) s += acc_a[m][n][j] * acc_d[m][n][j];
+          if (row < T && col < T) sb += acc_a[m][n][j] * acc_d[m][n][j];
         }
+        s += (m == 0 && n == 1) ? sb * w01 : sb;
       }
   }
   s = wave_sum_f32(s) * w;
