@@ -113,6 +113,23 @@ def test_fp16_shapes(ctx, variant, B, T, shapes):
     _check_grad_stats(ctx, layers, TOL_BF16, wgrad_variant=variant)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("T", [1, 64, 127, 128, 129, 255, 256, 257, 384, 500, 640])
+def test_gram_symmetry_shortcuts_at_ragged_T(dtype, T):
+    # the dual-tile Gram kernel (widths multiples of 64) leaves out the mirrored parts of the tile
+    # pairs on the diagonal: every position of the sequence end relative to the 128-row blocks,
+    # the 64-row wave tiles and the 32-row MFMA blocks
+    import paper_2508_18182_amd as A
+    c = A.Context(0)
+    try:
+        c.set_tuning("stats_variant", 0)
+        layers = synth.custom_grad_stats_inputs(770 + T, [(64, 128), (192, 64)], 3, T, dtype, std_delta=0.05,
+                                                rho=0.5)
+        _check_grad_stats(c, layers, TOL_BF16)
+    finally:
+        c.close()
+
+
 def test_bf16_strided_rows(ctx):
     # a and delta as column slices of wider buffers (fused qkv-style storage)
     import torch
