@@ -76,6 +76,21 @@ def test_tile_route_whole_and_split_entries(ctx):
     _compare(got, want)
 
 
+def test_tile_route_extreme_aspect_ratios(ctx):
+    # one tile row of 32 tile columns, one tile column of 16 tile rows, and a 5 x 9 grid: the blocks in
+    # which the tiles of a layer are ordered are cut off by the layer's edge in every way
+    B, T = 2, 32
+    shapes = [(4096, 8), (8, 4096), (1160, 1288)]
+    layers = synth.custom_grad_stats_inputs(6300, shapes, B, T, "bf16", std_delta=0.05, rho=0.3)
+    want = orc.grad_stats([(l["a"], l["delta"]) for l in layers], two_pass=False)
+    ctx.set_tuning("stats_variant", 1)
+    got = _check(ctx, layers)
+    _compare(got, want)
+    ctx.set_tuning("stats_variant", 0)       # the gradient-sum GEMM orders its 256 x 256 tiles the same way
+    _compare(_check(ctx, layers), want)
+    ctx.set_tuning("stats_variant", 1)
+
+
 def test_tile_route_accumulates_over_micro_batches(ctx):
     # switch mode: S1, n and the gradient sums continue over three micro-batches; whole and split
     # entries both add to what is there
