@@ -287,3 +287,50 @@ def device_outer_inputs(config: int, device, N=None, M=None):
     else:
         mom = torch.zeros((N,), dtype=torch.float32, device=device)
     return theta, insts, mom
+
+
+# --------------------------------------------------------------------------------------
+# One outer step of Algorithm 3 on tiny blocks: the stand-in for the model (sampling and
+# backward pass are outside the hot path) and the trainers' initial state.
+# --------------------------------------------------------------------------------------
+
+def round_batch_fn(shapes, T, vec=False):
+    """batch_fn(uid, worker, inner_step, micro_step, b, theta) -> blocks for b samples: one (a, delta)
+    pair per (d_in, d_out) in `shapes` (fp32; a component shared by the samples of a call keeps the
+    batch gradient away from zero), plus the bias vector of the last linear layer when `vec`.
+    Every (uid, worker, inner_step, micro_step, block) has its own seed, so that a driver which
+    asks for the wrong batch gets different numbers."""
+    def fn(uid, worker, h, s, b, theta):
+        out = []
+        for l, (di, do) in enumerate(shapes):
+            r = np.random.Generator(np.random.PCG64(100000 * uid + 1000 * worker + 100 * h + 10 * s + l))
+            shared = r.standard_normal((1, T, di + do))
+            x = 0.6 * shared + 0.8 * r.standard_normal((b, T, di + do))
+            out.append((x[:, :, :di].astype(np.float32), (0.1 * x[:, :, di:]).astype(np.float32)))
+        if vec:
+            out.append(("rowsum", None, out[-1][1]))
+        return out
+    return fn
+
+
+def round_trainers(k, M, N, b_reqs, seed=77, stale_workers=False):
+    """k trainers with M workers each over N flat fp32 parameters.  With `stale_workers` the
+    workers start from parameters, AdamW moments and step counts of their own, as they would after
+    earlier outer steps: only then does a driver that forgets the worker reset show."""
+    r = np.random.Generator(np.random.PCG64(seed))
+    ts = []
+    for i in range(k):
+        th = (0.02 * r.standard_normal(N)).astype(np.float32)
+        mom = (1e-3 * r.standard_normal(N)).astype(np.float32) if stale_workers else np.zeros(N, np.float32)
+        ws = []
+        for _ in range(M):
+            if stale_workers:
+                ws.append(dict(theta=(0.02 * r.standard_normal(N)).astype(np.float32),
+                               exp_avg=(1e-3 * r.standard_normal(N)).astype(np.float32),
+                               exp_avg_sq=(1e-6 * r.standard_normal(N) ** 2).astype(np.float32),
+                               step=int(r.integers(1, 5))))
+            else:
+                ws.append(dict(theta=th.copy(), exp_avg=np.zeros(N, np.float32),
+                               exp_avg_sq=np.zeros(N, np.float32), step=0))
+        ts.append(dict(uid=i, theta_outer=th, momentum=mom, b_req=b_reqs[i], workers=ws))
+    return ts

@@ -17,9 +17,20 @@
  *     them.  They must stay alive until the work enqueued on `stream` has completed.
  *     "host" pointers are ordinary host memory, read before the call returns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All device work
- *     is enqueued on it.  Only adloco_norm_test waits for the stream (it returns scalars to
- *     the host); every other call returns as soon as its kernels are enqueued.
- *   - A context owns only scratch memory (partial sums, descriptor tables, two pinned
+ *     is enqueued on it.  When a call waits for the stream:
+ *       * adloco_norm_test and adloco_inner_product_test always do (they return scalars to
+ *         the host);
+ *       * adloco_grad_stats, adloco_inner_products and adloco_norm_test do on the FIRST call
+ *         with a new list of shapes -- number of blocks, their kinds and flags, d_in, d_out, row
+ *         strides, 16-byte alignment class of a / delta, dtype, and for the statistics B and T:
+ *         that call builds the tile and job tables, which allocates scratch memory, copies
+ *         tables from the host and waits for the copies.  It must not be captured into a graph.
+ *       * Every later call with the same shapes returns as soon as its kernels are enqueued,
+ *         whatever the addresses in a, delta and grad_sum are: the pointers of a call travel in
+ *         kernel arguments, nothing is allocated, copied from the host or waited for, and such
+ *         a call can be captured (its pointers are part of the captured launches).
+ *       * Every other call returns as soon as its kernels are enqueued.
+ *   - A context owns only scratch memory (partial sums, descriptor tables, a few pinned
  *     doubles).  One context must not be used from two host threads at once, nor on two
  *     streams whose work may overlap.
  *   - Buffers must not alias unless the argument is documented "in/out".
@@ -49,6 +60,7 @@ extern "C" {
 
 /* ---- flags -------------------------------------------------------------------------- */
 #define ADLOCO_ACCUMULATE       0x1u  /* grad_stats: continue a batch (switch mode micro-batch) */
+#define ADLOCO_SUM_ONLY         0x2u  /* grad_stats: form the gradient sums only, no norms       */
 #define ADLOCO_GRAD_PROVIDED    0x1u  /* linear_desc.flags: caller maintains grad_sum itself     */
 /* linear_desc.flags, bits 4..7: which block of the parameters the descriptor stands for      */
 #define ADLOCO_KIND_LINEAR      0x00u /* weight W [d_out, d_in] of a linear layer (the default)  */
@@ -69,18 +81,6 @@ typedef struct adloco_ctx adloco_ctx;
 int adloco_create(adloco_ctx** out, int device);
 int adloco_destroy(adloco_ctx* ctx);
 const char* adloco_last_error(const adloco_ctx* ctx);
-
-/* Tuning knob for benchmarking kernel variants ("gram_variant", "wgrad_variant",
- * "stream_blocks_per_cu", "ip_group", "stats_variant", "overlap_aux", ...).  Unknown names give ADLOCO_EINVAL.  Results never depend on
- * a knob beyond floating-point summation order. */
-int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
-
-/* Measurement aid.  After adloco_set_tuning(ctx, "profile", 1) every launch of the named
- * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table",
- * "inner_step", "inner_products", "tile_stats") is bracketed by HIP
- * events on the call's stream.  adloco_profile_read waits for the recorded events of that
- * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
-int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
 
 /* ------------------------------------------------------------------------------------ *
  * Gradient statistics.
@@ -142,7 +142,11 @@ typedef struct {
  *            is overwritten); with it, S1, n_samples and grad_sum continue from their values
  *            (ADLOCO_ESTATE is NOT detected on the device: the flag is the caller's promise
  *            that acc and grad_sum hold the earlier micro-batches of the same batch).
- *   flags    0 or ADLOCO_ACCUMULATE
+ *   flags    0, ADLOCO_ACCUMULATE and / or ADLOCO_SUM_ONLY.  With ADLOCO_SUM_ONLY the call is the
+ *            plain "g <- g + grad L" of Algorithm 3 for a batch whose statistics nobody asks for
+ *            (every batch but the one that feeds the norm test): grad_sum (+)= sum_i delta_i^T a_i
+ *            by an ordinary GEMM, nothing else is written; per_sample_sqnorm, per_layer_sample_sqnorm
+ *            and acc may be NULL.
  * bf16 and fp16 inputs are multiplied exactly and accumulated in fp32 (MFMA); fp32 inputs in
  * fp32.  16-bit rows must be 2-byte aligned; 16-byte aligned rows with d % 8 == 0 take the fast
  * path, anything else a slower guarded path (same results).
@@ -317,9 +321,12 @@ int adloco_check_merge(const int64_t* b_req, int k, int w, int* sel_out, int* n_
  *      (x_m <- x_Ti), then runs `inner_steps` inner steps.  Each inner step takes accum
  *      micro-batches of b_micro samples: batch_fn -> adloco_grad_stats (ADLOCO_ACCUMULATE from
  *      the second micro-batch on: Algorithm 3's "g <- g + grad L") -> adloco_inner_step with
- *      g = grad / (accum * b_micro).  After the first inner step of worker 0 the norm test
- *      (adloco_norm_test with b_cur = b_req_i) gives the trainer's requested batch for the NEXT
- *      outer step ("store b_req for the next outer step").
+ *      g = grad / (accum * b_micro).  After the first inner step of worker 0 the norm test gives the
+ *      trainer's requested batch for the NEXT outer step ("store b_req for the next outer step"):
+ *      adloco_norm_test with b_cur = accum * b_micro, the samples the statistics come from (eq. 4
+ *      compares with the size of the batch at hand, which SwitchMode may have cut to b_max), then
+ *      b_req_i <- max(b_req_i, result) so that the request never shrinks.  Every other batch of the
+ *      outer step only needs its gradient sum (ADLOCO_SUM_ONLY).
  *   3. per trainer: Delta = (1/M) sum_m (x_Ti - x_m), x_Ti <- OuterOpt(x_Ti, Delta)
  *      (adloco_outer_step).
  * Readings of the listing: the switch decision is per trainer; the accumulate branch also runs
@@ -365,7 +372,9 @@ typedef struct {
  * (device) on `b` fresh samples and describes the result: on entry layers[l] holds d_in, d_out,
  * grad_sum, flags of the template; the callback fills a, delta and the row strides (device
  * tensors [b, T, .] that stay valid until the next callback for this trainer), and for blocks
- * with ADLOCO_GRAD_PROVIDED adds its own gradient sum into grad_sum.  Device work of the callback
+ * with ADLOCO_GRAD_PROVIDED maintains grad_sum itself: it STORES its gradient sum there when
+ * micro_step is 0 (the driver does not clear such blocks between inner steps) and adds to it when
+ * micro_step > 0.  Device work of the callback
  * must be ordered before later work on `stream`.  Return 0, or non-zero to abort the round. */
 typedef int (*adloco_batch_fn)(void* user, int32_t worker, int32_t inner_step, int32_t micro_step,
                                int64_t b, const float* theta, adloco_linear_desc* layers,

@@ -1,0 +1,31 @@
+/*
+ * adloco_internal.h -- measurement aids of libadloco.  NOT part of the library's interface: these
+ * two calls exist for the repository's own benchmark and tests (kernel variants, per-kernel
+ * timing); nothing a caller of the library needs depends on them, and they may change or go
+ * without notice.
+ */
+#ifndef ADLOCO_INTERNAL_H
+#define ADLOCO_INTERNAL_H
+
+#include "adloco.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Tuning knob for benchmarking kernel variants ("gram_variant", "wgrad_variant",
+ * "stream_blocks_per_cu", "ip_group", "stats_variant", "overlap_aux", ...).  Unknown names give
+ * ADLOCO_EINVAL.  Results never depend on a knob beyond floating-point summation order. */
+int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
+
+/* Measurement aid.  After adloco_set_tuning(ctx, "profile", 1) every launch of the named
+ * kernel ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge", "vector_table",
+ * "inner_step", "inner_products", "tile_stats") is bracketed by HIP
+ * events on the call's stream.  adloco_profile_read waits for the recorded events of that
+ * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
+int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADLOCO_INTERNAL_H */

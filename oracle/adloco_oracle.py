@@ -25,11 +25,15 @@ sum_i <g_i, G> = ||G||^2, numpy's var, the explicit residual vectors against the
 the collinear / orthogonal special cases; torch.optim.AdamW and the first-step / zero-gradient
 closed forms for the inner step; LocalSGD averaging (Section 3.1) and
 torch.optim.SGD(nesterov=True) for the outer step; convexity / identity cases for the
-merge; Algorithm 1's branches enumerated by hand.
+merge; Algorithm 1's branches enumerated by hand; for round_step (one outer step of Algorithm 3)
+a case of 3 trainers x 2 workers x 2 inner steps with a merge, a batch cut to b_max and an
+accumulated batch, sequenced by a separate script from the element functions above
+(tests/golden/make_round_step_case.py), which ten planted mistakes in round_step each fail.
 
 Parity unpinned (the paper fixes none of these; they are readings documented in the
 design notes): the 1/(B-1) normalisation of the variance, the B = 1 convention, the
-monotone clamp b_req >= b_cur and the optional ceiling b_cap.
+monotone clamp b_req >= b_cur and the optional ceiling b_cap; in round_step the reading of the
+listing itself (which batch feeds the norm test, H inner steps in the accumulate branch).
 """
 from __future__ import annotations
 
@@ -446,7 +450,8 @@ def round_step(trainers, cfg: dict, batch_fn) -> list:
     The flat parameter vector is the concatenation of the blocks in list order (a linear weight
     row-major [d_out, d_in]).  Readings as in the design notes: the switch decision is per trainer,
     the accumulate branch runs the same number of inner steps, each over its accumulated
-    micro-batches, and the norm test runs on the first inner step's batch of worker 0.
+    micro-batches, and the norm test runs on the first inner step's batch of worker 0 with b_cur =
+    the samples that batch held; the next request is never below the previous one.
     Returns one report dict per remaining trainer."""
     # CheckMerge / DoMerge (Algorithms 1 and 2)
     if len(trainers) > 1 and cfg["merge_w"] > 0:
@@ -471,10 +476,13 @@ def round_step(trainers, cfg: dict, batch_fn) -> list:
                 blocks = concat_micro_batches(micro)
                 st = grad_stats(blocks, two_pass=False)
                 if m == 0 and h == 0:
-                    nt = norm_test(st["S1"], st["S2"], st["B"], cfg["eta"], int(t["b_req"]), cfg["b_max"],
+                    # eq. 4 compares with the size of the batch the statistics come from, which
+                    # SwitchMode may have cut to b_max (Section 4.2); the previous request stays
+                    # the floor of the next one (b_{k+1} >= b_k)
+                    nt = norm_test(st["S1"], st["S2"], st["B"], cfg["eta"], int(st["B"]), cfg["b_max"],
                                    cfg["n_switch"], cfg["b_cap"])
                     rep["test"] = nt
-                    b_next = nt["b_req"]
+                    b_next = max(int(t["b_req"]), int(nt["b_req"]))
                 g = np.concatenate([np.asarray(G).reshape(-1) for G in st["G"]])
                 w["step"] += 1
                 o = inner_step(w["theta"], w["exp_avg"], w["exp_avg_sq"], g, w["step"], cfg["lr_inner"],

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "adloco.h"
+#include "adloco_internal.h"
 
 namespace adloco {
 
@@ -165,6 +166,10 @@ struct adloco_ctx {
   int overlap_aux = 1;
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
+  int table_inputs = -1;       // 1: the table was built by a call that reads a and delta
+  // region-form Gram kernel: job lists of the persistent workgroups and the parking area
+  adloco::Scratch pk_jobs, pk_start, pk_park;
+  int pk_B = -1, pk_T = -1;    // batch shape the job lists were built for
   long long max_lin_stride = 0;  // widest row stride (elements) among the linear blocks of the table
   double* pinned = nullptr;    // 8 doubles of pinned host memory (read-back of the tests' sums)
   double* dev_scalars = nullptr;  // 4 doubles on the device (S2, ...)

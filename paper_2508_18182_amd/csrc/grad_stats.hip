@@ -12,7 +12,66 @@ namespace {
 
 constexpr int kMaxLayers = 4096;
 
-// Build the device view of the layer list and upload it when it differs from the cached copy.
+// The device copy of the layer table keeps its shapes, strides and launch positions from call to
+// call; only the three pointers of every block change when the caller hands in other tensors (fresh
+// activations of the next micro-batch, another worker's gradient buffers).  They travel in the
+// argument of a small kernel, so that a call on a known list of shapes uploads nothing, waits for
+// nothing, and can be captured into a graph with its pointers in it.
+constexpr int kPtrChunk = 120;
+struct PtrChunk {
+  int first, count, which;            // which: 1 = a and delta, 2 = grad_sum, 3 = all
+  int pad;
+  const void* a[kPtrChunk];
+  const void* delta[kPtrChunk];
+  float* grad_sum[kPtrChunk];
+};
+__global__ void set_layer_pointers_kernel(LayerDev* tab, PtrChunk c) {
+  const int i = threadIdx.x;
+  if (i >= c.count) return;
+  LayerDev& L = tab[c.first + i];
+  if (c.which & 1) {
+    L.a = c.a[i];
+    L.delta = c.delta[i];
+  }
+  if (c.which & 2) L.grad_sum = c.grad_sum[i];
+}
+
+int upload_pointers(adloco_ctx* ctx, const std::vector<LayerDev>& tab, int which, hipStream_t st) {
+  PtrChunk c;
+  for (size_t first = 0; first < tab.size(); first += kPtrChunk) {
+    c.first = int(first);
+    c.count = int(std::min<size_t>(kPtrChunk, tab.size() - first));
+    c.which = which;
+    c.pad = 0;
+    for (int i = 0; i < c.count; ++i) {
+      c.a[i] = tab[first + i].a;
+      c.delta[i] = tab[first + i].delta;
+      c.grad_sum[i] = tab[first + i].grad_sum;
+    }
+    hipLaunchKernelGGL(set_layer_pointers_kernel, dim3(1), dim3(128), 0, st,
+                       static_cast<LayerDev*>(ctx->layer_tab.ptr), c);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+      return fail(ctx, ADLOCO_EHIP, "pointer table launch failed: %s", hipGetErrorString(e));
+  }
+  return ADLOCO_OK;
+}
+
+// Everything of a block that the tables, tile lists and kernel choices depend on: all of LayerDev
+// but the addresses themselves (their alignment class is in `fast`, whether they are there at all
+// is compared).
+bool same_shape(const LayerDev& x, const LayerDev& y) {
+  return x.a_stride == y.a_stride && x.delta_stride == y.delta_stride && x.d_in == y.d_in &&
+         x.d_out == y.d_out && x.fast == y.fast && x.provided == y.provided && x.kind == y.kind &&
+         x.wg_blk_start == y.wg_blk_start && x.sq_blk_start == y.sq_blk_start &&
+         (x.a == nullptr) == (y.a == nullptr) && (x.delta == nullptr) == (y.delta == nullptr) &&
+         (x.grad_sum == nullptr) == (y.grad_sum == nullptr);
+}
+
+// Build the device view of the layer list.  A list whose shapes (widths, strides, kinds, flags,
+// alignment classes) equal those of the previous call only has its pointers refreshed, by a kernel on
+// the caller's stream; any other list rebuilds every table that depends on it, which allocates,
+// copies from pageable memory and waits for the stream.
 int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers, int dtype,
                    bool need_inputs, hipStream_t st) {
   const size_t esize = is_16bit(dtype) ? 2 : 4;
@@ -79,10 +138,15 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
       return fail(ctx, ADLOCO_EUNSUPPORTED, "layer list too large for one launch");
     tab[l] = L;
   }
-  const bool same = ctx->table_dtype == dtype && tab.size() == ctx->layer_tab_host.size() &&
-                    std::memcmp(tab.data(), ctx->layer_tab_host.data(),
-                                tab.size() * sizeof(LayerDev)) == 0;
-  if (same) return ADLOCO_OK;
+  bool same = ctx->table_dtype == dtype && ctx->table_inputs == int(need_inputs) &&
+              tab.size() == ctx->layer_tab_host.size();
+  for (size_t l = 0; same && l < tab.size(); ++l) same = same_shape(tab[l], ctx->layer_tab_host[l]);
+  if (same) {
+    int rc = upload_pointers(ctx, tab, 3, st);
+    if (rc) return rc;
+    ctx->layer_tab_host = std::move(tab);
+    return ADLOCO_OK;
+  }
   // linear layers, heaviest first, so that the tail of the Gram launch is made of cheap workgroups
   std::vector<int> order;
   for (int l = 0; l < n_layers; ++l)
@@ -96,6 +160,7 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   if (rc) return rc;
   ctx->layer_tab_host.clear();          // invalid until both copies are enqueued
   ctx->table_dtype = -1;
+  ctx->pk_B = ctx->pk_T = -1;           // the job lists of the region-form Gram kernel follow the table
   ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->layer_tab.ptr, tab.data(), tab.size() * sizeof(LayerDev),
                                        hipMemcpyHostToDevice, st));
   if (!order.empty())
@@ -150,6 +215,7 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   ctx->order_host = std::move(order);
   ctx->wgrad_blocks = int(wg);
   ctx->table_dtype = dtype;
+  ctx->table_inputs = int(need_inputs);
   return ADLOCO_OK;
 }
 
@@ -230,10 +296,11 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   if (B < 1 || T < 1) return fail(ctx, ADLOCO_EINVAL, "grad_stats: B = %d, T = %d must be >= 1", B, T);
   if (dtype != ADLOCO_F32 && !is_16bit(dtype))
     return fail(ctx, ADLOCO_EUNSUPPORTED, "grad_stats: dtype %d not supported", dtype);
-  if (!per_sample_sqnorm || !acc) return fail(ctx, ADLOCO_EINVAL, "grad_stats: NULL output");
+  if (flags & ~(ADLOCO_ACCUMULATE | ADLOCO_SUM_ONLY)) return fail(ctx, ADLOCO_EINVAL, "grad_stats: unknown flags");
+  const bool sum_only = (flags & ADLOCO_SUM_ONLY) != 0;
+  if (!sum_only && (!per_sample_sqnorm || !acc)) return fail(ctx, ADLOCO_EINVAL, "grad_stats: NULL output");
   if (reinterpret_cast<uintptr_t>(acc) % 8)
     return fail(ctx, ADLOCO_EINVAL, "grad_stats: acc not 8-byte aligned");
-  if (flags & ~ADLOCO_ACCUMULATE) return fail(ctx, ADLOCO_EINVAL, "grad_stats: unknown flags");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int accumulate = (flags & ADLOCO_ACCUMULATE) ? 1 : 0;
 
@@ -273,7 +340,8 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
 
   // Per-sample gradient tiles (explicit form) when every linear block qualifies: the tiles that
   // add up to the gradient sum are squared on the way, no Gram contraction is needed.
-  const bool tile_form = ctx->stats_variant != 0 && ctx->ts_ok && T % 32 == 0 && T <= (1 << 20) && B <= 0x7fff;
+  const bool tile_form = !sum_only && ctx->stats_variant != 0 && ctx->ts_ok && T % 32 == 0 &&
+                         T <= (1 << 20) && B <= 0x7fff;
   if (tile_form && ctx->ts_B != B) {
     const std::vector<LayerDev>& tab = ctx->layer_tab_host;
     std::vector<char> use(n_layers, 0);
@@ -347,7 +415,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
                                         int(ctx->vec_host.size()), ctx->vec_blocks, ctx->vec_blocks2, B, T,
                                         dtype, static_cast<float*>(ctx->aux_vec.ptr), g.partials,
                                         int(n_pairs), accumulate, true, aux_st);
-    if (ea == hipSuccess)
+    if (ea == hipSuccess && !sum_only)
       ea = launch_embed_stats(g.layers, static_cast<const AuxDesc*>(ctx->emb_tab.ptr),
                               int(ctx->emb_host.size()), ctx->emb_blocks, B, T, dtype,
                               static_cast<int*>(ctx->aux_perm.ptr),
@@ -378,8 +446,8 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
     if (e != hipSuccess)
       return fail(ctx, ADLOCO_EHIP, "grad_stats: tile statistics launch failed: %s", hipGetErrorString(e));
   }
-  ev = (!tile_form && ctx->n_linear > 0) ? prof_begin(ctx, st) : nullptr;
-  if (tile_form || ctx->n_linear == 0)
+  ev = (!tile_form && !sum_only && ctx->n_linear > 0) ? prof_begin(ctx, st) : nullptr;
+  if (tile_form || sum_only || ctx->n_linear == 0)
     ;
   else if (dual)
     e = launch_gram_bf16_dual(g, static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n,
@@ -414,6 +482,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
     ADLOCO_HIP_CHECK(ctx, hipEventRecord(ctx->ev_join, aux_st));
     ADLOCO_HIP_CHECK(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
   }
+  if (sum_only) return ADLOCO_OK;       // the gradient sums are all this call was asked for
   e = launch_finalize_stats(g.partials, n_layers, B, int(n_pairs), per_sample_sqnorm,
                             per_layer_sample_sqnorm, static_cast<double*>(ctx->sample_f64.ptr),
                             acc, accumulate, st);
@@ -437,14 +506,20 @@ extern "C" int adloco_norm_test(adloco_ctx* ctx, const adloco_linear_desc* layer
   hipStream_t st = static_cast<hipStream_t>(stream);
   // the table is shared with grad_stats: same layer list -> no upload
   const int dtype = ctx->table_dtype >= 0 ? ctx->table_dtype : ADLOCO_BF16;
+  // (same widths as the table of the last call: only the grad_sum pointers are refreshed)
   bool cached = ctx->layer_tab_host.size() == size_t(n_layers);
   if (cached)
     for (int l = 0; l < n_layers && cached; ++l) {
       const LayerDev& L = ctx->layer_tab_host[l];
-      cached = L.grad_sum == layers[l].grad_sum && L.d_in == layers[l].d_in &&
-               L.d_out == layers[l].d_out && layers[l].grad_sum != nullptr;
+      cached = L.grad_sum != nullptr && L.d_in == layers[l].d_in && L.d_out == layers[l].d_out &&
+               layers[l].grad_sum != nullptr && (reinterpret_cast<uintptr_t>(layers[l].grad_sum) % 4) == 0;
     }
-  if (!cached) {
+  if (cached) {
+    // (written on every call: a graph replayed in between may have left other pointers in the table)
+    for (int l = 0; l < n_layers; ++l) ctx->layer_tab_host[l].grad_sum = layers[l].grad_sum;
+    int rc = upload_pointers(ctx, ctx->layer_tab_host, 2, st);
+    if (rc) return rc;
+  } else {
     int rc = prepare_tables(ctx, layers, n_layers, dtype, false, st);
     if (rc) return rc;
   }

@@ -118,16 +118,22 @@ extern "C" int adloco_round(adloco_ctx* ctx, const adloco_round_config* cfg, adl
           if (batch_fn(t.user, m, h, int(s), R.b_micro, w.theta, desc.data(), n_layers, stream) != 0)
             return fail(ctx, ADLOCO_ESTATE, "round: batch_fn failed (trainer %d, worker %d, inner step "
                         "%d, micro-batch %lld)", i, m, h, (long long)s);
+          // only the first inner step of worker 0 feeds the norm test: every other batch is a plain
+          // gradient accumulation
+          const uint32_t want = (m == 0 && h == 0) ? 0u : ADLOCO_SUM_ONLY;
           rc = adloco_grad_stats(ctx, desc.data(), n_layers, int(R.b_micro), cfg->T, cfg->dtype,
-                                 t.per_sample_sqnorm, nullptr, t.acc, s > 0 ? ADLOCO_ACCUMULATE : 0u,
-                                 stream);
+                                 t.per_sample_sqnorm, nullptr, t.acc,
+                                 (s > 0 ? ADLOCO_ACCUMULATE : 0u) | want, stream);
           if (rc) return rc;
         }
         if (m == 0 && h == 0) {
-          rc = adloco_norm_test(ctx, desc.data(), n_layers, t.acc, cfg->eta, t.b_req, cfg->b_max,
-                                cfg->n_switch, cfg->b_cap, 0, &R.test, stream);
+          // b_cur = the samples this batch really held (SwitchMode may have cut the request to
+          // b_max); the previous request stays the floor of the next one
+          rc = adloco_norm_test(ctx, desc.data(), n_layers, t.acc, cfg->eta,
+                                R.accum_steps * R.b_micro, cfg->b_max, cfg->n_switch, cfg->b_cap, 0,
+                                &R.test, stream);
           if (rc) return rc;
-          b_next = R.test.b_req;
+          b_next = std::max<int64_t>(t.b_req, R.test.b_req);
         }
         ++w.step;
         rc = adloco_inner_step(ctx, w.theta, w.exp_avg, w.exp_avg_sq, w.grad, N,

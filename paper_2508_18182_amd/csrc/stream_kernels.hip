@@ -285,6 +285,14 @@ static hipError_t launch_merge_s(const MergeArgs& a, bool vec, int bpc, hipStrea
 
 using namespace adloco;
 
+// Two [N] float vectors overlap (either pointer may be NULL: no vector, no overlap).
+static bool ranges_overlap(const void* p, const void* q, size_t N) {
+  if (!p || !q) return false;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(q);
+  const uintptr_t bytes = uintptr_t(N) * sizeof(float);
+  return a < b + bytes && b < a + bytes;
+}
+
 extern "C" int adloco_outer_step(adloco_ctx* ctx, float* theta_outer, float* const* theta_inst,
                                  int M, size_t N, float* momentum, double lr, double mu,
                                  int nesterov, uint32_t flags, float* pseudo_grad_out,
@@ -307,18 +315,21 @@ extern "C" int adloco_outer_step(adloco_ctx* ctx, float* theta_outer, float* con
   for (int m = 0; m < M; ++m) {
     float* p = theta_inst[m];
     if (!p) return fail(ctx, ADLOCO_EINVAL, "outer_step: theta_inst[%d] is NULL", m);
-    if (p == theta_outer || p == momentum || p == pseudo_grad_out)
-      return fail(ctx, ADLOCO_EINVAL, "outer_step: theta_inst[%d] aliases another argument", m);
+    if (ranges_overlap(p, theta_outer, N) || ranges_overlap(p, momentum, N) ||
+        ranges_overlap(p, pseudo_grad_out, N))
+      return fail(ctx, ADLOCO_EINVAL, "outer_step: theta_inst[%d] overlaps another argument", m);
+    // (instances that are only read may be one and the same vector; written ones may not overlap)
     for (int j = 0; j < m; ++j)
-      if (theta_inst[j] == p && (flags & ADLOCO_BROADCAST))
-        return fail(ctx, ADLOCO_EINVAL, "outer_step: theta_inst[%d] == theta_inst[%d]", j, m);
+      if ((flags & ADLOCO_BROADCAST) ? ranges_overlap(theta_inst[j], p, N)
+                                     : (theta_inst[j] != p && ranges_overlap(theta_inst[j], p, N)))
+        return fail(ctx, ADLOCO_EINVAL, "outer_step: theta_inst[%d] overlaps theta_inst[%d]", j, m);
     vec = vec && aligned16(p);
     a.inst[m] = p;
   }
-  if (momentum && (momentum == theta_outer || momentum == pseudo_grad_out))
-    return fail(ctx, ADLOCO_EINVAL, "outer_step: momentum aliases another argument");
-  if (pseudo_grad_out && pseudo_grad_out == theta_outer)
-    return fail(ctx, ADLOCO_EINVAL, "outer_step: pseudo_grad_out aliases theta_outer");
+  if (ranges_overlap(momentum, theta_outer, N) || ranges_overlap(momentum, pseudo_grad_out, N))
+    return fail(ctx, ADLOCO_EINVAL, "outer_step: momentum overlaps another argument");
+  if (ranges_overlap(pseudo_grad_out, theta_outer, N))
+    return fail(ctx, ADLOCO_EINVAL, "outer_step: pseudo_grad_out overlaps theta_outer");
   if (N / 4 > kMaxVecPerLaunch)
     return fail(ctx, ADLOCO_EUNSUPPORTED, "outer_step: N = %zu exceeds one launch", N);
   a.n = N;
@@ -364,7 +375,8 @@ extern "C" int adloco_merge(adloco_ctx* ctx, float* const* x, const double* weig
   for (int j = 0; j < S; ++j) {
     if (!x[j]) return fail(ctx, ADLOCO_EINVAL, "merge: x[%d] is NULL", j);
     for (int i = 0; i < j; ++i)
-      if (x[i] == x[j]) return fail(ctx, ADLOCO_EINVAL, "merge: x[%d] == x[%d]", i, j);
+      if (ranges_overlap(x[i], x[j], N))
+        return fail(ctx, ADLOCO_EINVAL, "merge: x[%d] overlaps x[%d]", i, j);
     vec = vec && aligned16(x[j]);
     a.x[j] = x[j];
   }
@@ -400,7 +412,8 @@ extern "C" int adloco_inner_step(adloco_ctx* ctx, float* theta, float* exp_avg, 
   const void* p[4] = {theta, exp_avg, exp_avg_sq, grad};
   for (int i = 0; i < 4; ++i)
     for (int j = 0; j < i; ++j)
-      if (p[i] == p[j]) return fail(ctx, ADLOCO_EINVAL, "inner_step: two arguments alias");
+      if (ranges_overlap(p[i], p[j], N))
+        return fail(ctx, ADLOCO_EINVAL, "inner_step: two arguments overlap");
   if (N / 4 > kMaxVecPerLaunch)
     return fail(ctx, ADLOCO_EUNSUPPORTED, "inner_step: N = %zu exceeds one launch", N);
   const bool vec = aligned16(theta) && aligned16(exp_avg) && aligned16(exp_avg_sq) && aligned16(grad);

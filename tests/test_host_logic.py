@@ -29,14 +29,18 @@ def _ints(s):
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "adloco.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(adloco_[a-z_]+)\s*\(", hdr))
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["adloco.h", "adloco_internal.h"]
+    names = set()
+    for h in headers:
+        hdr = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(adloco_[a-z_]+)\s*\(", hdr))
     assert {"adloco_grad_stats", "adloco_norm_test", "adloco_outer_step", "adloco_merge",
             "adloco_check_merge", "adloco_create", "adloco_destroy"} <= names
     lib = ctypes.CDLL(A.lib_path())
     for n in sorted(names):
-        assert hasattr(lib, n), f"{n} declared in adloco.h but not exported"
+        assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
     assert A.adloco_version() >= 100
 
 

@@ -782,3 +782,95 @@ def test_round_merge_switch_and_bookkeeping():
     orc.round_step(ts2, dict(_ROUND_CFG, lr_inner=0.0, weight_decay=0.0), fn)
     for t, b in zip(ts2, before):
         np.testing.assert_array_equal(t["theta_outer"], b)
+
+
+# ------------------------------------------------------------------ round_step against a case sequenced by hand
+
+_CASE_SHAPES, _CASE_T = [(3, 2), (2, 2)], 2
+_CASE_N = sum(a * b for a, b in _CASE_SHAPES)
+_CASE_CFG = dict(inner_steps=2, b_max=2, n_switch=2, b_cap=64, eta=0.5, merge_w=2, lr_inner=1e-3,
+                 beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.1, lr_outer=0.7, mu_outer=0.9,
+                 nesterov=1)
+
+
+def _round_case_expected():
+    want = dict(test={}, worker={}, switch={}, theta_outer={}, momentum={})
+    for ln in open(os.path.join(GOLD, "round_step_case.txt")):
+        f = ln.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "remaining_uids":
+            want["uids"] = [int(v) for v in f[1:]]
+        elif f[0] == "merged_from":
+            want["merged_from"] = [int(v) for v in f[1:]]
+        elif f[0] == "test":
+            want["test"][int(f[1])] = dict(b_cur=int(f[3]), stat=float(f[5]), passed=int(f[7]), b_next=int(f[9]))
+        elif f[0] == "worker":
+            want["worker"][(int(f[1]), int(f[2]))] = (int(f[4]), np.array([float(v) for v in f[6:]]))
+        elif f[0] == "switch":
+            want["switch"][int(f[1])] = (int(f[3]), int(f[5]), int(f[7]))
+        else:
+            want[f[0]][int(f[1])] = np.array([float(v) for v in f[2:]])
+    return want
+
+
+def _round_case_check(round_fn):
+    """Runs round_fn on the case of tests/golden/round_step_case.txt and compares everything the
+    fixture holds.  Raises AssertionError on the first difference."""
+    import adloco_synth as synth
+    fn = synth.round_batch_fn(_CASE_SHAPES, _CASE_T)
+    ts = synth.round_trainers(3, 2, _CASE_N, [3, 5, 2], stale_workers=True)
+    rep = round_fn(ts, dict(_CASE_CFG), fn)
+    want = _round_case_expected()
+    assert [t["uid"] for t in ts] == want["uids"]
+    assert [r["merged_from"] for r in rep] == want["merged_from"]
+    for t, r in zip(ts, rep):
+        u = t["uid"]
+        assert (r["accumulate"], r["accum_steps"], r["b_micro"]) == want["switch"][u]
+        w = want["test"][u]
+        assert r["test"]["b_cur"] == w["b_cur"] and r["test"]["test_passed"] == w["passed"]
+        np.testing.assert_allclose(r["test"]["stat"], w["stat"], rtol=1e-9)
+        assert t["b_req"] == w["b_next"]
+        for m, wk in enumerate(t["workers"]):
+            step, theta = want["worker"][(u, m)]
+            assert wk["step"] == step
+            np.testing.assert_allclose(wk["theta"], theta, rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(t["theta_outer"], want["theta_outer"][u], rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(t["momentum"], want["momentum"][u], rtol=2e-6, atol=1e-10)
+
+
+def test_round_step_matches_the_case_sequenced_by_hand():
+    # 3 trainers x 2 workers, H = 2, a merge, one trainer cut to b_max, one accumulating 3 x 2:
+    # expected values from tests/golden/make_round_step_case.py, which never calls round_step
+    _round_case_check(orc.round_step)
+
+
+_ROUND_MUTATIONS = [
+    # (what goes wrong, text of round_step, replacement)
+    ("gradient scale without the accumulation count",
+     'grad_scale=1.0 / (sm["accum_steps"] * sm["b_micro"])', 'grad_scale=1.0 / sm["b_micro"]'),
+    ("norm test on another worker's batch", "if m == 0 and h == 0:", "if m == 1 and h == 0:"),
+    ("norm test on the second inner step's batch", "if m == 0 and h == 0:", "if m == 0 and h == 1:"),
+    ("workers not reset to the trainer's model",
+     'w["theta"] = np.array(t["theta_outer"], dtype=np.float32, copy=True)', 'w["theta"] = w["theta"]'),
+    ("norm test told the requested instead of the actual batch size",
+     'cfg["eta"], int(st["B"]), cfg["b_max"]', 'cfg["eta"], int(t["b_req"]), cfg["b_max"]'),
+    ("next request may shrink", 'b_next = max(int(t["b_req"]), int(nt["b_req"]))', 'b_next = int(nt["b_req"]) - 8'),
+    ("one micro-batch too few", 'for s in range(sm["accum_steps"])]', 'for s in range(max(1, sm["accum_steps"] - 1))]'),
+    ("step count not advanced", 'w["step"] += 1', 'w["step"] += 0'),
+    ("merge weights ignored", '[trainers[j]["b_req"] for j in sel])', '[1 for j in sel])'),
+    ("outer step over the first worker only", '[w["theta"] for w in t["workers"]]', '[t["workers"][0]["theta"]]'),
+]
+
+
+@pytest.mark.parametrize("what,old,new", _ROUND_MUTATIONS, ids=[m[0] for m in _ROUND_MUTATIONS])
+def test_round_step_case_catches_planted_mistakes(what, old, new):
+    # the case above must fail as soon as round_step is wrong in one of the ways a driver of
+    # Algorithm 3 plausibly is: the mistake is planted in a copy of the oracle's own source
+    import inspect
+    src = inspect.getsource(orc.round_step)
+    assert src.count(old) == 1, f"mutation target not found: {old}"
+    ns = dict(vars(orc))
+    exec(compile(src.replace(old, new), "<mutated round_step>", "exec"), ns)
+    with pytest.raises(AssertionError):
+        _round_case_check(ns["round_step"])
