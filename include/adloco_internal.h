@@ -25,6 +25,11 @@ int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
  * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
 int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
 
+/* Number of times the context has built its shape-dependent tables (tile, job and descriptor
+ * tables): it moves on the first call with a new list of shapes and stays put while only the
+ * addresses in a, delta and grad_sum change from call to call. */
+int adloco_table_builds(const adloco_ctx* ctx);
+
 #ifdef __cplusplus
 }
 #endif

@@ -5,7 +5,7 @@ The Python layer only marshals arguments (device pointers of torch tensors, the 
 HIP stream); every step of the path runs in the HIP kernels of libadloco.so.
 """
 from .binding import (  # noqa: F401
-    ADLOCO_ACCUMULATE, ADLOCO_ALLOW_SHRINK, ADLOCO_BF16, ADLOCO_BIASED_VAR, ADLOCO_BROADCAST,
+    ADLOCO_ACCUMULATE, ADLOCO_SUM_ONLY, ADLOCO_ALLOW_SHRINK, ADLOCO_BF16, ADLOCO_BIASED_VAR, ADLOCO_BROADCAST,
     ADLOCO_F16, ADLOCO_F32, ADLOCO_GRAD_PROVIDED, ADLOCO_KIND_EMBED, ADLOCO_KIND_LINEAR, ADLOCO_KIND_VECTOR,
     ADLOCO_MAX_INSTANCES, AdlocoError, Context, IpAcc, IpTestResult, LinearDesc,
     NormTestResult, StatsAcc, adloco_check_merge, adloco_grad_stats, adloco_inner_product_decide,

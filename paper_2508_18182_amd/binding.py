@@ -14,6 +14,7 @@ _LIB_PATH = os.environ.get("ADLOCO_LIBRARY_PATH") or os.path.join(_PKG, "libadlo
 
 ADLOCO_F32, ADLOCO_BF16, ADLOCO_F16 = 0, 1, 2
 ADLOCO_ACCUMULATE = 0x1
+ADLOCO_SUM_ONLY = 0x2
 ADLOCO_GRAD_PROVIDED = 0x1
 ADLOCO_KIND_LINEAR, ADLOCO_KIND_VECTOR, ADLOCO_KIND_EMBED = 0x00, 0x10, 0x20
 ADLOCO_BROADCAST = 0x1
@@ -131,6 +132,8 @@ def load_library():
     lib.adloco_set_tuning.argtypes = [vp, C.c_char_p, C.c_int]
     lib.adloco_profile_read.argtypes = [vp, C.c_char_p, C.POINTER(dbl), C.POINTER(C.c_int)]
     lib.adloco_profile_read.restype = C.c_int
+    lib.adloco_table_builds.argtypes = [vp]
+    lib.adloco_table_builds.restype = C.c_int
     lib.adloco_grad_stats.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, C.c_int, C.c_int, C.c_int,
                                       vp, vp, vp, u32, vp]
     lib.adloco_norm_test.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, vp, dbl, i64, i64, i32,
@@ -198,6 +201,10 @@ class Context:
 
     def set_tuning(self, name: str, value: int):
         self._check(load_library().adloco_set_tuning(self._h, name.encode(), int(value)))
+
+    def table_builds(self) -> int:
+        """Number of times this context has (re)built its shape-dependent tables (measurement aid)."""
+        return int(load_library().adloco_table_builds(self._h))
 
     def profile_read(self, kernel: str):
         """(total milliseconds, launches) of the named kernel since the last read."""
@@ -304,10 +311,13 @@ def adloco_grad_stats(ctx: Context, layers: Sequence[dict], B: int, T: int, dtyp
     n = len(arr)
     ps = _dev_ptr(per_sample_sqnorm, torch.float32, B, "per_sample_sqnorm")
     pl = _dev_ptr(per_layer_sample_sqnorm, torch.float32, n * B, "per_layer_sample_sqnorm")
-    if acc is None or not acc.is_cuda or acc.numel() * acc.element_size() < 16:
+    if acc is None and (flags & ADLOCO_SUM_ONLY):
+        acc_ptr = C.c_void_p(None)
+    elif acc is None or not acc.is_cuda or acc.numel() * acc.element_size() < 16:
         raise ValueError("acc must be a GPU tensor of at least 16 bytes")
-    ctx._check(load_library().adloco_grad_stats(ctx._h, arr, n, B, T, dtype, ps, pl,
-                                                C.c_void_p(acc.data_ptr()), flags,
+    else:
+        acc_ptr = C.c_void_p(acc.data_ptr())
+    ctx._check(load_library().adloco_grad_stats(ctx._h, arr, n, B, T, dtype, ps, pl, acc_ptr, flags,
                                                 _stream_ptr(stream)))
 
 

@@ -167,6 +167,7 @@ struct adloco_ctx {
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
   int table_inputs = -1;       // 1: the table was built by a call that reads a and delta
+  int table_builds = 0;        // how often a shape-dependent table has been (re)built
   // region-form Gram kernel: job lists of the persistent workgroups and the parking area
   adloco::Scratch pk_jobs, pk_start, pk_park;
   int pk_B = -1, pk_T = -1;    // batch shape the job lists were built for

@@ -90,7 +90,9 @@ extern "C" int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* 
   return ADLOCO_OK;
 }
 
-extern "C" int adloco_version(void) { return 100; }
+extern "C" int adloco_version(void) { return 101; }
+
+extern "C" int adloco_table_builds(const adloco_ctx* ctx) { return ctx ? ctx->table_builds : -1; }
 
 extern "C" int adloco_create(adloco_ctx** out, int device) {
   if (!out) {

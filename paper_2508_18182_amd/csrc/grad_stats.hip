@@ -147,6 +147,7 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
     ctx->layer_tab_host = std::move(tab);
     return ADLOCO_OK;
   }
+  ++ctx->table_builds;
   // linear layers, heaviest first, so that the tail of the Gram launch is made of cheap workgroups
   std::vector<int> order;
   for (int l = 0; l < n_layers; ++l)
@@ -223,6 +224,7 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
 // the scratch they need.  Rebuilt when the layer table or the batch shape changed.
 int prepare_vector_table(adloco_ctx* ctx, int B, int T, hipStream_t st) {
   if (ctx->aux_B == B && ctx->aux_T == T) return ADLOCO_OK;
+  ++ctx->table_builds;
   const int slab = vector_table_slab();
   std::vector<AuxDesc> vec, emb;
   long long vb = 0, vb2 = 0, eb = 0, voff = 0, poff = 0, partoff = 0;
@@ -318,6 +320,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   long long n_pairs = nt * (nt + 1) / 2;      // partial sums per (layer, sample)
   if (dual) {
     if (ctx->job_tab_nt != int(nt)) {
+      ++ctx->table_builds;
       std::vector<GramJob> jobs = make_gram_jobs(int(nt));
       rc = ensure_scratch(ctx, ctx->job_tab, jobs.size() * sizeof(GramJob));
       if (rc) return rc;
@@ -343,6 +346,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   const bool tile_form = !sum_only && ctx->stats_variant != 0 && ctx->ts_ok && T % 32 == 0 &&
                          T <= (1 << 20) && B <= 0x7fff;
   if (tile_form && ctx->ts_B != B) {
+    ++ctx->table_builds;
     const std::vector<LayerDev>& tab = ctx->layer_tab_host;
     std::vector<char> use(n_layers, 0);
     for (int l = 0; l < n_layers; ++l) use[l] = tab[l].kind == ADLOCO_KIND_LINEAR;
@@ -580,6 +584,7 @@ extern "C" int adloco_inner_products(adloco_ctx* ctx, const adloco_linear_desc* 
 
   // ---- which blocks go through the tile GEMM, and its tile table
   if (ctx->ip_B != B || ctx->ip_T != T) {
+    ++ctx->table_builds;
     std::vector<char> use(n_layers, 0);
     bool any = false;
     for (int l = 0; l < n_layers; ++l) {
