@@ -194,6 +194,21 @@ int adloco_norm_test(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_la
                      int32_t n_switch, int64_t b_cap, uint32_t flags,
                      adloco_norm_test_result* out, void* stream);
 
+/* adloco_norm_test_noalloc: adloco_norm_test for callers that cannot allocate -- code between
+ * the begin and the end of a graph capture of another stream, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same result; the partial sums and the device
+ * copy of the block table live in a fixed device array of the library (about 1.1 MB per GPU, held
+ * until the process ends) instead of scratch memory that the context allocates on demand, so the
+ * call never allocates, frees or resizes anything.  Limits: n_layers <= 512 and at most 131072
+ * partial sums of 16384 gradient entries each (2^31 entries when every block fills its last
+ * chunk); beyond them ADLOCO_EUNSUPPORTED with the reason in adloco_last_error.  All calls on
+ * one GPU share that array: two calls whose device work may overlap (other streams, other
+ * contexts, other threads) race and must be ordered by the caller.  Waits for `stream`. */
+int adloco_norm_test_noalloc(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_layers,
+                             const adloco_stats_acc* acc, double eta, int64_t b_cur, int64_t b_max,
+                             int32_t n_switch, int64_t b_cap, uint32_t flags,
+                             adloco_norm_test_result* out, void* stream);
+
 /* Host-only halves of adloco_norm_test (no device, no context): the decision from given
  * S1, S2, B, and SwitchMode alone.  Same formulas, same edge conventions. */
 int adloco_norm_test_decide(double S1, double S2, int64_t n_samples, double eta,

@@ -138,6 +138,7 @@ def load_library():
                                       vp, vp, vp, u32, vp]
     lib.adloco_norm_test.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, vp, dbl, i64, i64, i32,
                                      i64, u32, C.POINTER(NormTestResult), vp]
+    lib.adloco_norm_test_noalloc.argtypes = lib.adloco_norm_test.argtypes
     lib.adloco_norm_test_decide.argtypes = [dbl, dbl, i64, dbl, i64, i64, i32, i64, u32,
                                             C.POINTER(NormTestResult)]
     lib.adloco_switch_mode.argtypes = [i64, i64, i32, C.POINTER(i32), C.POINTER(i64),
@@ -158,7 +159,7 @@ def load_library():
     lib.adloco_check_merge.argtypes = [C.POINTER(i64), C.c_int, C.c_int, C.POINTER(C.c_int),
                                        C.POINTER(C.c_int)]
     for name in ("adloco_create", "adloco_destroy", "adloco_set_tuning", "adloco_grad_stats",
-                 "adloco_norm_test", "adloco_norm_test_decide", "adloco_switch_mode",
+                 "adloco_norm_test", "adloco_norm_test_noalloc", "adloco_norm_test_decide", "adloco_switch_mode",
                  "adloco_outer_step", "adloco_merge", "adloco_check_merge", "adloco_inner_step", "adloco_round",
                  "adloco_inner_products", "adloco_inner_product_test", "adloco_inner_product_decide"):
         getattr(lib, name).restype = C.c_int
@@ -388,6 +389,18 @@ def adloco_norm_test(ctx: Context, layers, acc, eta: float, b_cur: int, b_max: i
     ctx._check(load_library().adloco_norm_test(ctx._h, arr, len(arr), C.c_void_p(acc.data_ptr()),
                                                eta, b_cur, b_max, n_switch, b_cap, flags,
                                                C.byref(res), _stream_ptr(stream)))
+    return res.as_dict()
+
+
+def adloco_norm_test_noalloc(ctx: Context, layers, acc, eta: float, b_cur: int, b_max: int,
+                             n_switch: int = 2, b_cap: int = 0, flags: int = 0, stream=None,
+                             descs=None) -> dict:
+    """adloco_norm_test through the entry point that allocates nothing (fixed device array)."""
+    arr = descs if descs is not None else _grad_sum_descs(layers)
+    res = NormTestResult()
+    ctx._check(load_library().adloco_norm_test_noalloc(ctx._h, arr, len(arr), C.c_void_p(acc.data_ptr()),
+                                                       eta, b_cur, b_max, n_switch, b_cap, flags,
+                                                       C.byref(res), _stream_ptr(stream)))
     return res.as_dict()
 
 

@@ -298,5 +298,11 @@ int sqnorm_chunk();
 size_t sqnorm_partials(const std::vector<LayerDev>& host_layers);
 hipError_t launch_sqnorm(const LayerDev* layers, const std::vector<LayerDev>& host_layers,
                          double* partial, double* out, hipStream_t st);
+// The same on a device table of n_layers blocks whose sq_blk_start fields add up to nblk workgroups.
+hipError_t launch_sqnorm_table(const LayerDev* layers, int n_layers, size_t nblk, double* partial,
+                               double* out, hipStream_t st);
+// Looks up, for the context's device, the address of the file-scope device array that serves
+// adloco_norm_test_noalloc (called once per context by adloco_create, with the device current).
+int no_alloc_init(adloco_ctx* ctx);
 
 }  // namespace adloco

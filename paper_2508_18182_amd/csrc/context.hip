@@ -125,6 +125,13 @@ extern "C" int adloco_create(adloco_ctx** out, int device) {
     delete c;
     return ADLOCO_ENOMEM;
   }
+  if (int rc = no_alloc_init(c)) {
+    g_create_err = "adloco_create: " + c->err;
+    (void)hipFree(c->dev_scalars);
+    (void)hipHostFree(c->pinned);
+    delete c;
+    return rc;
+  }
   *out = c;
   return ADLOCO_OK;
 }

@@ -124,13 +124,18 @@ size_t sqnorm_partials(const std::vector<LayerDev>& host_layers) {
 
 int sqnorm_chunk() { return kSqChunk; }
 
-hipError_t launch_sqnorm(const LayerDev* layers, const std::vector<LayerDev>& host_layers,
-                         double* partial, double* out, hipStream_t st) {
-  const size_t nblk = sqnorm_partials(host_layers);
+hipError_t launch_sqnorm_table(const LayerDev* layers, int n_layers, size_t nblk, double* partial,
+                               double* out, hipStream_t st) {
   hipLaunchKernelGGL(sqnorm_partial_kernel, dim3(unsigned(nblk)), dim3(kRedThreads), 0, st, layers,
-                     int(host_layers.size()), partial);
+                     n_layers, partial);
   hipLaunchKernelGGL(sum_f64_kernel, dim3(1), dim3(1024), 0, st, partial, (long long)nblk, out);
   return hipGetLastError();
+}
+
+hipError_t launch_sqnorm(const LayerDev* layers, const std::vector<LayerDev>& host_layers,
+                         double* partial, double* out, hipStream_t st) {
+  return launch_sqnorm_table(layers, int(host_layers.size()), sqnorm_partials(host_layers), partial,
+                             out, st);
 }
 
 hipError_t launch_finalize_stats(const float* partials, int n_layers, int B, int n_pairs,
