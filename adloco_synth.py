@@ -270,6 +270,51 @@ def device_grad_stats_inputs(config: int, device, linears=None, B=None, T=None, 
     return out
 
 
+def round_rho_schedule(eta: float, b_schedule, stat_targets):
+    """Correlation rho of each outer step's batches such that, for samples x_i = rho x0 + sqrt(1 -
+    rho^2) eps_i in both operands of every block (x0 shared by the whole batch), the norm-test
+    statistic of a batch of b samples lands near the target: with r = rho^4 the share of the
+    squared gradient that the samples have in common, stat ~ (1 - r) / (eta^2 (r + (1 - r) / b)).
+    Input recipe only: nothing here is computed from gradients."""
+    out = []
+    for b, s in zip(b_schedule, stat_targets):
+        e = eta * eta * s
+        r = (1.0 - e / b) / (1.0 + e * (1.0 - 1.0 / b))
+        out.append(float(max(r, 0.0) ** 0.25))
+    return out
+
+
+def device_round_micro_batches(config: int, device, rhos, linears=None, B=None, T=None, dtype=None):
+    """Micro-batches of one trainer's accumulated batches, on the device: set s holds, for every
+    linear, a [B, T, d_in] and delta [B, T, d_out] with samples x_i = rhos[s] x0 + sqrt(1 -
+    rhos[s]^2) eps_i.  x0 (one [1, T, d] tensor per operand and linear, seed = tensor_seed) is common
+    to all sets, so that micro-batches accumulated into one batch share their mean; eps has seed
+    tensor_seed + 100000 (set + 1).  Returns sets[s] = list of dicts {name, d_in, d_out, a, delta}."""
+    import torch
+    c = CONFIGS[config]
+    B = c["B"] if B is None else B
+    T = c["T"] if T is None else T
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype or c["dtype"]]
+    shapes = linear_shapes(config)
+    idx = list(range(len(shapes))) if linears is None else list(linears)
+    sets = [[] for _ in rhos]
+    for li in idx:
+        nm, di, do = shapes[li]
+        per_set = [dict(name=nm, d_in=di, d_out=do) for _ in rhos]
+        for which, (key, d, std) in enumerate((("a", di, c["std_a"]), ("delta", do, c["std_delta"]))):
+            seed = tensor_seed(config, li, which)
+            x0 = device_normal(seed, (1, T, d), std, torch.float32, device)
+            for s, rho in enumerate(rhos):
+                eps = device_normal(seed + 100000 * (s + 1), (B, T, d), std, torch.float32, device)
+                eps.mul_(float(np.sqrt(1.0 - rho * rho))).add_(x0, alpha=float(rho))
+                per_set[s][key] = eps.to(tdt).contiguous()
+                del eps
+            del x0
+        for s in range(len(rhos)):
+            sets[s].append(per_set[s])
+    return sets
+
+
 def device_outer_inputs(config: int, device, N=None, M=None):
     import torch
     o = CONFIGS[config]["outer"]

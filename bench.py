@@ -1,19 +1,32 @@
 #!/usr/bin/env python3
-"""Benchmark of the AdLoCo hot path on one MI355X.
+"""Benchmark of the AdLoCo hot path on one MI355X.  Prints ONE JSON line.
 
-One step = one pass of the whole path over one batch of synthetic input:
-  adloco_grad_stats   GPT-2-small-shaped workload: 12 blocks x {768->2304, 768->768, 768->3072,
-                      3072->768}, B = 32, T = 512, bf16 a ~ N(0,1), delta ~ N(0,1e-2):
-                      Gram kernel (per-sample norms), gradient-sum GEMM, reductions
-  adloco_norm_test    ||sum_i g_i||^2, norm test, batch rule, SwitchMode (eta = 0.3)
+Timed region (the "steps"): the full AdLoCo round of the largest single-GPU workload,
+  24 blocks x {1024->3072, 1024->1024, 1024->4096, 4096->1024} (350M-parameter model), T = 1024, bf16,
+  micro-batch cap b_max = 32, ceiling b_cap = 256, eta = 0.3, M = 8 instances x 350M fp32 parameters.
+One step = one pass of the whole path over one (accumulated) batch; the batch schedule 32, 64, 128, 256
+samples = 1, 2, 4, 8 micro-batches of 32 repeats every four steps:
+  adloco_grad_stats   per micro-batch, ADLOCO_ACCUMULATE from the second on; the gradient sum is the
+                      caller's (a training framework's backward pass already holds it), so the
+                      per-sample norms come from the Gram contractions
+  adloco_norm_test    ||sum_i g_i||^2, norm test, batch rule, SwitchMode
   adloco_check_merge  host
-  adloco_outer_step   M = 4 instances x 124M fp32 parameters, Nesterov (lr 0.7, mu 0.9), in place
-  adloco_merge        S = 4 instances, weights = requested batches, in place
-Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+  adloco_outer_step   pseudo-gradient average over the 8 instances, Nesterov (lr 0.7, mu 0.9), in place
+  adloco_merge        all 8 instances, weights = the requested batches the schedule produced
+`value` = tokens of the timed steps / time of their statistics part (grad_stats + norm_test, HIP events
+on the stream); the outer step and merge handle no tokens and are reported in GB/s.  Inputs are resident
+in HBM before the timed region; every micro-batch has its own tensors, so the pointers change from call
+to call as they do in training.
+
+Further legs (each timed apart, all in the same JSON line): the same round with the gradient sum formed
+by the library; the Llama-1B-shaped statistics on all 22 blocks (B = 64, T = 1024); the GPT-2-small
+statistics + 124M x 4 outer step and merge, also with rotating buffer sets; the LDS-fed MFMA ceiling;
+bias / gain / embedding blocks, inner products, fused AdamW step; the CPU oracle on a bounded slice.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -23,165 +36,362 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-DT = None                    # element type code / torch dtype of a and delta, set from --dtype
-TDT = None
-PEAK_BF16_MFMA = 2.5e15     # dense bf16 MFMA flop/s, MI355X
+PEAK_BF16_MFMA = 2.5e15     # dense bf16 / fp16 MFMA flop/s, MI355X
 PEAK_HBM = 8.0e12           # bytes/s
-TILE = 128                  # T-tile edge of the Gram kernel (executed-flop accounting)
+METRIC = "grad-stats tokens/s (MFMA util) + outer-step GB/s (frac HBM peak), 1 GPU"
+B_SCHEDULE = (32, 64, 128, 256)        # effective batch of the four outer steps of the schedule
+STAT_TARGETS = (63.5, 127.5, 255.0, 400.0)     # where the input recipe puts the norm-test statistic
 
 
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=20)
-    p.add_argument("--warmup", type=int, default=3)
-    p.add_argument("--gram-variant", type=int, default=None)
-    p.add_argument("--wgrad-variant", type=int, default=None)
-    p.add_argument("--stream-blocks-per-cu", type=int, default=None)
-    p.add_argument("--stats-variant", default="tile", choices=["tile", "gram"],
-                   help="route of the statistics in the timed step: per-sample gradient tiles fused "
-                        "with the gradient sum (default), or Gram kernel + gradient-sum GEMM")
+    p.add_argument("--steps", type=int, default=8)
+    p.add_argument("--warmup", type=int, default=4)
     p.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
-                   help="storage type of activations and output gradients (both run the same "
-                        "kernels; the metric is quoted on bf16)")
-    p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--cpu-blocks", type=int, default=12,
-                   help="transformer blocks (of 12) the CPU oracle is timed on")
-    p.add_argument("--grad-provided", action="store_true",
-                   help="caller supplies the gradient sum (skips the gradient-sum GEMM)")
-    p.add_argument("--calibrate-copy", action="store_true",
-                   help="also run three plain 1 GiB device copies (untimed) so that a counter "
-                        "profile of this command holds a kernel of known traffic")
-    p.add_argument("--config", type=int, default=2, choices=[2, 4, 5],
-                   help="2 (default, the benchmark workload): GPT-2-small statistics + 124M x 4 outer "
-                        "step; 4: transformer blocks of the Llama-1B-shaped workload (statistics only); "
-                        "5: blocks of the 350M round + its M = 8 outer step and merge")
+                   help="storage type of activations and output gradients (same kernels; the metric is "
+                        "quoted on bf16)")
     p.add_argument("--blocks", type=int, default=None,
-                   help="transformer blocks of --config 4 / 5 to hold in memory (default 2)")
-    p.add_argument("--no-next-rows", action="store_true",
-                   help="skip the extra leg that times the bias / gain / embedding blocks")
-    p.add_argument("--only", default="all", choices=["all", "stats", "outer"],
-                   help="time only one half (diagnostics; the JSON line says so)")
+                   help="transformer blocks of the round to hold (default: all 24)")
+    p.add_argument("--llama-blocks", type=int, default=None,
+                   help="transformer blocks of the Llama-1B-shaped leg (default: all 22)")
+    p.add_argument("--legs", default="all",
+                   help="comma-separated subset of: self,llama,gpt2,probe,next,cpu (default all); "
+                        "'none' runs the timed region only")
+    p.add_argument("--gram-variant", type=int, default=None)
+    p.add_argument("--stream-blocks-per-cu", type=int, default=None)
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run three plain 1 GiB device copies (untimed) so that a counter profile of "
+                        "this command holds a kernel of known traffic")
     return p.parse_args()
 
 
-def gram_flops(shapes, B, T):
-    """(symmetric-half algorithmic, full, executed by the tile-pair kernel) flops per launch."""
+# ------------------------------------------------------------------------------------------------
+# work accounting
+# ------------------------------------------------------------------------------------------------
+
+def gram_flops(shapes, B, T, kernel="dual"):
+    """(algorithmic = symmetric half, full, executed) flops of the Gram contractions of B samples.
+    Executed, tile-pair kernel: 128 x 128 tile pairs (p <= q); a pair on the diagonal computes 10 of
+    its 16 blocks of 32 x 32.  Region kernel: 256 x 256 regions, 36 of 64 blocks on the diagonal."""
     dsum = sum(di + do for _, di, do in shapes)
-    nt = -(-T // TILE)
-    # 128 x 128 tile pairs: nt(nt-1)/2 off the diagonal, nt on it, where one of the four 64 x 64
-    # wave tiles mirrors another and is not computed and the two on the diagonal leave out one of
-    # their four 32 x 32 blocks: (0.75 + 0.75 + 1 + 0) / 4 of a pair
-    pairs = nt * (nt - 1) / 2 + 0.625 * nt
-    sym = B * T * (T + 1) * dsum
-    full = 2 * B * T * T * dsum
-    executed = 0
-    for _, di, do in shapes:
-        kp = -(-di // 64) * 64 + -(-do // 64) * 64      # k-chunks of 64 are zero padded
-        executed += B * pairs * 2 * TILE * TILE * kp
-    return sym, full, int(executed)
+    if kernel == "dual":
+        nt = -(-T // 128)
+        blocks = 16 * nt * (nt - 1) / 2 + 10 * nt
+    else:
+        ns = T // 256
+        blocks = 64 * ns * (ns - 1) / 2 + 36 * ns
+    return B * T * (T + 1) * dsum, 2 * B * T * T * dsum, B * blocks * 2 * 32 * 32 * dsum
 
 
-def cpu_baseline(synth, orc, shapes, B, T, N, M, blocks):
-    """The oracle, as it stands, on a bounded sample of the same workload: `blocks` of the 12
-    transformer blocks (all samples), and the outer step + merge on N/4 parameters."""
+def source_hash():
+    """sha256 over the kernel sources: a counter summary under profiles/ is only quoted for the build
+    it was taken from."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2508_18182_amd", "csrc")
+    for fn in sorted(os.listdir(d)):
+        with open(os.path.join(d, fn), "rb") as f:
+            h.update(fn.encode())
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(name):
+    """HBM bytes per launch of kernel `name` from the rocprofv3 counter summary committed under
+    profiles/ -- only if that summary carries the hash of the kernel sources of this build."""
+    path = os.path.join(ROOT, "profiles", "bench_round350m_hbm_traffic.md")
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    n_blocks = len(shapes) // 4
-    t_stats = 0.0
-    for b in range(blocks):
-        layers = synth.grad_stats_inputs(2, linears=range(4 * b, 4 * b + 4), B=B, T=T)
+        txt = open(path).read()
+    except OSError:
+        return None, "no counter summary under profiles/"
+    stamp = [ln.split(":", 1)[1].strip() for ln in txt.splitlines() if ln.startswith("kernel_source_sha256:")]
+    if not stamp or stamp[0] != source_hash():
+        return None, "the counter summary under profiles/ belongs to other kernel sources: not quoted"
+    for ln in txt.splitlines():
+        parts = [p.strip() for p in ln.split("|")]
+        if len(parts) >= 5 and parts[1] == name:
+            return float(parts[2]) + float(parts[3]), "profiles/bench_round350m_hbm_traffic.md (same kernel sources)"
+    return None, "kernel not in the counter summary"
+
+
+def roof(bound, work, ms, peak, unit, scale, **extra):
+    if not ms:
+        return None
+    a = work / (ms * 1e-3) / scale
+    return dict(bound=bound, achieved=a, peak=peak / scale, unit=unit, frac=a / (peak / scale),
+                avg_kernel_ms=ms, **extra)
+
+
+class Timer:
+    """HIP events on torch's current stream, which is the stream the library launches on."""
+    def __init__(self, torch):
+        self.torch, self.pairs = torch, []
+
+    def span(self):
+        e0 = self.torch.cuda.Event(enable_timing=True)
+        e1 = self.torch.cuda.Event(enable_timing=True)
+        self.pairs.append((e0, e1))
+        return e0, e1
+
+    def total_ms(self):
+        self.torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in self.pairs)
+
+
+def drop_profile(ctx, names):
+    for k in names:
+        ctx.profile_read(k)
+
+
+def read_profile(ctx, names):
+    out = {}
+    for k in names:
+        ms, n = ctx.profile_read(k)
+        out[k] = dict(avg_ms=(ms / n) if n else None, launches=n)
+    return out
+
+
+PROF = ("tile_stats", "gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge")
+
+
+# ------------------------------------------------------------------------------------------------
+# the round (timed region and its self-contained twin)
+# ------------------------------------------------------------------------------------------------
+
+def build_round(torch, synth, A, ctx, args, dev, DT):
+    cfg = synth.CONFIGS[5]
+    T, eta, b_max, b_cap = cfg["T"], cfg["eta"], cfg["b_max"], cfg["b_cap"]
+    n_blocks = args.blocks or cfg["n_blocks"]
+    linears = range(4 * n_blocks)
+    shapes = synth.linear_shapes(5)[:4 * n_blocks]
+    per_set_bytes = sum(2 * b_max * T * (di + do) for _, di, do in shapes)
+    free, _ = torch.cuda.mem_get_info()
+    ocfg = cfg["outer"]
+    N, M = ocfg["N"], ocfg["M"]
+    fixed = (M + 2) * 4 * N + 5 * 4 * sum(di * do for _, di, do in shapes) + (6 << 30)
+    n_sets = 8 if free - fixed > 8 * per_set_bytes else 4
+    rhos_sched = synth.round_rho_schedule(eta, B_SCHEDULE, STAT_TARGETS)
+    # which sets each outer step of the schedule accumulates, and the correlation they are drawn with:
+    # step 0 -> set 0, step 1 -> sets 1, 2, step 2 -> sets 3..6, step 3 -> all eight (set 7 with its own)
+    if n_sets == 8:
+        plan = [[0], [1, 2], [3, 4, 5, 6], [7, 0, 1, 2, 3, 4, 5, 6]]
+        rho_of_set = [rhos_sched[0], rhos_sched[1], rhos_sched[1], rhos_sched[2], rhos_sched[2],
+                      rhos_sched[2], rhos_sched[2], rhos_sched[3]]
+    else:   # not enough free memory for eight sets: four, each used twice in the largest batch
+        plan = [[0], [1, 2], [3, 0, 1, 2], [3, 0, 1, 2, 3, 0, 1, 2]]
+        rho_of_set = [rhos_sched[0], rhos_sched[1], rhos_sched[1], rhos_sched[2]]
+    sets = synth.device_round_micro_batches(5, dev, rho_of_set, linears=linears, dtype=args.dtype)
+    # one set of gradient-sum buffers per outer step of the schedule (the "caller's" weight gradients)
+    grads = [[torch.zeros(do, di, dtype=torch.float32, device=dev) for _, di, do in shapes] for _ in plan]
+    theta, insts, mom = synth.device_outer_inputs(5, dev)
+    st = dict(cfg=cfg, T=T, eta=eta, b_max=b_max, b_cap=b_cap, shapes=shapes, n_blocks=n_blocks, plan=plan,
+              sets=sets, grads=grads, theta=theta, insts=insts, mom=mom, N=N, M=M, ocfg=ocfg, n_sets=n_sets,
+              rho_of_set=rho_of_set, per_set_bytes=per_set_bytes,
+              per_sample=torch.zeros(b_max, dtype=torch.float32, device=dev),
+              acc=torch.zeros(2, dtype=torch.float64, device=dev))
+
+    def descs(provided):
+        out = {}
+        for r, ids in enumerate(plan):
+            for s in set(ids):
+                layers = [dict(a=l["a"], delta=l["delta"], grad_sum=g, provided=provided)
+                          for l, g in zip(sets[s], grads[r])]
+                out[(r, s)] = A.make_layer_descs(layers, b_max, T, DT)
+        return out
+    st["descs_provided"], st["descs_own"] = descs(True), descs(False)
+    return st
+
+
+def round_stats(A, ctx, st, r, DT, provided):
+    """The statistics of outer step r of the schedule: its micro-batches, then the norm test."""
+    d = st["descs_provided"] if provided else st["descs_own"]
+    for j, s in enumerate(st["plan"][r]):
+        A.adloco_grad_stats(ctx, None, st["b_max"], st["T"], DT, st["per_sample"], None, st["acc"],
+                            A.ADLOCO_ACCUMULATE if j else 0, descs=d[(r, s)])
+    b = st["b_max"] * len(st["plan"][r])
+    return A.adloco_norm_test(ctx, None, st["acc"], st["eta"], b, st["b_max"], 2, st["b_cap"],
+                              descs=d[(r, st["plan"][r][0])])
+
+
+# ------------------------------------------------------------------------------------------------
+# legs
+# ------------------------------------------------------------------------------------------------
+
+def llama_leg(torch, synth, A, ctx, args, dev, DT):
+    """Llama-1B-shaped statistics, all blocks resident: 7 linears per block, q / k / v and gate / up read
+    one activation tensor each, B = 64, T = 1024."""
+    cfg = synth.CONFIGS[4]
+    B, T, eta = cfg["B"], cfg["T"], cfg["eta"]
+    n_blocks = args.llama_blocks or cfg["n_blocks"]
+    linears = range(7 * n_blocks)
+    shapes = synth.linear_shapes(4)[:7 * n_blocks]
+    layers = synth.device_grad_stats_inputs(4, dev, linears=linears, share=True, dtype=args.dtype)
+    for l in layers:
+        l["grad_sum"] = torch.zeros(l["d_out"], l["d_in"], dtype=torch.float32, device=dev)
+    ps = torch.zeros(B, dtype=torch.float32, device=dev)
+    acc = torch.zeros(2, dtype=torch.float64, device=dev)
+    own = A.make_layer_descs([dict(l, provided=False) for l in layers], B, T, DT)
+    prov = A.make_layer_descs([dict(l, provided=True) for l in layers], B, T, DT)
+    out = {}
+    for name, d, reps in (("self_contained", own, 3), ("gradient_supplied", prov, 5)):
+        def run():
+            A.adloco_grad_stats(ctx, None, B, T, DT, ps, None, acc, 0, descs=d)
+            return A.adloco_norm_test(ctx, None, acc, eta, B, 32, 2, 0, descs=d)
+        run()
+        torch.cuda.synchronize()
+        drop_profile(ctx, PROF)
         t0 = time.perf_counter()
-        st = orc.grad_stats([(l["a"], l["delta"]) for l in layers], two_pass=False)
-        orc.norm_test(st["S1"], st["S2"], B, 0.3, B, 32)
-        t_stats += time.perf_counter() - t0
-        del layers, st
-    n_s = N // 4
-    theta, insts, mom = synth.outer_inputs(3, N=n_s, M=M)
-    t0 = time.perf_counter()
-    orc.outer_step(theta, insts, mom, 0.7, 0.9, True)
-    orc.merge(insts, [32.0 + k for k in range(M)])
-    t_outer = time.perf_counter() - t0
-    t_est = t_stats * n_blocks / blocks + 4 * t_outer
-    return dict(value=B * T / t_est, unit="tokens/s", cores=int(cores), kind="oracle",
-                sample=(f"{blocks} of {n_blocks} blocks ({4 * blocks} linears, all {B} samples, "
-                        f"T={T}) took {t_stats:.2f} s; outer step + merge on N/4 = {n_s} params "
-                        f"took {t_outer:.2f} s; step time scaled linearly to {n_blocks} blocks "
-                        f"and N params: {t_est:.1f} s"),
-                grad_stats_tokens_per_s=B * T / (t_stats * n_blocks / blocks),
-                outer_merge_GBps=((4 * (M + 2) + 8 + 4 * (M + 1)) * n_s) / t_outer / 1e9)
+        for _ in range(reps):
+            res = run()
+        torch.cuda.synchronize()
+        out[name] = dict(ms=(time.perf_counter() - t0) / reps * 1e3, kernels=read_profile(ctx, PROF),
+                         norm_test={k: res[k] for k in ("stat", "b_req", "test_passed", "accumulate")})
+    sym, full, executed = gram_flops(shapes, B, T)
+    wflops = sum(2.0 * B * T * di * do for _, di, do in shapes)
+    g_ms = out["gradient_supplied"]["kernels"]["gram"]["avg_ms"]
+    t_ms = out["self_contained"]["kernels"]["tile_stats"]["avg_ms"]
+    return dict(workload=f"Llama-1B-shaped grad stats, all {n_blocks} blocks = {len(shapes)} linears "
+                         f"(q/k/v and gate/up share their input), B={B}, T={T}, {args.dtype}",
+                tokens=B * T,
+                gradient_supplied=dict(ms=out["gradient_supplied"]["ms"], tokens_per_s=B * T / (out["gradient_supplied"]["ms"] * 1e-3),
+                                       norm_test=out["gradient_supplied"]["norm_test"]),
+                self_contained=dict(ms=out["self_contained"]["ms"], tokens_per_s=B * T / (out["self_contained"]["ms"] * 1e-3),
+                                    norm_test=out["self_contained"]["norm_test"]),
+                gram=roof("mfma", sym, g_ms, PEAK_BF16_MFMA, "TFLOP/s", 1e12, kernel="gram_bf16_dual_kernel",
+                          flops_algorithmic_symmetric=sym, flops_full=full, flops_executed=executed,
+                          frac_executed=(executed / (g_ms * 1e-3) / PEAK_BF16_MFMA) if g_ms else None),
+                tile_stats=roof("mfma", wflops, t_ms, PEAK_BF16_MFMA, "TFLOP/s", 1e12,
+                                kernel="ip_tile_kernel<1, true> (norms and gradient sum in one pass)",
+                                flops_algorithmic=wflops))
 
 
-def vector_table_leg(torch, synth, A, ctx, layers, B, T, dev, steps):
-    """Extra leg (not part of `value`): per-sample norms of the GPT-2-small blocks that are not
-    linear weights -- the four linear biases of each block (their delta is the linear layer's),
-    two LayerNorm gains and biases per block plus the final one, token and position embeddings.
-    Returns the group's kernel time and its algorithmic HBM bytes (every delta / x element once
-    per block that uses it, 2 bytes each; ids 4 bytes)."""
+def gpt2_leg(torch, synth, A, ctx, args, dev, DT, TDT):
+    """GPT-2-small statistics (48 linears, B = 32, T = 512) + 124M x 4 outer step and merge.  The
+    statistics are timed with one fixed set of buffers and with three sets taken in turn."""
+    cfg = synth.CONFIGS[2]
+    B, T, eta = cfg["B"], cfg["T"], cfg["eta"]
+    shapes = synth.linear_shapes(2)
+    base = synth.device_grad_stats_inputs(2, dev, dtype=args.dtype)
+    sets = [base]
+    for k in (1, 2):     # two more sets of the same shapes (other values, other addresses)
+        sets.append([dict(l, a=torch.roll(l["a"], k, 0).contiguous(), delta=torch.roll(l["delta"], k, 0).contiguous())
+                     for l in base])
+    for s in sets:
+        for l in s:
+            l["grad_sum"] = torch.zeros(l["d_out"], l["d_in"], dtype=torch.float32, device=dev)
+    ps = torch.zeros(B, dtype=torch.float32, device=dev)
+    acc = torch.zeros(2, dtype=torch.float64, device=dev)
+    d_own = [A.make_layer_descs([dict(l, provided=False) for l in s], B, T, DT) for s in sets]
+    d_prov = [A.make_layer_descs([dict(l, provided=True) for l in s], B, T, DT) for s in sets]
+    reps = 12
+
+    def timed(dl):
+        def run(i):
+            d = dl[i % len(dl)]
+            A.adloco_grad_stats(ctx, None, B, T, DT, ps, None, acc, 0, descs=d)
+            return A.adloco_norm_test(ctx, None, acc, eta, B, 32, 2, 256, descs=d)
+        for i in range(3):
+            run(i)
+        torch.cuda.synchronize()
+        drop_profile(ctx, PROF)
+        b0 = ctx.table_builds()
+        t0 = time.perf_counter()
+        for i in range(reps):
+            run(i)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        rebuilt[0] += ctx.table_builds() - b0
+        return ms, read_profile(ctx, PROF)
+
+    rebuilt = [0]
+    own_fixed_ms, own_k = timed(d_own[:1])
+    own_rot_ms, _ = timed(d_own)
+    prov_fixed_ms, prov_k = timed(d_prov[:1])
+    prov_rot_ms, _ = timed(d_prov)
+    sym, full, executed = gram_flops(shapes, B, T)
+    wflops = sum(2.0 * B * T * di * do for _, di, do in shapes)
+    # outer step + merge, M = 4 x 124M
+    ocfg = synth.CONFIGS[3]["outer"]
+    N, M = ocfg["N"], ocfg["M"]
+    theta, insts, mom = synth.device_outer_inputs(3, dev)
+    for _ in range(3):
+        A.adloco_outer_step(ctx, theta, insts, mom, ocfg["lr"], ocfg["mu"], True)
+        A.adloco_merge(ctx, insts, [32.0 + k for k in range(M)])
+    torch.cuda.synchronize()
+    drop_profile(ctx, PROF)
+    for _ in range(20):
+        A.adloco_outer_step(ctx, theta, insts, mom, ocfg["lr"], ocfg["mu"], True)
+        A.adloco_merge(ctx, insts, [32.0 + k for k in range(M)])
+    torch.cuda.synchronize()
+    k = read_profile(ctx, PROF)
+    g_ms, t_ms = prov_k["gram"]["avg_ms"], own_k["tile_stats"]["avg_ms"]
+    out = dict(workload=f"GPT-2-small-shaped grad stats (48 linears, B={B}, T={T}, {args.dtype}) + outer step "
+                        f"and merge (M={M} x {N // 10**6}M fp32)",
+               tokens=B * T,
+               gradient_supplied=dict(ms=prov_fixed_ms, tokens_per_s=B * T / (prov_fixed_ms * 1e-3),
+                                      ms_three_buffer_sets_in_turn=prov_rot_ms),
+               self_contained=dict(ms=own_fixed_ms, tokens_per_s=B * T / (own_fixed_ms * 1e-3),
+                                   ms_three_buffer_sets_in_turn=own_rot_ms),
+               rotation_overhead=dict(self_contained=own_rot_ms / own_fixed_ms - 1.0,
+                                      gradient_supplied=prov_rot_ms / prov_fixed_ms - 1.0,
+                                      tables_rebuilt_while_timing=rebuilt[0]),
+               gram=roof("mfma", sym, g_ms, PEAK_BF16_MFMA, "TFLOP/s", 1e12, kernel="gram_bf16_dual_kernel",
+                         flops_algorithmic_symmetric=sym, flops_full=full, flops_executed=executed,
+                         frac_executed=(executed / (g_ms * 1e-3) / PEAK_BF16_MFMA) if g_ms else None),
+               tile_stats=roof("mfma", wflops, t_ms, PEAK_BF16_MFMA, "TFLOP/s", 1e12,
+                               kernel="ip_tile_kernel<1, true>", flops_algorithmic=wflops),
+               outer_step=roof("hbm", (4 * (M + 2) + 8) * N, k["outer_step"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+                               kernel="outer_step_vec_kernel", bytes_algorithmic=(4 * (M + 2) + 8) * N),
+               merge=roof("hbm", 4 * (M + 1) * N, k["merge"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+                          kernel="merge_vec_kernel", bytes_algorithmic=4 * (M + 1) * N))
+    del theta, insts, mom
+    return out, sets[0], (B, T)
+
+
+def vector_table_leg(torch, synth, A, ctx, layers, B, T, dev, DT, TDT, steps):
+    """Per-sample norms of the GPT-2-small blocks that are not linear weights: four linear biases per
+    block (their delta is the linear layer's), two LayerNorm gains and biases per block plus the final
+    one, token and position embeddings.  Algorithmic HBM bytes: every distinct delta / x tensor once,
+    2 bytes per element; ids 4 bytes."""
     d, V = 768, 50257
     blocks, nbytes = [], 0
     for l in layers:                                   # biases
-        blocks.append(dict(kind="vector", x=None, delta=l["delta"],
-                           grad_sum=torch.zeros(l["d_out"], device=dev)))
+        blocks.append(dict(kind="vector", x=None, delta=l["delta"], grad_sum=torch.zeros(l["d_out"], device=dev)))
         nbytes += 2 * B * T * l["d_out"]
-    for j in range(25):                                # LayerNorm gains and biases
+    for j in range(25):                                # LayerNorm gains and biases: x and delta once each
         x = synth.device_normal(7000 + 2 * j, (B, T, d), 1.0, TDT, dev)
         dl = synth.device_normal(7001 + 2 * j, (B, T, d), 1e-2, TDT, dev)
         blocks.append(dict(kind="vector", x=x, delta=dl, grad_sum=torch.zeros(d, device=dev)))
         blocks.append(dict(kind="vector", x=None, delta=dl, grad_sum=torch.zeros(d, device=dev)))
-        nbytes += 3 * 2 * B * T * d
+        nbytes += 2 * 2 * B * T * d
     ids = torch.from_numpy(synth.token_ids(7100, B, T, V)).to(dev)
     pos = torch.arange(T, dtype=torch.int32, device=dev).repeat(B, 1).contiguous()
     de = synth.device_normal(7101, (B, T, d), 1e-2, TDT, dev)
     blocks.append(dict(kind="embed", ids=ids, vocab=V, delta=de, grad_sum=None))
     blocks.append(dict(kind="embed", ids=pos, vocab=T, delta=de, grad_sum=None))
-    nbytes += 2 * (2 * B * T * d + 4 * B * T)
+    nbytes += 2 * B * T * d + 2 * 4 * B * T
     descs = A.make_layer_descs(blocks, B, T, DT)
     ps = torch.zeros(B, dtype=torch.float32, device=dev)
     acc = torch.zeros(2, dtype=torch.float64, device=dev)
     for _ in range(2):
-        A.adloco_grad_stats(ctx, blocks, B, T, DT, ps, None, acc, 0, descs=descs)
+        A.adloco_grad_stats(ctx, None, B, T, DT, ps, None, acc, 0, descs=descs)
     torch.cuda.synchronize()
     ctx.profile_read("vector_table")
     for _ in range(steps):
-        A.adloco_grad_stats(ctx, blocks, B, T, DT, ps, None, acc, 0, descs=descs)
+        A.adloco_grad_stats(ctx, None, B, T, DT, ps, None, acc, 0, descs=descs)
     torch.cuda.synchronize()
     ms, n = ctx.profile_read("vector_table")
     ms = ms / n if n else None
-    # the whole parameter list of the model in one call (linear weights + these blocks): the
-    # vector / table kernels run on a second stream next to the tile-statistics kernel
-    both = list(layers) + blocks
-    for l in layers:
-        l["provided"] = False
-    d_both = A.make_layer_descs(both, B, T, DT)
-    combined = {}
-    for overlap in (1, 0):
-        ctx.set_tuning("overlap_aux", overlap)
-        for _ in range(2):
-            A.adloco_grad_stats(ctx, both, B, T, DT, ps, None, acc, 0, descs=d_both)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            A.adloco_grad_stats(ctx, both, B, T, DT, ps, None, acc, 0, descs=d_both)
-        torch.cuda.synchronize()
-        combined["overlapped" if overlap else "serial"] = (time.perf_counter() - t0) / steps * 1e3
-    ctx.set_tuning("overlap_aux", 1)
-    for k in ("vector_table", "tile_stats", "gram", "wgrad", "finalize", "sqnorm"):
-        ctx.profile_read(k)
+    drop_profile(ctx, PROF)
     return dict(bound="hbm", kernel="vector_rowsum_kernel + embed_rows_kernel (+ small reductions)",
-                all_blocks_of_the_model_ms=combined,
                 blocks=len(blocks), avg_kernel_ms=ms, bytes_algorithmic=nbytes,
                 achieved=(nbytes / (ms * 1e-3) / 1e9) if ms else None, peak=PEAK_HBM / 1e9, unit="GB/s",
-                frac=(nbytes / (ms * 1e-3) / PEAK_HBM) if ms else None, traffic=None)
+                frac=(nbytes / (ms * 1e-3) / PEAK_HBM) if ms else None)
 
 
-def inner_products_leg(torch, A, ctx, layers, B, T, dev, steps):
-    """Extra leg (not part of `value`): c_i = <g_i, G> of every sample against the gradient sums
-    the timed step left in place (Section 3.3.2's tests).  Each 256 x 256 tile of each per-sample
-    gradient is one T-deep bf16 contraction: 2 * d_in * d_out * T flop per (block, sample)."""
+def inner_products_leg(torch, A, ctx, layers, B, T, dev, DT, steps):
+    """c_i = <g_i, G> of every sample against the gradient sums in place (Section 3.3.2's tests): per
+    (block, sample) one T-deep bf16 contraction of 2 d_in d_out T flop."""
     flops = sum(2.0 * l["d_in"] * l["d_out"] * T * B for l in layers)
     descs = A.make_layer_descs(layers, B, T, DT)
     c = torch.zeros(B, dtype=torch.float32, device=dev)
@@ -198,12 +408,12 @@ def inner_products_leg(torch, A, ctx, layers, B, T, dev, steps):
     return dict(bound="mfma", kernel="ip_tile_kernel (+ small reductions)", blocks=len(layers),
                 avg_kernel_ms=ms, flops_algorithmic=flops,
                 achieved=(flops / (ms * 1e-3) / 1e12) if ms else None, peak=PEAK_BF16_MFMA / 1e12,
-                unit="TFLOP/s", frac=(flops / (ms * 1e-3) / PEAK_BF16_MFMA) if ms else None, traffic=None)
+                unit="TFLOP/s", frac=(flops / (ms * 1e-3) / PEAK_BF16_MFMA) if ms else None)
 
 
 def inner_step_leg(torch, synth, A, ctx, N, dev, steps):
-    """Extra leg (not part of `value`): the workers' fused AdamW step on N parameters; reads
-    theta, m, v, grad and writes theta, m, v: 28 bytes per parameter."""
+    """The workers' fused AdamW step on N parameters: reads theta, m, v, grad and writes theta, m, v,
+    28 bytes per parameter."""
     th = synth.device_normal(7200, (N,), 0.02, torch.float32, dev)
     m = synth.device_normal(7201, (N,), 1e-3, torch.float32, dev)
     v = synth.device_normal(7202, (N,), 1e-3, torch.float32, dev).square_()
@@ -217,36 +427,51 @@ def inner_step_leg(torch, synth, A, ctx, N, dev, steps):
     torch.cuda.synchronize()
     ms, n = ctx.profile_read("inner_step")
     ms = ms / n if n else None
-    nbytes = 28 * N
-    return dict(bound="hbm", kernel="inner_step_vec_kernel", N=N, avg_kernel_ms=ms,
-                bytes_algorithmic=nbytes, achieved=(nbytes / (ms * 1e-3) / 1e9) if ms else None,
-                peak=PEAK_HBM / 1e9, unit="GB/s", frac=(nbytes / (ms * 1e-3) / PEAK_HBM) if ms else None,
-                traffic=None)
+    return roof("hbm", 28 * N, ms, PEAK_HBM, "GB/s", 1e9, kernel="inner_step_vec_kernel", N=N,
+                bytes_algorithmic=28 * N)
 
 
-def measured_traffic():
-    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE runs of this command, scaled as stated there); {} when the file is absent."""
-    path = os.path.join(ROOT, "profiles", "bench_gpt2small_hbm_traffic.md")
-    out = {}
-    try:
-        with open(path) as f:
-            for ln in f:
-                parts = [p.strip() for p in ln.split("|")]
-                if len(parts) >= 5 and parts[1] in ("tile_stats", "gram", "wgrad", "outer_step", "merge",
-                                                     "sqnorm", "vector_table", "inner_step",
-                                                     "inner_products"):
-                    out[parts[1]] = float(parts[2]) + float(parts[3])
-    except OSError:
-        pass
-    return out
+def cpu_baseline(synth, orc, cfg, n_blocks, N, M):
+    """The oracle as it stands on a bounded slice of the timed workload: the four linears of 4 of the
+    24 transformer blocks on one whole micro-batch of 32 samples (per-sample norms, gradient sum, norm
+    test), and the outer step + merge on N / 8 parameters."""
+    import numpy as np
+    cores = len(os.sched_getaffinity(0))
+    T, B, ns, nb = cfg["T"], cfg["b_max"], cfg["b_max"], 4
+    t_stats = 0.0
+    for b in range(nb):
+        layers = synth.grad_stats_inputs(5, linears=range(4 * b, 4 * b + 4), B=ns, T=T)
+        t0 = time.perf_counter()
+        st = orc.grad_stats([(l["a"], l["delta"]) for l in layers], two_pass=False)
+        orc.norm_test(st["S1"], st["S2"], ns, cfg["eta"], ns, B)
+        t_stats += time.perf_counter() - t0
+        del layers, st
+    t_stats /= nb
+    n_s = N // 8
+    theta, insts, mom = synth.outer_inputs(5, N=n_s, M=M)
+    t0 = time.perf_counter()
+    orc.outer_step(theta, insts, mom, 0.7, 0.9, True)
+    orc.merge(insts, [32.0 + k for k in range(M)])
+    t_outer = time.perf_counter() - t0
+    tok_s = ns * T / (t_stats * n_blocks)
+    nbytes = ((4 * (M + 2) + 8) + 4 * (M + 1)) * n_s
+    return dict(value=tok_s, unit="tokens/s", cores=cores, kind="oracle",
+                sample=(f"statistics: the 4 linears of each of {nb} of {n_blocks} blocks on {ns} samples x {T} tokens took "
+                        f"{t_stats:.2f} s per block (explicit per-sample gradients, numpy fp64: the matrix products run on "
+                        f"the BLAS thread pool of up to {cores} cores, squares and sums on one); tokens/s = "
+                        f"{ns * T} tokens / ({t_stats:.2f} s x {n_blocks} blocks), a linear extrapolation to the "
+                        f"whole model; outer step + merge on N/8 = {n_s} parameters, M = {M}: {t_outer:.2f} s, "
+                        f"single-threaded numpy"),
+                outer_merge_GBps=nbytes / t_outer / 1e9)
 
+
+# ------------------------------------------------------------------------------------------------
 
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures the one-GPU hot path only: --gpus must be 1 "
-              "(this build has no multi-GPU path)", file=sys.stderr)
+        print("bench.py measures the one-GPU hot path only: --gpus must be 1 (this build has no multi-GPU "
+              "path)", file=sys.stderr)
         sys.exit(2)
     import torch
 
@@ -256,95 +481,26 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
-    global DT, TDT
     DT, TDT = {"bf16": (A.ADLOCO_BF16, torch.bfloat16), "f16": (A.ADLOCO_F16, torch.float16)}[args.dtype]
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    legs = set("self,llama,gpt2,probe,next,cpu".split(",")) if args.legs == "all" else \
+        (set() if args.legs == "none" else set(args.legs.split(",")))
     ctx = A.Context(0)
     if args.gram_variant is not None:
         ctx.set_tuning("gram_variant", args.gram_variant)
-    if args.wgrad_variant is not None:
-        ctx.set_tuning("wgrad_variant", args.wgrad_variant)
     if args.stream_blocks_per_cu is not None:
         ctx.set_tuning("stream_blocks_per_cu", args.stream_blocks_per_cu)
-    ctx.set_tuning("stats_variant", 1 if args.stats_variant == "tile" else 0)
     ctx.set_tuning("profile", 1)
 
-    cfg = synth.CONFIGS[args.config]
-    B, T, eta = cfg["B"], cfg["T"], cfg["eta"]
-    shapes = synth.linear_shapes(args.config)
-    linears = None
-    if args.config != 2:
-        per_block = len(cfg["block"])
-        linears = range(per_block * (args.blocks or 2))
-        shapes = shapes[:len(linears)]
-        args.no_next_rows = True
-        args.no_cpu_baseline = True
-        if args.config == 4 and args.only == "all":
-            args.only = "stats"
-    ocfg = synth.CONFIGS[5 if args.config == 5 else 3]["outer"]
-    N, M = ocfg["N"], ocfg["M"]
-    workload = {2: "GPT-2-small-shaped grad stats (48 linears, B=32, T=512, " + args.dtype + ") + norm test + "
-                   "outer step and merge (M=4 x 124M fp32)",
-                4: f"Llama-1B-shaped grad stats, {len(shapes)} linears of {len(shapes) // 7} blocks "
-                   f"(B=64, T=1024, bf16, q/k/v and gate/up share their input) + norm test",
-                5: f"350M-round grad stats, {len(shapes)} linears of {len(shapes) // 4} blocks (B=32, "
-                   f"T=1024, bf16) + norm test + outer step and merge (M=8 x 350M fp32)"}[args.config]
-
-    # ---- inputs, resident in HBM
-    layers = synth.device_grad_stats_inputs(args.config, dev, linears=linears, share=args.config == 4,
-                                            dtype=args.dtype)
-    for l in layers:
-        l["grad_sum"] = torch.zeros(l["d_out"], l["d_in"], dtype=torch.float32, device=dev)
-        l["provided"] = bool(args.grad_provided)
-    descs = A.binding.make_layer_descs(layers, B, T, DT)
-    per_sample = torch.zeros(B, dtype=torch.float32, device=dev)
-    per_layer = torch.zeros(len(layers), B, dtype=torch.float32, device=dev)
-    acc = torch.zeros(2, dtype=torch.float64, device=dev)
-    theta, insts, mom = (synth.device_outer_inputs(5 if args.config == 5 else 3, dev)
-                         if args.only in ("all", "outer") else (None, None, None))
-    if args.grad_provided:
-        # the caller's own weight gradient: any values do; computed once, outside the timed region
-        for l in layers:
-            l["provided"] = False
-        d2 = A.binding.make_layer_descs(layers, B, T, DT)
-        A.adloco_grad_stats(ctx, layers, B, T, DT, per_sample, per_layer, acc, 0,
-                            descs=d2)
-        for l in layers:
-            l["provided"] = True
+    st = build_round(torch, synth, A, ctx, args, dev, DT)
+    T, M, N, ocfg, plan = st["T"], st["M"], st["N"], st["ocfg"], st["plan"]
+    # the caller's gradient sums, formed once outside the timed region (by the library itself)
+    reqs = []
+    for r in range(len(plan)):
+        res = round_stats(A, ctx, st, r, DT, provided=False)
+        reqs.append(int(res["b_req"]))
     torch.cuda.synchronize()
-
-    b_req = [B] * M
-    last = {}
-
-    def step():
-        if args.only in ("all", "stats"):
-            A.adloco_grad_stats(ctx, layers, B, T, DT, per_sample, per_layer, acc, 0,
-                                descs=descs)
-            res = A.adloco_norm_test(ctx, None, acc, eta, B, 32, 2, 256, descs=descs)
-            last.update(res)
-            b_req[0] = res["b_req"]
-        if args.only in ("all", "outer"):
-            A.adloco_check_merge(b_req, M)
-            A.adloco_outer_step(ctx, theta, insts, mom, ocfg["lr"], ocfg["mu"], True)
-            A.adloco_merge(ctx, insts, [float(b + k) for k, b in enumerate(b_req)])
-
-    # PyTorch's plain device copy of 1 GiB, for scale (a read + write stream on this machine)
-    copy_GBps = None
-    if args.only in ("all", "outer") and args.config == 2:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(2):
-            dst.copy_(src)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(5):
-            dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        copy_GBps = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        del src, dst
-
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -353,164 +509,152 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
+    b_req = [reqs[k % len(reqs)] + k // len(reqs) for k in range(M)]   # the M instances' requests
+    tm_stats, tm_outer = Timer(torch), Timer(torch)
+    last = {}
+
+    def step(i, timed):
+        r = i % len(plan)
+        if timed:
+            e0, e1 = tm_stats.span()
+            e0.record()
+        res = round_stats(A, ctx, st, r, DT, provided=True)
+        if timed:
+            e1.record()
+        b_req[r] = int(res["b_req"])
+        last[r] = {k: res[k] for k in ("stat", "b_req", "test_passed", "accumulate", "accum_steps")}
+        A.adloco_check_merge(b_req, M)
+        if timed:
+            e0, e1 = tm_outer.span()
+            e0.record()
+        A.adloco_outer_step(ctx, st["theta"], st["insts"], st["mom"], ocfg["lr"], ocfg["mu"], True)
+        A.adloco_merge(ctx, st["insts"], [float(b) for b in b_req])
+        if timed:
+            e1.record()
+
+    for i in range(args.warmup):
+        step(i, False)
     torch.cuda.synchronize()
-    PROF = ("tile_stats", "gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge")
-    for k in PROF:
-        ctx.profile_read(k)                      # drop warm-up events
+    drop_profile(ctx, PROF)
+    builds0 = ctx.table_builds()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        step(i, True)
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    kern = read_profile(ctx, PROF)
+    stats_ms, outer_ms = tm_stats.total_ms(), tm_outer.total_ms()
+    tokens = sum(st["b_max"] * len(plan[i % len(plan)]) * T for i in range(args.steps))
+    rebuilt = ctx.table_builds() - builds0
 
-    kern = {}
-    for k in PROF:
-        ms, n = ctx.profile_read(k)
-        kern[k] = dict(avg_ms=(ms / n) if n else None, launches=n)
-
-    # the other route to the same statistics: Gram kernel + gradient-sum GEMM (what runs when a
-    # block does not qualify for the tile form, or with stats_variant = 0); timed apart, not part
-    # of `value` unless --stats-variant gram made it the step's route
-    alt_ms = None
-    if args.only in ("all", "stats") and args.stats_variant == "tile" and not args.grad_provided:
-        ctx.set_tuning("stats_variant", 0)
-
-        def stats_gram():
-            A.adloco_grad_stats(ctx, layers, B, T, DT, per_sample, per_layer, acc, 0,
-                                descs=descs)
-        for _ in range(2):
-            stats_gram()
-        torch.cuda.synchronize()
-        for k in ("gram", "wgrad", "finalize", "sqnorm"):
-            ctx.profile_read(k)
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            stats_gram()
-        torch.cuda.synchronize()
-        alt_ms = (time.perf_counter() - t1) / args.steps * 1e3
-        for k in ("gram", "wgrad"):
-            ms, n = ctx.profile_read(k)
-            kern[k] = dict(avg_ms=(ms / n) if n else None, launches=n)
-        for k in ("finalize", "sqnorm"):
-            ctx.profile_read(k)
-        ctx.set_tuning("stats_variant", 1)
-
-    # the same statistics with the gradient sum supplied by the caller (the training framework's
-    # own weight gradient): Gram kernel + reductions + norm test only
-    provided_ms = None
-    if args.only in ("all", "stats") and not args.grad_provided:
-        for l in layers:
-            l["provided"] = True
-        d_prov = A.binding.make_layer_descs(layers, B, T, DT)
-
-        def stats_provided():
-            A.adloco_grad_stats(ctx, layers, B, T, DT, per_sample, per_layer, acc, 0,
-                                descs=d_prov)
-            A.adloco_norm_test(ctx, None, acc, eta, B, 32, 2, 256, descs=d_prov)
-        for _ in range(2):
-            stats_provided()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            stats_provided()
-        torch.cuda.synchronize()
-        provided_ms = (time.perf_counter() - t1) / args.steps * 1e3
-        ms, n = ctx.profile_read("gram")
-        if kern["gram"]["avg_ms"] is None and n:
-            kern["gram"] = dict(avg_ms=ms / n, launches=n)
-        for k in ("finalize", "sqnorm"):
-            ctx.profile_read(k)
-
-    sym, full, executed = gram_flops(shapes, B, T)
-    wgrad_flops = sum(2 * B * T * di * do for _, di, do in shapes)
-    outer_bytes = (4 * (M + 2) + 8) * N
-    merge_bytes = 4 * (M + 1) * N
+    shapes = st["shapes"]
+    sym, full, executed = gram_flops(shapes, st["b_max"], T)       # per launch = per micro-batch
+    g_ms = kern["gram"]["avg_ms"]
+    traffic, traffic_note = measured_traffic("gram")
+    r_gram = roof("mfma", sym, g_ms, PEAK_BF16_MFMA, "TFLOP/s", 1e12, kernel="gram_bf16_dual_kernel",
+                  launches=kern["gram"]["launches"], units_per_launch=f"{st['b_max']} samples x {T} tokens x {len(shapes)} linears",
+                  flops_algorithmic_symmetric=sym, flops_full=full, flops_executed=executed,
+                  frac_executed=(executed / (g_ms * 1e-3) / PEAK_BF16_MFMA) if g_ms else None,
+                  traffic=traffic, traffic_source=traffic_note)
+    outer_bytes, merge_bytes = (4 * (M + 2) + 8) * N, 4 * (M + 1) * N
     sq_bytes = 4 * sum(di * do for _, di, do in shapes)
-
-    # the committed counter summary belongs to the default workload and its bf16 kernels only
-    traffic = measured_traffic() if (args.config == 2 and args.dtype == "bf16") else {}
-
-    def roof(name, bound, work, ms, peak, unit, scale, **extra):
-        if not ms:
-            return None
-        a = work / (ms * 1e-3) / scale
-        return dict(bound=bound, achieved=a, peak=peak / scale, unit=unit, frac=a / (peak / scale),
-                    traffic=traffic.get(name), avg_kernel_ms=ms, **extra)
-
-    r_gram = roof("gram", "mfma", sym, kern["gram"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
-                  kernel="gram_bf16_dual_kernel<false>", flops_algorithmic_symmetric=sym, flops_full=full,
-                  flops_executed=executed,
-                  frac_executed=(executed / (kern["gram"]["avg_ms"] * 1e-3) / PEAK_BF16_MFMA)
-                  if kern["gram"]["avg_ms"] else None)
-    r_wgrad = roof("wgrad", "mfma", wgrad_flops, kern["wgrad"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
-                   kernel="wgrad_bf16_x_kernel<false>", flops_algorithmic=wgrad_flops)
-    r_tile = roof("tile_stats", "mfma", wgrad_flops, kern["tile_stats"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s",
-                  1e12, kernel="ip_tile_kernel<1, true, false> (+ split-tile and per-sample reductions)",
-                  flops_algorithmic=wgrad_flops)
-    r_outer = roof("outer_step", "hbm", outer_bytes, kern["outer_step"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+    r_outer = roof("hbm", outer_bytes, kern["outer_step"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                    kernel="outer_step_vec_kernel", bytes_algorithmic=outer_bytes)
-    r_merge = roof("merge", "hbm", merge_bytes, kern["merge"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+    r_merge = roof("hbm", merge_bytes, kern["merge"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                    kernel="merge_vec_kernel", bytes_algorithmic=merge_bytes)
-    r_sq = roof("sqnorm", "hbm", sq_bytes, kern["sqnorm"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
+    r_sq = roof("hbm", sq_bytes, kern["sqnorm"]["avg_ms"], PEAK_HBM, "GB/s", 1e9,
                 kernel="sqnorm_partial_kernel", bytes_algorithmic=sq_bytes)
-    roofs = dict(tile_stats=r_tile, gram=r_gram, wgrad=r_wgrad, outer_step=r_outer, merge=r_merge,
-                 sqnorm=r_sq)
-    # kernels of the timed step (the other route's kernels were timed apart)
-    in_step = ("tile_stats", "finalize", "sqnorm", "outer_step", "merge") if kern["tile_stats"]["avg_ms"] \
-        else ("gram", "wgrad", "finalize", "sqnorm", "outer_step", "merge")
-    timed = {k: kern[k]["avg_ms"] for k in in_step if kern[k]["avg_ms"]}
-    dominant = max(timed, key=timed.get) if timed else None
-    stats_ms = sum(kern[k]["avg_ms"] or 0.0 for k in in_step if k not in ("outer_step", "merge"))
 
     out = {
-        "metric": "grad-stats tokens/s (MFMA util) + outer-step GB/s (frac HBM peak), 1 GPU",
-        "value": B * T / (ms_per_step * 1e-3),
+        "metric": METRIC,
+        "value": tokens / (stats_ms * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": workload,
-                   "blocks_held": (len(shapes) // len(cfg["block"])), "blocks_of_model": cfg["n_blocks"],
-                   "B": B, "T": T, "n_linears": len(shapes), "M": M, "N": N, "eta": eta,
-                   "grad_sum": "caller-provided" if args.grad_provided else "computed by the library",
-                   "stats_route": args.stats_variant,
-                   "timed_part": args.only},
-        "roofline": (dict(roofs[dominant], dominant_kernel=dominant)
-                     if dominant in roofs and roofs[dominant] else None),
-        "kernels": {"avg_ms": {k: v["avg_ms"] for k, v in kern.items()},
-                    "tile_stats": r_tile, "gram": r_gram, "wgrad": r_wgrad, "outer_step": r_outer,
-                    "merge": r_merge, "sqnorm": r_sq,
-                    "in_timed_step": list(in_step)},
-        "grad_stats_ms_gram_plus_gradient_sum_route": alt_ms,
-        "grad_stats_tokens_per_s": (B * T / (stats_ms * 1e-3)) if stats_ms else None,
-        "grad_stats_tokens_per_s_gradient_supplied": (B * T / (provided_ms * 1e-3)) if provided_ms else None,
+        "value_is": ("grad-stats tokens/s with the gradient sum supplied by the caller: tokens of the timed "
+                     "steps / HIP-event time of their adloco_grad_stats + adloco_norm_test calls; the outer "
+                     "step and merge of the same steps handle no tokens and are given in GB/s"),
+        "config": {"workload": (f"full AdLoCo round on one GPU: M={M} instances of a 350M-parameter model "
+                                f"({st['n_blocks']} of 24 blocks resident = {len(shapes)} linears, d=1024, MLP 4096, "
+                                f"T={T}, {args.dtype}), batch schedule {list(B_SCHEDULE)} samples = 1, 2, 4, 8 "
+                                f"accumulated micro-batches of {st['b_max']}, norm test eta={st['eta']}, b_cap "
+                                f"{st['b_cap']}, then outer step (Nesterov, lr 0.7, mu 0.9) and merge of all {M}"),
+                   "micro_batch_sets_resident": st["n_sets"], "bytes_per_micro_batch": st["per_set_bytes"],
+                   "rho_of_set": st["rho_of_set"], "M": M, "N": N,
+                   "grad_sum": "caller-supplied in the timed region (formed once by the library beforehand)",
+                   "tokens_in_timed_steps": tokens},
+        "stats_ms_in_timed_steps": stats_ms, "outer_merge_ms_in_timed_steps": outer_ms,
+        "tables_rebuilt_in_timed_steps": rebuilt,
         "outer_step_GBps": r_outer["achieved"] if r_outer else None,
         "merge_GBps": r_merge["achieved"] if r_merge else None,
-        "norm_test": {k: last.get(k) for k in ("stat", "b_req", "test_passed", "accumulate")},
-        "hbm_copy_reference": ({"GBps": copy_GBps, "how": "PyTorch device copy of 1 GiB fp32 (read + write bytes), for scale",
-                              "outer_step_vs_copy": (r_outer["achieved"] / copy_GBps) if r_outer else None,
-                              "merge_vs_copy": (r_merge["achieved"] / copy_GBps) if r_merge else None}
-                             if copy_GBps else None),
+        "roofline": dict(r_gram, dominant_kernel="gram") if r_gram else None,
+        "kernels": {"avg_ms": {k: v["avg_ms"] for k, v in kern.items()},
+                    "launches": {k: v["launches"] for k, v in kern.items()},
+                    "gram": r_gram, "outer_step": r_outer, "merge": r_merge, "sqnorm": r_sq},
+        "norm_test_by_schedule_step": [last.get(r) for r in range(len(plan))],
+        "requested_batches_from_the_setup_pass": reqs,
     }
-    if not args.no_next_rows:
-        out["next_rows"] = {}
-        if args.only in ("all", "stats"):
-            out["next_rows"]["vector_table"] = vector_table_leg(torch, synth, A, ctx, layers, B, T, dev,
-                                                                args.steps)
-            out["next_rows"]["inner_products"] = inner_products_leg(torch, A, ctx, layers, B, T, dev,
-                                                                    args.steps)
-        if args.only in ("all", "outer"):
-            del insts, mom
-            torch.cuda.empty_cache()
-            out["next_rows"]["inner_step"] = inner_step_leg(torch, synth, A, ctx, N, dev, args.steps)
-        for k, v in out["next_rows"].items():
-            v["traffic"] = traffic.get(k)
-    if not args.no_cpu_baseline:
+
+    # ---- the same round with the gradient sum formed by the library (per-sample gradient tiles)
+    if "self" in legs:
+        for r in range(len(plan)):
+            round_stats(A, ctx, st, r, DT, provided=False)
+        torch.cuda.synchronize()
+        drop_profile(ctx, PROF)
+        tm = Timer(torch)
+        n_pass = 2
+        for _ in range(n_pass):
+            for r in range(len(plan)):
+                e0, e1 = tm.span()
+                e0.record()
+                round_stats(A, ctx, st, r, DT, provided=False)
+                e1.record()
+        ms = tm.total_ms()
+        k = read_profile(ctx, PROF)
+        wflops = sum(2.0 * st["b_max"] * T * di * do for _, di, do in shapes)
+        out["self_contained"] = dict(
+            what="the same batch schedule with grad_sum formed by the library: norms and gradient sum from "
+                 "one pass over per-sample gradient tiles",
+            tokens_per_s=n_pass * sum(st["b_max"] * len(p) * T for p in plan) / (ms * 1e-3),
+            tile_stats=roof("mfma", wflops, k["tile_stats"]["avg_ms"], PEAK_BF16_MFMA, "TFLOP/s", 1e12,
+                            kernel="ip_tile_kernel<1, true>", flops_algorithmic=wflops,
+                            launches=k["tile_stats"]["launches"]))
+    # free the round before the other legs
+    for key in ("sets", "grads", "theta", "insts", "mom", "descs_provided", "descs_own"):
+        st[key] = None
+    torch.cuda.empty_cache()
+
+    if "llama" in legs:
+        out["llama_1b"] = llama_leg(torch, synth, A, ctx, args, dev, DT)
+        torch.cuda.empty_cache()
+    gpt2_layers = None
+    if "gpt2" in legs or "next" in legs:
+        out["gpt2_small_plus_outer_124m"], gpt2_layers, (B2, T2) = gpt2_leg(torch, synth, A, ctx, args, dev, DT, TDT)
+    if "probe" in legs:
+        probes = {}
+        for v, name in ((0, "wave_tile_64x64"), (1, "wave_tile_128x64")):
+            ms, fl = ctx.probe_mfma_lds(v, 8192)
+            probes[name] = dict(ms=ms, TFLOPs=fl / (ms * 1e-3) / 1e12, frac_of_peak=fl / (ms * 1e-3) / PEAK_BF16_MFMA)
+        out["lds_fed_mfma_ceiling"] = dict(
+            what="32x32x16 bf16 MFMAs on fragments read from LDS, nothing else running (no global loads, no "
+                 "barriers): what the chip sustains at the clock it holds under that load",
+            **probes)
+        if r_gram:
+            best = max(p["frac_of_peak"] for p in probes.values())
+            out["roofline"]["frac_executed_of_lds_fed_ceiling"] = r_gram["frac_executed"] / best
+    if "next" in legs and gpt2_layers is not None:
+        nr = {}
+        nr["vector_table"] = vector_table_leg(torch, synth, A, ctx, gpt2_layers, B2, T2, dev, DT, TDT, 10)
+        nr["inner_products"] = inner_products_leg(torch, A, ctx, gpt2_layers, B2, T2, dev, DT, 10)
+        gpt2_layers = None
+        torch.cuda.empty_cache()
+        nr["inner_step"] = inner_step_leg(torch, synth, A, ctx, 124_000_000, dev, 10)
+        out["next_rows"] = nr
+    if "cpu" in legs:
         from oracle import adloco_oracle as orc
-        out["cpu_baseline"] = cpu_baseline(synth, orc, shapes, B, T, N, M, max(1, min(12, args.cpu_blocks)))
+        out["cpu_baseline"] = cpu_baseline(synth, orc, st["cfg"], 24, N, M)
     else:
         out["cpu_baseline"] = None
     ctx.close()

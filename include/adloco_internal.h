@@ -25,6 +25,13 @@ int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value);
  * kernel, returns their summed duration in milliseconds and their count, and forgets them. */
 int adloco_profile_read(adloco_ctx* ctx, const char* kernel, double* total_ms, int* launches);
 
+/* The rate at which the chip's MFMA units run when their bf16 operands come from LDS and nothing
+ * else happens (no global loads, no barriers): the practical ceiling of the Gram and gradient-sum
+ * kernels.  variant 0: 64 x 64 wave tiles, 1: 128 x 64 wave tiles; one 8-wave workgroup per CU,
+ * `ksteps` k-steps of 16.  Runs on the null stream and waits for it.  ms: kernel time, flops: MFMA
+ * flops executed in it. */
+int adloco_probe_mfma_lds(adloco_ctx* ctx, int variant, int ksteps, double* ms, double* flops);
+
 /* Number of times the context has built its shape-dependent tables (tile, job and descriptor
  * tables): it moves on the first call with a new list of shapes and stays put while only the
  * addresses in a, delta and grad_sum change from call to call. */

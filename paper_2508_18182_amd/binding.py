@@ -133,6 +133,8 @@ def load_library():
     lib.adloco_profile_read.argtypes = [vp, C.c_char_p, C.POINTER(dbl), C.POINTER(C.c_int)]
     lib.adloco_profile_read.restype = C.c_int
     lib.adloco_table_builds.argtypes = [vp]
+    lib.adloco_probe_mfma_lds.argtypes = [vp, C.c_int, C.c_int, C.POINTER(dbl), C.POINTER(dbl)]
+    lib.adloco_probe_mfma_lds.restype = C.c_int
     lib.adloco_table_builds.restype = C.c_int
     lib.adloco_grad_stats.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, C.c_int, C.c_int, C.c_int,
                                       vp, vp, vp, u32, vp]
@@ -206,6 +208,12 @@ class Context:
     def table_builds(self) -> int:
         """Number of times this context has (re)built its shape-dependent tables (measurement aid)."""
         return int(load_library().adloco_table_builds(self._h))
+
+    def probe_mfma_lds(self, variant: int, ksteps: int = 4096):
+        """(ms, flops) of the LDS-fed MFMA loop (measurement aid, see adloco_internal.h)."""
+        ms, fl = C.c_double(), C.c_double()
+        self._check(load_library().adloco_probe_mfma_lds(self._h, variant, ksteps, C.byref(ms), C.byref(fl)))
+        return ms.value, fl.value
 
     def profile_read(self, kernel: str):
         """(total milliseconds, launches) of the named kernel since the last read."""
