@@ -217,3 +217,83 @@ def test_outer_step_broadcast_350m_m8(ctx):
     np.testing.assert_allclose(pg[tidx].cpu().numpy(), ref["pseudo_grad"], rtol=TOL_OUTER, atol=0)
     for x in insts:
         assert torch.equal(x, theta)                                    # reset everywhere
+
+
+def test_round_350m_real_widths_eight_micro_batches(ctx):
+    # workload 5 at its real widths: one transformer block {1024->3072, 1024->1024, 1024->4096,
+    # 4096->1024}, T = 1024, micro-batch cap 32, the batch grown to 256 samples = 8 accumulated
+    # micro-batches with their own tensors (as bench.py holds them), then the M = 8 x 350M outer step
+    # and the merge of all 8 instances weighted by the requested batches.
+    import torch
+    import paper_2508_18182_amd as A
+    cfg = synth.CONFIGS[5]
+    T, b_max, eta, b_cap = cfg["T"], cfg["b_max"], cfg["eta"], cfg["b_cap"]
+    rho = synth.round_rho_schedule(eta, [256], [180.0])[0]
+    sets = synth.device_round_micro_batches(5, "cuda:0", [rho] * 8, linears=range(4))
+    shapes = [(l["d_in"], l["d_out"]) for l in sets[0]]
+    assert shapes == [(1024, 3072), (1024, 1024), (1024, 4096), (4096, 1024)]
+    grad_sums = [torch.full((do, di), float("nan"), device="cuda:0") for di, do in shapes]
+    acc = torch.zeros(2, dtype=torch.float64, device="cuda:0")
+    per_set, S1_running, checkpoints = [], 0.0, {}
+    for m, mb in enumerate(sets):
+        layers = [dict(l, grad_sum=g) for l, g in zip(mb, grad_sums)]
+        ps, pl, acc = _run_stats(ctx, layers, b_max, T, A.ADLOCO_ACCUMULATE if m else 0, acc)
+        per_set.append((ps.cpu().numpy().astype(np.float64), pl.clone()))
+        S1_running += float(per_set[-1][0].sum())
+        # the running accumulator after 1, 2, 4 and 8 micro-batches
+        if m + 1 in (1, 2, 4, 8):
+            assert int(acc.cpu().view(torch.int64)[1]) == b_max * (m + 1)
+            assert float(acc.cpu()[0]) == pytest.approx(S1_running, rel=1e-6)
+            res = A.adloco_norm_test(ctx, layers, acc, eta, b_max * (m + 1), b_max, 2, b_cap)
+            S2_host = sum(float((g.double() ** 2).sum()) for g in grad_sums)
+            assert res["S2"] == pytest.approx(S2_host, rel=1e-9)
+            ref = orc.norm_test(res["S1"], res["S2"], b_max * (m + 1), eta, b_max * (m + 1), b_max, 2, b_cap)
+            assert res["stat"] == pytest.approx(ref["stat"], rel=1e-9)
+            for k in ("b_req", "test_passed", "accumulate", "accum_steps", "b_micro"):
+                assert res[k] == ref[k], (m, k)
+            checkpoints[m + 1] = res
+    # sampled per-(layer, sample) norms of several micro-batches against explicit per-sample gradients
+    for m, picks in ((0, [(0, 0), (3, 31)]), (3, [(1, 7)]), (7, [(2, 19), (3, 2)])):
+        _check_sampled_norms(sets[m], per_set[m][1], picks)
+    for ps, pl in per_set:
+        np.testing.assert_allclose(pl.cpu().numpy().astype(np.float64).sum(axis=0), ps, rtol=1e-6)
+    # sampled rows of the accumulated gradient sum: all 256 samples of the 1024->1024 layer
+    a_all = np.concatenate([orc.widen(_bits(mb[1]["a"].reshape(-1, 1024))) for mb in sets])
+    for e in (0, 517, 1023):
+        col = np.concatenate([orc.widen(_bits(mb[1]["delta"].reshape(-1, 1024)[:, e])) for mb in sets])
+        want = col @ a_all
+        got = grad_sums[1][e].cpu().numpy().astype(np.float64)
+        assert np.max(np.abs(got - want)) <= 1e-4 * float(np.sqrt(np.mean(want * want))), e
+    del a_all
+    # the statistic sits where the input recipe puts it (common component rho in every sample)
+    assert checkpoints[8]["stat"] == pytest.approx(180.0, rel=0.1)
+    assert checkpoints[8]["n_samples"] == 256 and checkpoints[8]["accumulate"] == 1
+    sets = None
+    torch.cuda.empty_cache()
+    # ---- the outer half: 8 instances x 350M, then the merge of all 8 weighted by requested batches
+    o = cfg["outer"]
+    N = o["N"]
+    theta, insts, mom = synth.device_outer_inputs(5, "cuda:0")
+    idx = _sample_idx(N, 300_000, 79)
+    tidx = torch.from_numpy(idx).to("cuda:0")
+    h_theta, h_mom = theta[tidx].cpu().numpy(), mom[tidx].cpu().numpy()
+    h_inst = [x[tidx].cpu().numpy() for x in insts]
+    A.adloco_outer_step(ctx, theta, insts, mom, o["lr"], o["mu"], True)
+    torch.cuda.synchronize()
+    ref = orc.outer_step(h_theta, h_inst, h_mom, o["lr"], o["mu"], True)
+    scale = np.maximum.reduce([np.abs(h_theta.astype(np.float64))] + [np.abs(x.astype(np.float64)) for x in h_inst])
+    got = theta[tidx].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref["theta_outer_f64"]) <= TOL_OUTER * np.maximum(scale, np.abs(got)))
+    np.testing.assert_allclose(mom[tidx].cpu().numpy(), ref["momentum"], rtol=TOL_OUTER, atol=0)
+    w = [checkpoints[c]["b_req"] for c in (1, 2, 4, 8)] + [checkpoints[c]["b_req"] + 1 for c in (1, 2, 4, 8)]
+    assert A.adloco_check_merge(w, 8) == list(np.argsort(np.array(w), kind="stable"))
+    rep = A.adloco_merge(ctx, insts, w)
+    torch.cuda.synchronize()
+    m = orc.merge(h_inst, w)
+    assert rep == m["rep"]
+    got = insts[rep][tidx].cpu().numpy().astype(np.float64)
+    mscale = np.max(np.abs(np.stack(h_inst)), axis=0).astype(np.float64)
+    assert np.all(np.abs(got - m["x_merge_f64"]) <= TOL_OUTER * mscale)
+    for j in range(8):
+        if j != rep:
+            np.testing.assert_array_equal(insts[j][tidx].cpu().numpy(), h_inst[j])
