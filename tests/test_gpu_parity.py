@@ -56,7 +56,9 @@ def test_tiny_config_fp32(ctx):
     got, want = _check_grad_stats(ctx, layers, TOL_F32)
     import paper_2508_18182_amd as A
     res = A.adloco_norm_test(ctx, got["layers"], got["acc"], 0.5, 8, 32)
-    ref = orc.norm_test(want["S1"], want["S2"], 8, 0.5, 8, 32)
+    # the oracle's own variance: the second pass over the explicit per-sample gradients
+    want2 = orc.grad_stats([(l["a"], l["delta"]) for l in layers], two_pass=True)
+    ref = orc.norm_test(want2["S1"], want2["S2"], 8, 0.5, 8, 32, V=want2["V"])
     assert res["S2"] == pytest.approx(want["S2"], rel=TOL_F32)
     assert res["stat"] == pytest.approx(ref["stat"], rel=1e-3)
     for k in ("b_req", "test_passed", "accumulate", "accum_steps", "b_micro"):
@@ -184,7 +186,7 @@ def test_micro_batch_accumulation_matches_concatenation(ctx):
     _same_decisions(res, ref, eta=0.3, b_cur=12, b_max=4, n_switch=2, b_cap=256)
 
 
-NEAR_CUT = {"n": 0, "total": 0}
+NEAR_CUT = {"n": 0, "total": 0, "cases": []}
 
 
 def _same_decisions(res, ref, **oracle_kw):
@@ -194,18 +196,23 @@ def _same_decisions(res, ref, **oracle_kw):
     oracle's."""
     stat = ref["stat"]
     assert res["stat"] == pytest.approx(stat, rel=1e-3)
-    cuts = [math.floor(stat), math.ceil(stat), ref["b_cur"]]
+    # the cuts that can change a decision: b_cur (the test flips there), and the integers next to the
+    # statistic unless both neighbours give the same request anyway (below b_cur, or above the ceiling)
+    cap = oracle_kw.get("b_cap", 0) or float("inf")
+    req = [min(cap, max(ref["b_cur"], c, 1)) for c in (math.floor(stat), math.ceil(stat))]
+    cuts = [ref["b_cur"]] + ([math.floor(stat), math.ceil(stat)] if req[0] != req[1] else [])
     near = any(c > 0 and abs(stat - c) <= 1e-3 * c for c in cuts)
     NEAR_CUT["total"] += 1
     if near:
         NEAR_CUT["n"] += 1
+        NEAR_CUT["cases"].append((round(stat, 4), dict(oracle_kw)))
         ref = orc.norm_test(res["S1"], res["S2"], res["n_samples"], **oracle_kw)
     for k in ("b_req", "test_passed", "accumulate", "accum_steps", "b_micro", "stat_undefined"):
         assert res[k] == ref[k], (k, res, ref)
 
 
 @pytest.mark.parametrize("rho,eta,b_cur,b_max,cap", [
-    (0.0, 0.3, 8, 32, 0), (0.5, 0.3, 8, 32, 256), (0.9, 0.3, 8, 4, 0), (0.7, 0.8, 8, 2, 64)])
+    (0.0, 0.31, 8, 32, 0), (0.5, 0.3, 8, 32, 256), (0.9, 0.3, 8, 4, 0), (0.7, 0.8, 8, 2, 64)])
 def test_norm_test_decisions(ctx, rho, eta, b_cur, b_max, cap):
     import paper_2508_18182_amd as A
     from gpu_util import run_grad_stats
@@ -402,5 +409,5 @@ def test_argument_errors(ctx):
 
 
 def test_zz_boundary_cases_are_rare():
-    # runs after the decision tests of this module: most seeded cases must sit away from a cut
-    assert NEAR_CUT["total"] == 0 or NEAR_CUT["n"] * 3 <= NEAR_CUT["total"], NEAR_CUT
+    # runs after the decision tests of this module: at most one seeded case in ten may sit on a cut
+    assert NEAR_CUT["total"] == 0 or NEAR_CUT["n"] * 10 <= NEAR_CUT["total"], NEAR_CUT

@@ -117,6 +117,14 @@ def test_random_case(ctx, seed):
         assert res["stat"] == pytest.approx(ref["stat"], rel=min(0.5, 3 * tol * amp)), case
         slack = 3 * tol * amp * ref["stat"]
         near_cut = (abs(ref["stat"] - round(ref["stat"])) < slack or abs(ref["stat"] - max(1, n)) < slack)
-        if not near_cut:
-            for key in ("b_req", "test_passed", "accumulate", "accum_steps", "b_micro"):
-                assert res[key] == ref[key], (key, case)
+        if near_cut:
+            # next to a cut the two statistics may fall on either side of it: there the decisions are
+            # held against the oracle's rule applied to the sums the GPU itself returned
+            ref = orc.norm_test(res["S1"], res["S2"], n, 0.4, max(1, n), 8, 2, 512)
+            assert res["stat"] == pytest.approx(ref["stat"], rel=1e-9), case
+        for key in ("b_req", "test_passed", "accumulate", "accum_steps", "b_micro"):
+            assert res[key] == ref[key], (key, case)
+    else:
+        ref = orc.norm_test(res["S1"], res["S2"], n, 0.4, max(1, n), 8, 2, 512)
+        for key in ("b_req", "test_passed", "accumulate", "accum_steps", "b_micro", "stat_undefined"):
+            assert res[key] == ref[key], (key, case)
