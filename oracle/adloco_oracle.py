@@ -401,6 +401,73 @@ def outer_step(theta_outer, thetas, momentum, lr: float, mu: float, nesterov: bo
 
 
 # --------------------------------------------------------------------------------------
+# The same outer step and merge with the instances' DRIFTS stored in bf16 (the quantity
+# Algorithm 3 averages, x^{(t-1)} - x_m^{(t,H)}, is what travels; outer model and momentum
+# stay fp32).  Halves the bytes an instance contributes; the drift, not the parameter,
+# carries the rounding error: at most 2^-8 relative to the drift itself.
+# --------------------------------------------------------------------------------------
+
+def round_to_bf16_bits(x32) -> np.ndarray:
+    """fp32 -> bf16 bit patterns (uint16), round to nearest, ties to even, written out on the bit
+    pattern: keep the upper 16 bits, add one if the dropped half is above one half, or exactly one
+    half and the kept part is odd.  NaN stays NaN (quiet bit set)."""
+    u = np.ascontiguousarray(np.asarray(x32, dtype=np.float32)).view(np.uint32)
+    upper = u >> np.uint32(16)
+    lower = u & np.uint32(0xFFFF)
+    up = (lower > 0x8000) | ((lower == 0x8000) & ((upper & 1) == 1))
+    out = (upper + up.astype(np.uint32)).astype(np.uint32)
+    nan = np.isnan(np.asarray(x32, dtype=np.float32))
+    out = np.where(nan, upper | np.uint32(0x40), out)
+    return out.astype(np.uint16)
+
+
+def pack_drift(theta_outer, theta_m) -> np.ndarray:
+    """d_m = x^{(t-1)} - x_m^{(t,H)} (Algorithm 3, the summand of Delta) as stored: the fp32
+    difference of the two fp32 vectors, rounded to bf16.  Both roundings are the format's own
+    (IEEE fp32 subtraction, then nearest-even to 8 significant bits): the stored code is decided in
+    fp32 on both sides of a comparison."""
+    a = np.asarray(theta_outer, dtype=np.float32)
+    b = np.asarray(theta_m, dtype=np.float32)
+    return round_to_bf16_bits(a - b)
+
+
+def outer_step_drift(theta_outer, drift_bits, momentum, lr: float, mu: float, nesterov: bool = True,
+                     broadcast: bool = False) -> dict:
+    """Algorithm 3's Delta and OuterOpt from stored drifts: Delta = (1/M) sum_m d_m with d_m the
+    bf16 values as stored (widened exactly), then the update of outer_step, fp64, rounded once.
+    broadcast: the worker reset x_m <- x leaves every drift at zero."""
+    x = widen(theta_outer)
+    M = len(drift_bits)
+    delta = np.zeros_like(x)
+    for d in drift_bits:
+        delta += widen(np.asarray(d, dtype=np.uint16))
+    delta /= M
+    buf = widen(momentum) if momentum is not None else np.zeros_like(x)
+    buf = mu * buf + delta
+    step = delta + mu * buf if nesterov else buf
+    x_new = x - lr * step
+    out = dict(theta_outer=x_new.astype(np.float32), momentum=buf.astype(np.float32),
+               pseudo_grad=delta.astype(np.float32), theta_outer_f64=x_new, momentum_f64=buf,
+               pseudo_grad_f64=delta)
+    if broadcast:
+        out["drifts"] = [np.zeros(x.shape, dtype=np.uint16) for _ in range(M)]
+    return out
+
+
+def merge_drift(x_rep, drift_bits, w_rep: float, w_others) -> dict:
+    """DoMerge (Algorithm 2) when the other trainers are known by their stored drifts from the
+    representative, d_j = x_r - x_j (bf16): x_merge = sum_j b_j x_j / sum_j b_j = x_r - sum_{j != r}
+    b_j d_j / sum_j b_j, fp64, rounded once."""
+    x = widen(x_rep)
+    wsum = float(w_rep) + float(sum(float(w) for w in w_others))
+    s = np.zeros_like(x)
+    for d, w in zip(drift_bits, w_others):
+        s += float(w) * widen(np.asarray(d, dtype=np.uint16))
+    xm = x - s / wsum
+    return dict(x_merge=xm.astype(np.float32), x_merge_f64=xm)
+
+
+# --------------------------------------------------------------------------------------
 # Trainer merge (Section 4.1.1; Algorithms 1 and 2)
 # --------------------------------------------------------------------------------------
 

@@ -874,3 +874,77 @@ def test_round_step_case_catches_planted_mistakes(what, old, new):
     exec(compile(src.replace(old, new), "<mutated round_step>", "exec"), ns)
     with pytest.raises(AssertionError):
         _round_case_check(ns["round_step"])
+
+
+# ------------------------------------------------------------------ drifts stored in bf16
+
+def test_bf16_rounding_is_nearest_even_and_matches_torch():
+    import torch
+    # hand cases on the bit pattern: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1);
+    # 1 + 3 * 2^-8 is a tie -> even (1 + 2^-6); just above a tie rounds up; exact values stay
+    one = np.float32(1.0)
+    cases = [(one + np.float32(2.0 ** -8), 0x3F80), (one + np.float32(3 * 2.0 ** -8), 0x3F82),
+             (one + np.float32(2.0 ** -8 + 2.0 ** -20), 0x3F81), (np.float32(-0.5), 0xBF00),
+             (np.float32(0.0), 0x0000), (np.float32(3.0e38), 0x7F62), (np.float32(np.inf), 0x7F80)]
+    for x, want in cases:
+        assert int(orc.round_to_bf16_bits(np.array([x]))[0]) == want, (x, hex(want))
+    assert np.isnan(orc.widen(orc.round_to_bf16_bits(np.array([np.nan], np.float32)))[0])
+    # library pin: torch's own fp32 -> bf16 conversion on two million values of every size
+    r = _rng(4401)
+    x = (r.standard_normal(2_000_000) * np.exp(r.uniform(-30, 30, 2_000_000))).astype(np.float32)
+    tb = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(orc.round_to_bf16_bits(x), tb)
+
+
+def test_pack_drift_hand_values_and_error_bound():
+    th = np.array([1.0, 0.02, -0.5, 3.0], np.float32)
+    xm = np.array([0.99609375, 0.02, -0.75, 1.0], np.float32)      # drifts 2^-8, 0, 0.25, 2: exact in bf16
+    np.testing.assert_array_equal(orc.widen(orc.pack_drift(th, xm)), [2.0 ** -8, 0.0, 0.25, 2.0])
+    r = _rng(4402)
+    th = (0.02 * r.standard_normal(100_000)).astype(np.float32)
+    xm = th - (1e-3 * r.standard_normal(100_000)).astype(np.float32)
+    d = orc.widen(orc.pack_drift(th, xm))
+    exact = th.astype(np.float64) - xm.astype(np.float64)
+    # one fp32 subtraction (2^-24 of the operands) and one bf16 rounding (half an ulp of 8 significant bits: 2^-8 of the drift)
+    assert np.all(np.abs(d - exact) <= 2.0 ** -8 * np.abs(exact) + 2.0 ** -23 * np.abs(th))
+
+
+def test_outer_step_drift_is_outer_step_on_the_stored_drifts():
+    r = _rng(4403)
+    N, M = 5000, 3
+    th = (0.02 * r.standard_normal(N)).astype(np.float32)
+    mom = (1e-4 * r.standard_normal(N)).astype(np.float32)
+    insts = [th - (1e-3 * r.standard_normal(N)).astype(np.float32) for _ in range(M)]
+    bits = [orc.pack_drift(th, x) for x in insts]
+    got = orc.outer_step_drift(th, bits, mom, 0.7, 0.9, True)
+    # the plain outer step on instances that sit exactly at theta - stored drift (fp64 inputs)
+    ref = orc.outer_step(th, [th.astype(np.float64) - orc.widen(b) for b in bits], mom, 0.7, 0.9, True)
+    np.testing.assert_allclose(got["theta_outer_f64"], ref["theta_outer_f64"], rtol=0, atol=1e-18)
+    np.testing.assert_allclose(got["momentum_f64"], ref["momentum_f64"], rtol=1e-13, atol=1e-20)
+    # against the unquantised step: the pseudo-gradient moves by at most 2^-8 of the mean |drift|
+    full = orc.outer_step(th, insts, mom, 0.7, 0.9, True)
+    bound = 2.0 ** -8 * np.mean([np.abs(th.astype(np.float64) - x) for x in insts], axis=0) + 1e-9
+    assert np.all(np.abs(got["pseudo_grad_f64"] - full["pseudo_grad_f64"]) <= bound)
+    # hand value: drifts 0.25 and 0.75, zero momentum, lr 1, mu 0 -> theta - 0.5
+    h = orc.outer_step_drift(np.array([2.0], np.float32),
+                             [orc.round_to_bf16_bits(np.array([0.25], np.float32)),
+                              orc.round_to_bf16_bits(np.array([0.75], np.float32))], None, 1.0, 0.0, False)
+    assert float(h["theta_outer"][0]) == 1.5 and float(h["pseudo_grad"][0]) == 0.5
+    z = orc.outer_step_drift(th, bits, mom, 0.7, 0.9, True, broadcast=True)
+    assert all(not b.any() for b in z["drifts"])
+
+
+def test_merge_drift_is_merge_on_the_stored_drifts():
+    r = _rng(4404)
+    N = 4000
+    xr = (0.02 * r.standard_normal(N)).astype(np.float32)
+    others = [xr - (1e-3 * r.standard_normal(N)).astype(np.float32) for _ in range(3)]
+    bits = [orc.pack_drift(xr, x) for x in others]
+    got = orc.merge_drift(xr, bits, 9.0, [3.0, 5.0, 1.0])
+    ref = orc.merge([xr.astype(np.float64)] + [xr.astype(np.float64) - orc.widen(b) for b in bits],
+                    [9.0, 3.0, 5.0, 1.0])
+    assert ref["rep"] == 0
+    np.testing.assert_allclose(got["x_merge_f64"], ref["x_merge_f64"], rtol=0, atol=1e-17)
+    # hand value: representative 4 (weight 1), one other at 0 (drift 4, weight 3) -> 1
+    h = orc.merge_drift(np.array([4.0], np.float32), [orc.round_to_bf16_bits(np.array([4.0], np.float32))], 1.0, [3.0])
+    assert float(h["x_merge"][0]) == 1.0
