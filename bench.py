@@ -431,6 +431,42 @@ def inner_step_leg(torch, synth, A, ctx, N, dev, steps):
                 bytes_algorithmic=28 * N)
 
 
+def drift_leg(torch, synth, A, ctx, dev, steps):
+    """The outer step and merge of the round (M = 8 x 350M) on instance drifts stored in bf16: the
+    outer step reads 8 + 2 M and writes 8 bytes per parameter, the merge reads 4 + 2 (S - 1) and writes
+    4, packing one instance reads 8 and writes 2."""
+    o = synth.CONFIGS[5]["outer"]
+    N, M = o["N"], o["M"]
+    theta = synth.device_normal(9305, (N,), o["std_theta"], torch.float32, dev)
+    mom = synth.device_normal(9355, (N,), o["std_mom"], torch.float32, dev)
+    inst = theta - synth.device_normal(9405, (N,), o["std_delta"], torch.float32, dev)
+    drifts = [torch.empty(N, dtype=torch.bfloat16, device=dev) for _ in range(M)]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {}
+
+    def timed(fn, nbytes, kernel):
+        for _ in range(2):
+            fn()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return roof("hbm", nbytes, e0.elapsed_time(e1) / steps, PEAK_HBM, "GB/s", 1e9, kernel=kernel,
+                    bytes_algorithmic=nbytes)
+    out["pack_drift"] = timed(lambda: A.adloco_pack_drift(ctx, theta, inst, drifts[0]), 10 * N,
+                              "pack_drift_vec_kernel")
+    for d in drifts[1:]:
+        d.copy_(drifts[0])
+    out["outer_step_drift"] = timed(lambda: A.adloco_outer_step_drift(ctx, theta, drifts, mom, o["lr"], o["mu"], True),
+                                    (16 + 2 * M) * N, "outer_step_drift_vec_kernel")
+    out["merge_drift"] = timed(lambda: A.adloco_merge_drift(ctx, theta, drifts[1:], 64.0, [32.0 + k for k in range(M - 1)]),
+                               (8 + 2 * (M - 1)) * N, "merge_drift_vec_kernel")
+    out["bytes_vs_fp32_instances"] = dict(outer_step=(16 + 2 * M) / (16 + 4 * M), merge=(8 + 2 * (M - 1)) / (4 * (M + 1)))
+    return out
+
+
 def cpu_baseline(synth, orc, cfg, n_blocks, N, M):
     """The oracle as it stands on a bounded slice of the timed workload: the four linears of 4 of the
     24 transformer blocks on one whole micro-batch of 32 samples (per-sample norms, gradient sum, norm
@@ -651,6 +687,8 @@ def main():
         gpt2_layers = None
         torch.cuda.empty_cache()
         nr["inner_step"] = inner_step_leg(torch, synth, A, ctx, 124_000_000, dev, 10)
+        torch.cuda.empty_cache()
+        nr["bf16_drift_M8_350M"] = drift_leg(torch, synth, A, ctx, dev, 10)
         out["next_rows"] = nr
     if "cpu" in legs:
         from oracle import adloco_oracle as orc

@@ -235,6 +235,35 @@ int adloco_outer_step(adloco_ctx* ctx, float* theta_outer, float* const* theta_i
                       uint32_t flags, float* pseudo_grad_out, void* stream);
 
 /* ------------------------------------------------------------------------------------ *
+ * The outer step and the merge on instance DRIFTS stored in bf16.  What Algorithm 3 averages is
+ * the drift d_m = x^{(t-1)} - x_m^{(t,H)} of every instance (the Delta line); kept in bf16 it costs
+ * 2 bytes per instance and parameter instead of 4 -- the traffic (on one GPU: HBM bytes, across
+ * GPUs: the message) that the paper's motivation is about (Sections 1 and 3.2) -- at a rounding
+ * error of at most 2^-8 of the drift itself.  Outer model and momentum stay fp32.
+ *
+ * adloco_pack_drift: drift_out = bf16(theta_outer - theta_m): the fp32 difference rounded to
+ *   nearest-even.  drift_out: device [N] bf16 bit patterns, may not overlap the inputs.
+ * adloco_outer_step_drift: adloco_outer_step with Delta = (1/M) sum_m d_m read from M bf16
+ *   vectors.  drift: HOST array of M device pointers, each [N] bf16 (written only with
+ *   ADLOCO_BROADCAST: the worker reset x_m <- x_outer leaves every drift at zero).  All other
+ *   arguments, conventions and error codes as adloco_outer_step.  Reads 8 + 2 M and writes 8 bytes
+ *   per parameter (adloco_outer_step: 8 + 4 M and 8).
+ * adloco_merge_drift: DoMerge (Algorithm 2) when the other trainers are known by their drifts
+ *   from the representative, d_j = x_r - x_j:  x_r <- x_r - sum_{j != r} b_j d_j / sum_j b_j, which
+ *   is sum_j b_j x_j / sum_j b_j.  x_rep: device [N] fp32 in/out; drift: HOST array of n_others
+ *   device pointers ([N] bf16, read only); w_rep = b_r, w_others: HOST [n_others], all > 0;
+ *   n_others + 1 <= ADLOCO_MAX_INSTANCES; n_others = 0 leaves x_r as it is.
+ * 16-byte aligned pointers take the vector path, others a scalar path with the same results;
+ * fp64 in registers, rounded once. */
+int adloco_pack_drift(adloco_ctx* ctx, const float* theta_outer, const float* theta_m,
+                      uint16_t* drift_out, size_t N, void* stream);
+int adloco_outer_step_drift(adloco_ctx* ctx, float* theta_outer, uint16_t* const* drift, int M,
+                            size_t N, float* momentum, double lr, double mu, int nesterov,
+                            uint32_t flags, float* pseudo_grad_out, void* stream);
+int adloco_merge_drift(adloco_ctx* ctx, float* x_rep, const uint16_t* const* drift, double w_rep,
+                       const double* w_others, int n_others, size_t N, void* stream);
+
+/* ------------------------------------------------------------------------------------ *
  * Inner-product test and augmented inner-product test (Section 3.3.2), the two alternatives to
  * the norm test.  Both need, per sample, the inner product with the batch gradient
  *   c_i = <g_i, G>,  G = sum_j g_j  (the grad_sum buffers; <g_i, g_k> = c_i / B),

@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     NormTestResult, StatsAcc, adloco_check_merge, adloco_grad_stats, adloco_inner_product_decide,
     adloco_inner_product_test, adloco_inner_products, adloco_inner_step, adloco_merge,
     adloco_norm_test, adloco_norm_test_decide, adloco_norm_test_noalloc, adloco_outer_step, adloco_round, adloco_switch_mode,
-    adloco_version, lib_path, load_library, make_layer_descs,
+    adloco_pack_drift, adloco_outer_step_drift, adloco_merge_drift, adloco_version, lib_path, load_library, make_layer_descs,
 )

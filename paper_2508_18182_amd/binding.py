@@ -150,6 +150,9 @@ def load_library():
     lib.adloco_merge.argtypes = [vp, C.POINTER(vp), C.POINTER(dbl), C.c_int, sz, C.c_int,
                                  C.POINTER(C.c_int), vp]
     lib.adloco_inner_step.argtypes = [vp, vp, vp, vp, vp, sz, dbl, dbl, dbl, dbl, dbl, dbl, i64, vp]
+    lib.adloco_pack_drift.argtypes = [vp, vp, vp, vp, sz, vp]
+    lib.adloco_outer_step_drift.argtypes = [vp, vp, C.POINTER(vp), C.c_int, sz, vp, dbl, dbl, C.c_int, u32, vp, vp]
+    lib.adloco_merge_drift.argtypes = [vp, vp, C.POINTER(vp), dbl, C.POINTER(dbl), C.c_int, sz, vp]
     lib.adloco_round.argtypes = [vp, C.POINTER(RoundConfig), C.POINTER(Trainer), C.POINTER(C.c_int),
                                  C.POINTER(LinearDesc), C.c_int, sz, BATCH_FN, C.POINTER(RoundReport), vp]
     lib.adloco_inner_products.argtypes = [vp, C.POINTER(LinearDesc), C.c_int, C.c_int, C.c_int,
@@ -163,7 +166,8 @@ def load_library():
     for name in ("adloco_create", "adloco_destroy", "adloco_set_tuning", "adloco_grad_stats",
                  "adloco_norm_test", "adloco_norm_test_noalloc", "adloco_norm_test_decide", "adloco_switch_mode",
                  "adloco_outer_step", "adloco_merge", "adloco_check_merge", "adloco_inner_step", "adloco_round",
-                 "adloco_inner_products", "adloco_inner_product_test", "adloco_inner_product_decide"):
+                 "adloco_inner_products", "adloco_inner_product_test", "adloco_inner_product_decide",
+                 "adloco_pack_drift", "adloco_outer_step_drift", "adloco_merge_drift"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -476,6 +480,56 @@ def adloco_merge(ctx: Context, x, weights, rep: int = -1, stream=None,
     ctx._check(load_library().adloco_merge(ctx._h, arr, w, len(x), N, rep, C.byref(r),
                                            _stream_ptr(stream)))
     return r.value
+
+
+def _bf16_ptr(t, N, name):
+    """Device address of a contiguous bf16 (or int16 / uint16 bit pattern) tensor of >= N elements."""
+    import torch
+    if t is None or not t.is_cuda or t.dtype not in (torch.bfloat16, torch.int16, torch.uint16):
+        raise TypeError(f"{name} must be a GPU bf16 tensor")
+    if not t.is_contiguous() or t.numel() < N:
+        raise ValueError(f"{name} must be contiguous with at least {N} elements")
+    return C.c_void_p(t.data_ptr())
+
+
+def adloco_pack_drift(ctx: Context, theta_outer, theta_m, drift_out, stream=None, N: Optional[int] = None):
+    """drift_out (bf16 [N]) = bf16(theta_outer - theta_m)."""
+    import torch
+    N = theta_outer.numel() if N is None else N
+    ctx._check(load_library().adloco_pack_drift(
+        ctx._h, _dev_ptr(theta_outer, torch.float32, N, "theta_outer"),
+        _dev_ptr(theta_m, torch.float32, N, "theta_m"), _bf16_ptr(drift_out, N, "drift_out"), N,
+        _stream_ptr(stream)))
+
+
+def adloco_outer_step_drift(ctx: Context, theta_outer, drifts, momentum, lr: float, mu: float,
+                            nesterov: bool = True, flags: int = 0, pseudo_grad_out=None, stream=None,
+                            N: Optional[int] = None):
+    """adloco_outer_step on M instance drifts stored in bf16."""
+    import torch
+    N = theta_outer.numel() if N is None else N
+    arr = (C.c_void_p * len(drifts))()
+    for i, t in enumerate(drifts):
+        arr[i] = _bf16_ptr(t, N, f"drifts[{i}]").value
+    ctx._check(load_library().adloco_outer_step_drift(
+        ctx._h, _dev_ptr(theta_outer, torch.float32, N, "theta_outer"), arr, len(drifts), N,
+        _dev_ptr(momentum, torch.float32, N, "momentum"), lr, mu, 1 if nesterov else 0, flags,
+        _dev_ptr(pseudo_grad_out, torch.float32, N, "pseudo_grad_out"), _stream_ptr(stream)))
+
+
+def adloco_merge_drift(ctx: Context, x_rep, drifts, w_rep: float, w_others, stream=None,
+                       N: Optional[int] = None):
+    """x_rep <- x_rep - sum_j w_j d_j / (w_rep + sum_j w_j), d_j bf16 drifts of the other trainers."""
+    import torch
+    N = x_rep.numel() if N is None else N
+    if len(w_others) != len(drifts):
+        raise ValueError("one weight per drift")
+    arr = (C.c_void_p * max(len(drifts), 1))()
+    for i, t in enumerate(drifts):
+        arr[i] = _bf16_ptr(t, N, f"drifts[{i}]").value
+    w = (C.c_double * max(len(w_others), 1))(*[float(v) for v in w_others])
+    ctx._check(load_library().adloco_merge_drift(ctx._h, _dev_ptr(x_rep, torch.float32, N, "x_rep"), arr,
+                                                 float(w_rep), w, len(drifts), N, _stream_ptr(stream)))
 
 
 def adloco_check_merge(b_req: Sequence[int], w: int):

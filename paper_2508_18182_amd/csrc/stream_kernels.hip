@@ -217,6 +217,177 @@ __global__ __launch_bounds__(256) void inner_step_scalar_kernel(InnerArgs a, siz
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Instance drifts stored in bf16.  What Algorithm 3 averages is d_m = x^{(t-1)} - x_m^{(t,H)}; stored
+// in bf16 it costs 2 bytes per instance and parameter instead of 4 and carries a rounding error of
+// at most 2^-8 of the drift itself (a bf16 copy of the parameters would lose the drift altogether).
+// Outer model and momentum stay fp32.  Eight parameters per thread: two 16-byte loads of every fp32
+// stream, one of every drift.
+// ---------------------------------------------------------------------------------------
+typedef unsigned short __attribute__((ext_vector_type(8))) u16x8;
+
+// fp32 -> bf16, round to nearest, ties to even (NaN keeps a quiet bit)
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
+  const unsigned u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
+  return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ double bf16_to_f64(unsigned short h) {
+  return double(__uint_as_float(unsigned(h) << 16));
+}
+
+struct PackArgs {
+  const float* theta;
+  const float* inst;
+  unsigned short* out;
+  size_t n_grp, n;      // groups of eight handled by the vector kernel; total elements
+};
+
+__global__ __launch_bounds__(kStreamThreads) void pack_drift_vec_kernel(PackArgs a) {
+  const size_t v = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (v >= a.n_grp) return;
+  const size_t e = v * 8;
+  const f32x4 t0 = ld_stream(a.theta + e), t1 = ld_stream(a.theta + e + 4);
+  const f32x4 x0 = ld_stream(a.inst + e), x1 = ld_stream(a.inst + e + 4);
+  u16x8 o;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    o[c] = f32_to_bf16_rne(t0[c] - x0[c]);        // the fp32 difference, then one rounding to bf16
+    o[4 + c] = f32_to_bf16_rne(t1[c] - x1[c]);
+  }
+  __builtin_nontemporal_store(o, reinterpret_cast<u16x8*>(a.out + e));
+}
+__global__ __launch_bounds__(256) void pack_drift_scalar_kernel(PackArgs a, size_t first) {
+  const size_t stride = size_t(gridDim.x) * blockDim.x;
+  for (size_t e = first + size_t(blockIdx.x) * blockDim.x + threadIdx.x; e < a.n; e += stride)
+    a.out[e] = f32_to_bf16_rne(a.theta[e] - a.inst[e]);
+}
+
+struct OuterDriftArgs {
+  float* theta;
+  float* mom;         // may be null (mu == 0)
+  float* pg;          // may be null
+  unsigned short* drift[ADLOCO_MAX_INSTANCES];
+  size_t n_grp, n;
+  double lr, mu, inv_m;
+  int nesterov, broadcast;
+};
+
+template <int M>
+__device__ __forceinline__ void outer_drift_elem(const OuterDriftArgs& a, double th, double buf,
+                                                 const double (&d)[M], double& th_new, double& buf_new,
+                                                 double& delta) {
+  double s = 0.0;
+#pragma unroll
+  for (int m = 0; m < M; ++m) s += d[m];
+  delta = s * a.inv_m;
+  buf_new = a.mu * buf + delta;
+  const double step = a.nesterov ? delta + a.mu * buf_new : buf_new;
+  th_new = th - a.lr * step;
+}
+
+template <int M>
+__global__ __launch_bounds__(kStreamThreads) void outer_step_drift_vec_kernel(OuterDriftArgs a) {
+  const size_t v = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (v >= a.n_grp) return;
+  const size_t e = v * 8;
+  f32x4 th[2], bf[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  th[0] = ld_stream(a.theta + e);
+  th[1] = ld_stream(a.theta + e + 4);
+  if (a.mom) {
+    bf[0] = ld_stream(a.mom + e);
+    bf[1] = ld_stream(a.mom + e + 4);
+  }
+  u16x8 ds[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) ds[m] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(a.drift[m] + e));
+  f32x4 th_o[2], bf_o[2], pg_o[2];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    double d[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) d[m] = bf16_to_f64(ds[m][c]);
+    double tn, bn, dl;
+    outer_drift_elem<M>(a, double(th[c >> 2][c & 3]), double(bf[c >> 2][c & 3]), d, tn, bn, dl);
+    th_o[c >> 2][c & 3] = float(tn);
+    bf_o[c >> 2][c & 3] = float(bn);
+    pg_o[c >> 2][c & 3] = float(dl);
+  }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    __builtin_nontemporal_store(th_o[h], reinterpret_cast<f32x4*>(a.theta + e + 4 * h));
+    if (a.mom) __builtin_nontemporal_store(bf_o[h], reinterpret_cast<f32x4*>(a.mom + e + 4 * h));
+    if (a.pg) __builtin_nontemporal_store(pg_o[h], reinterpret_cast<f32x4*>(a.pg + e + 4 * h));
+  }
+  if (a.broadcast) {          // worker reset x_m <- x: every drift is zero again
+    const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int m = 0; m < M; ++m) __builtin_nontemporal_store(z, reinterpret_cast<u16x8*>(a.drift[m] + e));
+  }
+}
+
+template <int M>
+__global__ __launch_bounds__(256) void outer_step_drift_scalar_kernel(OuterDriftArgs a, size_t first) {
+  const size_t stride = size_t(gridDim.x) * blockDim.x;
+  for (size_t e = first + size_t(blockIdx.x) * blockDim.x + threadIdx.x; e < a.n; e += stride) {
+    double d[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) d[m] = bf16_to_f64(a.drift[m][e]);
+    double tn, bn, dl;
+    outer_drift_elem<M>(a, double(a.theta[e]), a.mom ? double(a.mom[e]) : 0.0, d, tn, bn, dl);
+    a.theta[e] = float(tn);
+    if (a.mom) a.mom[e] = float(bn);
+    if (a.pg) a.pg[e] = float(dl);
+    if (a.broadcast) {
+#pragma unroll
+      for (int m = 0; m < M; ++m) a.drift[m][e] = 0;
+    }
+  }
+}
+
+struct MergeDriftArgs {
+  float* x_rep;
+  const unsigned short* drift[ADLOCO_MAX_INSTANCES];
+  double w[ADLOCO_MAX_INSTANCES];   // b_j of the others
+  double inv_wsum;                  // 1 / (b_r + sum_j b_j)
+  size_t n_grp, n;
+};
+
+template <int S>
+__global__ __launch_bounds__(kStreamThreads) void merge_drift_vec_kernel(MergeDriftArgs a) {
+  const size_t v = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (v >= a.n_grp) return;
+  const size_t e = v * 8;
+  f32x4 x[2];
+  x[0] = ld_stream(a.x_rep + e);
+  x[1] = ld_stream(a.x_rep + e + 4);
+  u16x8 ds[S];
+#pragma unroll
+  for (int j = 0; j < S; ++j) ds[j] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(a.drift[j] + e));
+  f32x4 o[2];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    // x_merge = x_r - sum_{j != r} b_j d_j / sum_j b_j
+    double s = 0.0;
+#pragma unroll
+    for (int j = 0; j < S; ++j) s += a.w[j] * bf16_to_f64(ds[j][c]);
+    o[c >> 2][c & 3] = float(double(x[c >> 2][c & 3]) - s * a.inv_wsum);
+  }
+  __builtin_nontemporal_store(o[0], reinterpret_cast<f32x4*>(a.x_rep + e));
+  __builtin_nontemporal_store(o[1], reinterpret_cast<f32x4*>(a.x_rep + e + 4));
+}
+
+template <int S>
+__global__ __launch_bounds__(256) void merge_drift_scalar_kernel(MergeDriftArgs a, size_t first) {
+  const size_t stride = size_t(gridDim.x) * blockDim.x;
+  for (size_t e = first + size_t(blockIdx.x) * blockDim.x + threadIdx.x; e < a.n; e += stride) {
+    double s = 0.0;
+#pragma unroll
+    for (int j = 0; j < S; ++j) s += a.w[j] * bf16_to_f64(a.drift[j][e]);
+    a.x_rep[e] = float(double(a.x_rep[e]) - s * a.inv_wsum);
+  }
+}
+
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Scalar (tail / unaligned) kernels use a grid-stride loop over a bounded grid.
@@ -255,6 +426,38 @@ static hipError_t launch_merge_s(const MergeArgs& a, bool vec, int bpc, hipStrea
       hipLaunchKernelGGL(merge_scalar_kernel<S>, dim3(1), dim3(256), 0, st, a, a.n_vec * 4);
   } else {
     hipLaunchKernelGGL(merge_scalar_kernel<S>, dim3(grid_for(a.n, bpc)), dim3(256), 0, st, a,
+                       size_t(0));
+  }
+  return hipGetLastError();
+}
+
+template <int M>
+static hipError_t launch_outer_drift_m(const OuterDriftArgs& a, bool vec, int bpc, hipStream_t st) {
+  if (vec) {
+    if (a.n_grp > 0)
+      hipLaunchKernelGGL(outer_step_drift_vec_kernel<M>,
+                         dim3(unsigned((a.n_grp + kStreamThreads - 1) / kStreamThreads)),
+                         dim3(kStreamThreads), stream_lds_bytes(bpc, M + (a.mom ? 4 : 2)), st, a);
+    if (a.n_grp * 8 < a.n)
+      hipLaunchKernelGGL(outer_step_drift_scalar_kernel<M>, dim3(1), dim3(256), 0, st, a, a.n_grp * 8);
+  } else {
+    hipLaunchKernelGGL(outer_step_drift_scalar_kernel<M>, dim3(grid_for(a.n, bpc)), dim3(256), 0, st, a,
+                       size_t(0));
+  }
+  return hipGetLastError();
+}
+
+template <int S>
+static hipError_t launch_merge_drift_s(const MergeDriftArgs& a, bool vec, int bpc, hipStream_t st) {
+  if (vec) {
+    if (a.n_grp > 0)
+      hipLaunchKernelGGL(merge_drift_vec_kernel<S>,
+                         dim3(unsigned((a.n_grp + kStreamThreads - 1) / kStreamThreads)),
+                         dim3(kStreamThreads), stream_lds_bytes(bpc, S + 2), st, a);
+    if (a.n_grp * 8 < a.n)
+      hipLaunchKernelGGL(merge_drift_scalar_kernel<S>, dim3(1), dim3(256), 0, st, a, a.n_grp * 8);
+  } else {
+    hipLaunchKernelGGL(merge_drift_scalar_kernel<S>, dim3(grid_for(a.n, bpc)), dim3(256), 0, st, a,
                        size_t(0));
   }
   return hipGetLastError();
@@ -450,5 +653,139 @@ extern "C" int adloco_inner_step(adloco_ctx* ctx, float* theta, float* exp_avg, 
   prof_end(ctx, kProfInner, ev, st);
   if (e != hipSuccess)
     return fail(ctx, ADLOCO_EHIP, "inner_step launch failed: %s", hipGetErrorString(e));
+  return ADLOCO_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Entry points of the bf16-drift variants
+// ---------------------------------------------------------------------------------------------
+static bool ranges_overlap_b(const void* p, size_t pb, const void* q, size_t qb) {
+  if (!p || !q) return false;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(q);
+  return a < b + qb && b < a + pb;
+}
+
+extern "C" int adloco_pack_drift(adloco_ctx* ctx, const float* theta_outer, const float* theta_m,
+                                 uint16_t* drift_out, size_t N, void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (N == 0) return ADLOCO_OK;
+  if (!theta_outer || !theta_m || !drift_out) return fail(ctx, ADLOCO_EINVAL, "pack_drift: NULL pointer");
+  if (reinterpret_cast<uintptr_t>(drift_out) % 2)
+    return fail(ctx, ADLOCO_EINVAL, "pack_drift: drift_out not 2-byte aligned");
+  if (ranges_overlap_b(drift_out, 2 * N, theta_outer, 4 * N) || ranges_overlap_b(drift_out, 2 * N, theta_m, 4 * N))
+    return fail(ctx, ADLOCO_EINVAL, "pack_drift: drift_out overlaps an input");
+  if (N / 8 > kMaxVecPerLaunch)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "pack_drift: N = %zu exceeds one launch", N);
+  const bool vec = aligned16(theta_outer) && aligned16(theta_m) && aligned16(drift_out);
+  PackArgs a{theta_outer, theta_m, drift_out, vec ? N / 8 : 0, N};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (vec) {
+    if (a.n_grp > 0)
+      hipLaunchKernelGGL(pack_drift_vec_kernel, dim3(unsigned((a.n_grp + kStreamThreads - 1) / kStreamThreads)),
+                         dim3(kStreamThreads), stream_lds_bytes(ctx->stream_blocks_per_cu, 4), st, a);
+    if (a.n_grp * 8 < N) hipLaunchKernelGGL(pack_drift_scalar_kernel, dim3(1), dim3(256), 0, st, a, a.n_grp * 8);
+  } else {
+    hipLaunchKernelGGL(pack_drift_scalar_kernel, dim3(grid_for(N, ctx->stream_blocks_per_cu)), dim3(256), 0,
+                       st, a, size_t(0));
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, ADLOCO_EHIP, "pack_drift launch failed: %s", hipGetErrorString(e));
+  return ADLOCO_OK;
+}
+
+extern "C" int adloco_outer_step_drift(adloco_ctx* ctx, float* theta_outer, uint16_t* const* drift, int M,
+                                       size_t N, float* momentum, double lr, double mu, int nesterov,
+                                       uint32_t flags, float* pseudo_grad_out, void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (M < 1) return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: M = %d, need M >= 1", M);
+  if (M > ADLOCO_MAX_INSTANCES)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "outer_step_drift: M = %d exceeds %d", M, ADLOCO_MAX_INSTANCES);
+  if (flags & ~ADLOCO_BROADCAST) return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: unknown flags");
+  if (!(lr == lr) || !(mu == mu)) return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: lr or mu is NaN");
+  if (N == 0) return ADLOCO_OK;
+  if (!theta_outer || !drift) return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: NULL pointer");
+  if (!momentum && mu != 0.0)
+    return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: momentum is NULL but mu != 0");
+  OuterDriftArgs a{};
+  a.theta = theta_outer;
+  a.mom = momentum;
+  a.pg = pseudo_grad_out;
+  bool vec = aligned16(theta_outer) && aligned16(momentum) && aligned16(pseudo_grad_out);
+  for (int m = 0; m < M; ++m) {
+    uint16_t* p = drift[m];
+    if (!p || (reinterpret_cast<uintptr_t>(p) % 2))
+      return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: drift[%d] is NULL or not 2-byte aligned", m);
+    if (ranges_overlap_b(p, 2 * N, theta_outer, 4 * N) || ranges_overlap_b(p, 2 * N, momentum, 4 * N) ||
+        ranges_overlap_b(p, 2 * N, pseudo_grad_out, 4 * N))
+      return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: drift[%d] overlaps another argument", m);
+    for (int j = 0; j < m; ++j)
+      if ((flags & ADLOCO_BROADCAST) ? ranges_overlap_b(drift[j], 2 * N, p, 2 * N)
+                                     : (drift[j] != p && ranges_overlap_b(drift[j], 2 * N, p, 2 * N)))
+        return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: drift[%d] overlaps drift[%d]", j, m);
+    vec = vec && aligned16(p);
+    a.drift[m] = p;
+  }
+  if (ranges_overlap(momentum, theta_outer, N) || ranges_overlap(momentum, pseudo_grad_out, N) ||
+      ranges_overlap(pseudo_grad_out, theta_outer, N))
+    return fail(ctx, ADLOCO_EINVAL, "outer_step_drift: theta_outer, momentum and pseudo_grad_out overlap");
+  if (N / 8 > kMaxVecPerLaunch)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "outer_step_drift: N = %zu exceeds one launch", N);
+  a.n = N;
+  a.n_grp = vec ? N / 8 : 0;
+  a.lr = lr;
+  a.mu = mu;
+  a.inv_m = 1.0 / double(M);
+  a.nesterov = nesterov ? 1 : 0;
+  a.broadcast = (flags & ADLOCO_BROADCAST) ? 1 : 0;
+  hipError_t e;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t ev = prof_begin(ctx, st);
+  ADLOCO_DISPATCH_COUNT(M, launch_outer_drift_m, a, vec, ctx->stream_blocks_per_cu, st);
+  prof_end(ctx, kProfOuter, ev, st);
+  if (e != hipSuccess)
+    return fail(ctx, ADLOCO_EHIP, "outer_step_drift launch failed: %s", hipGetErrorString(e));
+  return ADLOCO_OK;
+}
+
+extern "C" int adloco_merge_drift(adloco_ctx* ctx, float* x_rep, const uint16_t* const* drift,
+                                  double w_rep, const double* w_others, int n_others, size_t N,
+                                  void* stream) {
+  if (!ctx) return ADLOCO_EINVAL;
+  if (n_others < 0) return fail(ctx, ADLOCO_EINVAL, "merge_drift: n_others = %d", n_others);
+  if (n_others + 1 > ADLOCO_MAX_INSTANCES)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "merge_drift: %d trainers exceed %d", n_others + 1, ADLOCO_MAX_INSTANCES);
+  if (!(w_rep > 0.0) || w_rep > 1.0e300) return fail(ctx, ADLOCO_EINVAL, "merge_drift: w_rep must be positive and finite");
+  if (n_others > 0 && (!w_others || !drift)) return fail(ctx, ADLOCO_EINVAL, "merge_drift: NULL weights or drifts");
+  MergeDriftArgs a{};
+  double wsum = w_rep;
+  for (int j = 0; j < n_others; ++j) {
+    if (!(w_others[j] > 0.0) || w_others[j] > 1.0e300)
+      return fail(ctx, ADLOCO_EINVAL, "merge_drift: w_others[%d] must be positive and finite", j);
+    a.w[j] = w_others[j];
+    wsum += w_others[j];
+  }
+  if (N == 0 || n_others == 0) return ADLOCO_OK;      // a singleton merge leaves x_r as it is
+  if (!x_rep) return fail(ctx, ADLOCO_EINVAL, "merge_drift: x_rep is NULL");
+  bool vec = aligned16(x_rep);
+  for (int j = 0; j < n_others; ++j) {
+    if (!drift[j] || (reinterpret_cast<uintptr_t>(drift[j]) % 2))
+      return fail(ctx, ADLOCO_EINVAL, "merge_drift: drift[%d] is NULL or not 2-byte aligned", j);
+    if (ranges_overlap_b(drift[j], 2 * N, x_rep, 4 * N))
+      return fail(ctx, ADLOCO_EINVAL, "merge_drift: drift[%d] overlaps x_rep", j);
+    vec = vec && aligned16(drift[j]);
+    a.drift[j] = drift[j];
+  }
+  if (N / 8 > kMaxVecPerLaunch)
+    return fail(ctx, ADLOCO_EUNSUPPORTED, "merge_drift: N = %zu exceeds one launch", N);
+  a.x_rep = x_rep;
+  a.inv_wsum = 1.0 / wsum;
+  a.n = N;
+  a.n_grp = vec ? N / 8 : 0;
+  hipError_t e;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t ev = prof_begin(ctx, st);
+  ADLOCO_DISPATCH_COUNT(n_others, launch_merge_drift_s, a, vec, ctx->stream_blocks_per_cu, st);
+  prof_end(ctx, kProfMerge, ev, st);
+  if (e != hipSuccess) return fail(ctx, ADLOCO_EHIP, "merge_drift launch failed: %s", hipGetErrorString(e));
   return ADLOCO_OK;
 }
