@@ -117,9 +117,9 @@ typedef struct {
  *     tokens with id v, so ||g_i||^2 = sum_{t,t'} [id_t = id_t'] delta_t . delta_t'.  The table
  *     gradient itself is the caller's: ADLOCO_GRAD_PROVIDED is required, grad_sum [V, d_out] is
  *     only read (by adloco_norm_test) and may be NULL in adloco_grad_stats.  T <= 8192.
- * Both kinds stream delta (and x) once; their sums run in a fixed order.  In a call that also
- * holds linear blocks their kernels run on a second stream owned by the context, forked from
- * and joined to `stream` by events inside the call ("overlap_aux" = 0 keeps them in line). */
+ * Both kinds stream delta (and x) once; their sums run in a fixed order.  A gain and a bias that are
+ * given the same delta tensor (the two vectors of a normalisation layer) are formed in one pass
+ * over it.  All kernels run on `stream`, one after the other. */
 
 /* Running accumulator of one (possibly accumulated) batch; lives in device memory, owned by
  * the caller (16 bytes, 8-byte aligned). */

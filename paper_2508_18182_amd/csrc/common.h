@@ -68,6 +68,7 @@ struct LayerDev {
   int wg_blk_start;        // first workgroup of this layer in the wgrad launch
   int sq_blk_start;        // first workgroup of this layer in the squared-norm launch
   int kind;                // ADLOCO_KIND_* (0: linear weight)
+  int delta_twin;          // vector blocks: first earlier vector block reading the same delta rows, or -1
 };
 
 // One vector (bias / gain) or embedding-table block in the launches of its kernels.
@@ -77,6 +78,8 @@ struct AuxDesc {
   int blk_start;           // first workgroup in the (sample, slab) launch: B * slabs per block
   int blk_start2;          // first workgroup in the per-slab launch (vectors: column sums)
   long long vec_off;       // vectors: offset (floats) of this block's [B, d_out] sums
+  long long vec_off_bias;  // vectors: >= 0: this gain block also forms the row sums of the bias block that
+                           // reads the same delta, stored at this offset (that block has no workgroups of its own)
   long long perm_off;      // tables: offset (ints) of this block's [B, T] token order
   long long part_off;      // tables: offset (doubles) of this block's [B, slabs] slab totals
 };
@@ -159,11 +162,12 @@ struct adloco_ctx {
   int ts_slots = 0, ts_n_split = 0, ts_n_listed = 0, ts_idx_len = 0, ts_B = -1;
   bool ts_ok = false;          // every linear block is aligned bf16 with its gradient sum formed here
   int stats_variant = 1;       // 1: tile form when eligible; 0: Gram + gradient-sum kernels
-  // the vector / table kernels (HBM-bound) run next to the kernels of the linear blocks (MFMA /
-  // L2-bound) on a second stream, forked from and joined to the caller's stream by events
+  // the vector / table kernels (HBM-bound) can run next to the kernels of the linear blocks (MFMA /
+  // L2-bound) on a second stream, forked from and joined to the caller's stream by events; measured,
+  // that buys nothing (both go through the same L2), so it is off unless "overlap_aux" asks for it
   hipStream_t side_stream = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-  int overlap_aux = 1;
+  int overlap_aux = 0;
   int wgrad_blocks = 0;        // workgroups of the wgrad launch for the uploaded table
   int table_dtype = -1;        // dtype the uploaded table was built for
   int table_inputs = -1;       // 1: the table was built by a call that reads a and delta

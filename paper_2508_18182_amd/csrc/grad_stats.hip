@@ -63,7 +63,7 @@ int upload_pointers(adloco_ctx* ctx, const std::vector<LayerDev>& tab, int which
 bool same_shape(const LayerDev& x, const LayerDev& y) {
   return x.a_stride == y.a_stride && x.delta_stride == y.delta_stride && x.d_in == y.d_in &&
          x.d_out == y.d_out && x.fast == y.fast && x.provided == y.provided && x.kind == y.kind &&
-         x.wg_blk_start == y.wg_blk_start && x.sq_blk_start == y.sq_blk_start &&
+         x.wg_blk_start == y.wg_blk_start && x.sq_blk_start == y.sq_blk_start && x.delta_twin == y.delta_twin &&
          (x.a == nullptr) == (y.a == nullptr) && (x.delta == nullptr) == (y.delta == nullptr) &&
          (x.grad_sum == nullptr) == (y.grad_sum == nullptr);
 }
@@ -129,6 +129,14 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
     }
     if (d.grad_sum && (reinterpret_cast<uintptr_t>(d.grad_sum) % 4))
       return fail(ctx, ADLOCO_EINVAL, "layer %d: grad_sum not 4-byte aligned", l);
+    L.delta_twin = -1;
+    if (need_inputs && kind == ADLOCO_KIND_VECTOR)
+      for (int j = 0; j < l; ++j)
+        if (tab[j].kind == ADLOCO_KIND_VECTOR && tab[j].delta == L.delta && tab[j].d_out == L.d_out &&
+            tab[j].delta_stride == L.delta_stride) {
+          L.delta_twin = j;
+          break;
+        }
     L.wg_blk_start = int(wg);
     L.sq_blk_start = int(sq);
     if (!provided && kind == ADLOCO_KIND_LINEAR)
@@ -227,6 +235,7 @@ int prepare_vector_table(adloco_ctx* ctx, int B, int T, hipStream_t st) {
   ++ctx->table_builds;
   const int slab = vector_table_slab();
   std::vector<AuxDesc> vec, emb;
+  std::vector<char> fused;     // per vector block: 1 = its row sums are formed by another block's workgroups
   long long vb = 0, vb2 = 0, eb = 0, voff = 0, poff = 0, partoff = 0;
   for (size_t l = 0; l < ctx->layer_tab_host.size(); ++l) {
     const LayerDev& L = ctx->layer_tab_host[l];
@@ -239,7 +248,33 @@ int prepare_vector_table(adloco_ctx* ctx, int B, int T, hipStream_t st) {
       A.blk_start = int(vb);
       A.blk_start2 = int(vb2);
       A.vec_off = voff;
-      vb += (long long)B * A.slabs;
+      A.vec_off_bias = -1;
+      // a gain (x given) and a bias (x = 1) that read the same delta rows -- the two vectors of a
+      // normalisation layer -- are formed in one pass over delta by the gain block's workgroups
+      int host = -1;
+      if (L.delta_twin >= 0) {
+        for (size_t k = 0; k < vec.size(); ++k)
+          if (vec[k].layer == L.delta_twin) host = int(k);
+      }
+      const bool pair = host >= 0 && vec[host].vec_off_bias < 0 && !fused[host] &&
+                        (ctx->layer_tab_host[vec[host].layer].a == nullptr) != (L.a == nullptr);
+      if (pair && L.a == nullptr) {
+        // this bias rides on the earlier gain block: no row-sum workgroups of its own
+        vec[host].vec_off_bias = voff;
+        fused.push_back(1);
+      } else if (pair) {
+        // this gain also serves the earlier bias block, whose workgroups are withdrawn
+        A.vec_off_bias = vec[host].vec_off;
+        const long long gone = (long long)B * vec[host].slabs;
+        for (size_t k = host + 1; k < vec.size(); ++k) vec[k].blk_start -= int(gone);
+        vb -= gone;
+        A.blk_start = int(vb);
+        fused[host] = 1;
+        fused.push_back(0);
+      } else {
+        fused.push_back(0);
+      }
+      if (!(pair && L.a == nullptr)) vb += (long long)B * A.slabs;
       vb2 += A.slabs;
       voff += (long long)B * L.d_out;
       vec.push_back(A);

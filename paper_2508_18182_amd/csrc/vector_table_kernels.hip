@@ -50,11 +50,11 @@ __device__ __forceinline__ void load8(const E* row, int c, int d, bool fast, flo
   if (fast && c + 8 <= d) {
     if constexpr (std::is_same<E, _Float16>::value) {
       typedef __attribute__((ext_vector_type(8))) _Float16 h8;
-      const h8 r = *reinterpret_cast<const h8*>(row + c);
+      const h8 r = __builtin_nontemporal_load(reinterpret_cast<const h8*>(row + c));
 #pragma unroll
       for (int j = 0; j < 8; ++j) v[j] = float(r[j]);
     } else if constexpr (sizeof(E) == 2) {
-      const u32x4 r = *reinterpret_cast<const u32x4*>(row + c);
+      const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + c));   // read once
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         v[2 * j] = __uint_as_float(r[j] << 16);
@@ -91,7 +91,9 @@ __global__ __launch_bounds__(kVtThreads) void vector_rowsum_kernel(const LayerDe
   const int c = slab * kSlab + cs * 8;
   const E* D = reinterpret_cast<const E*>(L.delta) + (long long)sample * T * L.delta_stride;
   const E* X = L.a ? reinterpret_cast<const E*>(L.a) + (long long)sample * T * L.a_stride : nullptr;
+  const bool also_bias = A.vec_off_bias >= 0;     // the bias that reads the same delta: sum_t delta as well
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float acc1[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (c < d) {
 #pragma unroll 4
     for (int t = rg; t < T; t += 8) {
@@ -102,6 +104,10 @@ __global__ __launch_bounds__(kVtThreads) void vector_rowsum_kernel(const LayerDe
         load8<E>(X + (long long)t * L.a_stride, c, d, L.fast, xv);
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = fmaf(dv[j], xv[j], acc[j]);
+        if (also_bias) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc1[j] += dv[j];
+        }
       } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] += dv[j];
@@ -117,6 +123,18 @@ __global__ __launch_bounds__(kVtThreads) void vector_rowsum_kernel(const LayerDe
 #pragma unroll
     for (int r = 0; r < 8; ++r) s += red[r][threadIdx.x];
     vec[A.vec_off + (long long)sample * d + col] = s;
+  }
+  if (also_bias) {           // same order of summation as a bias block of its own
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[rg][cs * 8 + j] = acc1[j];
+    __syncthreads();
+    if (col < d) {
+      float s = 0.f;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) s += red[r][threadIdx.x];
+      vec[A.vec_off_bias + (long long)sample * d + col] = s;
+    }
   }
 }
 

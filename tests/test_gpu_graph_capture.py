@@ -1,8 +1,8 @@
 """The device-only entry points can be captured into a HIP graph by the caller (here through
 torch.cuda.graph): after one eager call on the same layer list (descriptor tables and scratch are
 set up then; nothing is allocated or copied from the host afterwards) a captured adloco_grad_stats
--- tile statistics, the vector / table kernels forked onto the context's second stream, reductions
--- adloco_outer_step, adloco_merge and adloco_inner_step replay bit for bit.  Every replay is
+-- tile statistics, the vector / table kernels (in line, and forked onto the context's second stream
+when "overlap_aux" is set), reductions -- adloco_outer_step, adloco_merge and adloco_inner_step replay bit for bit.  Every replay is
 checked against the eager result, with eager work and synchronisations between the replays.
 (adloco_norm_test reads scalars back to the host and is not capturable.)"""
 import numpy as np
@@ -13,11 +13,13 @@ import adloco_synth as synth
 pytestmark = pytest.mark.gpu
 
 
-def test_graph_replays_match_eager():
+@pytest.mark.parametrize("overlap_aux", [0, 1])
+def test_graph_replays_match_eager(overlap_aux):
     import torch
     import paper_2508_18182_amd as A
     from gpu_util import to_dev, DEV
     ctx = A.Context(0)
+    ctx.set_tuning("overlap_aux", overlap_aux)
     B, T, d = 4, 64, 256
     lin = synth.custom_grad_stats_inputs(7700, [(d, 2 * d), (2 * d, d)], B, T, "bf16", std_delta=0.1, rho=0.3)
     aux = synth.vector_table_inputs(7701, B, T, "bf16", [(d, True), (d, False)], [(50, d)],

@@ -304,3 +304,19 @@ def test_fullsize_gpt2_vector_table_blocks(ctx):
     sq = (de.float() ** 2).sum(dim=(1, 2)).cpu().numpy()
     np.testing.assert_allclose(pl_h[99], sq, rtol=2e-3)
     assert np.all(np.abs(pl_h[98] - sq) > 1e-6 * sq)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("order", ["gain_first", "bias_first", "two_layers"])
+def test_gain_and_bias_of_one_normalisation_layer_share_their_delta(ctx, dtype, order):
+    # the gain (x = normalised input) and the bias (x = 1) of a normalisation layer are given the
+    # same delta tensor: the library forms both in one pass over it, in either order of the list, and
+    # keeps them apart from a second layer's pair and from a bias that has no partner
+    B, T, d = 3, 37, 300
+    aux = synth.vector_table_inputs(6100, B, T, dtype, [(d, True), (d, True), (d, False)], [], std_delta=0.1, rho=0.3)
+    g1, g2, lone = aux
+    b1 = dict(kind="vector", d=d, x=None, delta=g1["delta"])
+    b2 = dict(kind="vector", d=d, x=None, delta=g2["delta"])
+    entries = {"gain_first": [g1, b1, lone], "bias_first": [b1, lone, g1],
+               "two_layers": [g1, b1, b2, g2, lone]}[order]
+    _check(ctx, entries, B, T, dtype)       # norms and the gradient sums of every block
