@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libadloco.so")
 
 SOURCES = ["context.hip", "host_logic.cpp", "stream_kernels.hip", "reduce_kernels.hip",
-           "gram_kernels.hip", "gram_park_kernels.hip", "wgrad_kernels.hip", "vector_table_kernels.hip", "ip_kernels.hip", "grad_stats.hip", "round.hip", "no_alloc.hip", "probe_kernels.hip"]
+           "gram_kernels.hip", "wgrad_kernels.hip", "vector_table_kernels.hip", "ip_kernels.hip", "grad_stats.hip", "round.hip", "no_alloc.hip", "probe_kernels.hip"]
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                # packed fp32 instructions are disabled for all device code

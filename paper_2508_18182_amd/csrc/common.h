@@ -98,10 +98,6 @@ __device__ __forceinline__ void direct_load_lds16(const void* src, unsigned lds_
 // byte offset per lane: a kernel that walks along its rows bumps the base on the scalar unit and
 // keeps the lane offsets constant, so that no vector instruction is spent on addresses.
 __device__ __forceinline__ void direct_load_lds16_s(unsigned lane_off, const void* base, unsigned lds_addr) {
-#ifdef PK_NOLOAD   // timing experiment: no staging loads at all
-  (void)lane_off; (void)base; (void)lds_addr;
-  return;
-#endif
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(lane_off), "s"(base), "s"(lds_addr) : "m0");
 }
@@ -172,9 +168,6 @@ struct adloco_ctx {
   int table_dtype = -1;        // dtype the uploaded table was built for
   int table_inputs = -1;       // 1: the table was built by a call that reads a and delta
   int table_builds = 0;        // how often a shape-dependent table has been (re)built
-  // region-form Gram kernel: job lists of the persistent workgroups and the parking area
-  adloco::Scratch pk_jobs, pk_start, pk_park;
-  int pk_B = -1, pk_T = -1;    // batch shape the job lists were built for
   long long max_lin_stride = 0;  // widest row stride (elements) among the linear blocks of the table
   double* pinned = nullptr;    // 8 doubles of pinned host memory (read-back of the tests' sums)
   double* dev_scalars = nullptr;  // 4 doubles on the device (S2, ...)
@@ -242,17 +235,6 @@ int gram_tile_edge(int dtype, int variant);
 hipError_t launch_gram_bf16_dual(const GramLaunch& g, const GramJob* jobs, int n_jobs,
                                  int variant, hipStream_t st);
 hipError_t launch_gram_bf16(const GramLaunch& g, int variant, hipStream_t st);
-// Region form of the Gram kernel (256 x 256 regions, one accumulator set, the first contraction's
-// result parked in device memory): persistent workgroups walking host-built job lists.
-constexpr int kGramParkFloats = 8 * 16 * 64;    // parked floats per wave: 8 blocks x 16 registers x 64 lanes
-int gram_park_grid();
-size_t gram_park_scratch_floats();
-int gram_park_parts(int T);                     // partial sums per (layer, sample)
-bool gram_park_eligible(int T);
-void make_park_jobs(const std::vector<LayerDev>& layers, const std::vector<int>& order, int B, int T,
-                    std::vector<int2>& jobs, std::vector<int>& wg_start);
-hipError_t launch_gram_park(const GramLaunch& g, const int2* jobs, const int* wg_start, float* park,
-                            hipStream_t st);
 hipError_t launch_gram_f32(const GramLaunch& g, hipStream_t st);
 int wgrad_tile_edge(int dtype);
 int make_wgrad_x_tiles(const std::vector<LayerDev>& layers, std::vector<int4>& out,

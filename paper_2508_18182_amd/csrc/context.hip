@@ -145,8 +145,7 @@ extern "C" int adloco_destroy(adloco_ctx* ctx) {
                     &ctx->wgx_split, &ctx->wgx_part, &ctx->vec_tab, &ctx->emb_tab,
                     &ctx->aux_vec, &ctx->aux_perm, &ctx->aux_part, &ctx->ip_tab, &ctx->ip_tile_out,
                     &ctx->ip_dot, &ctx->ip_sq, &ctx->ip_part, &ctx->ip_flags, &ctx->ts_tab,
-                    &ctx->ts_part_idx, &ctx->ts_split, &ctx->ts_ptiles, &ctx->ts_out, &ctx->ts_csr,
-                    &ctx->pk_jobs, &ctx->pk_start, &ctx->pk_park};
+                    &ctx->ts_part_idx, &ctx->ts_split, &ctx->ts_ptiles, &ctx->ts_out, &ctx->ts_csr};
   for (Scratch* s : all)
     if (s->ptr) (void)hipFree(s->ptr);
   for (auto& r : ctx->prof) {

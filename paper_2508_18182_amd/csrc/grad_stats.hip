@@ -169,7 +169,6 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
   if (rc) return rc;
   ctx->layer_tab_host.clear();          // invalid until both copies are enqueued
   ctx->table_dtype = -1;
-  ctx->pk_B = ctx->pk_T = -1;           // the job lists of the region-form Gram kernel follow the table
   ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->layer_tab.ptr, tab.data(), tab.size() * sizeof(LayerDev),
                                        hipMemcpyHostToDevice, st));
   if (!order.empty())
