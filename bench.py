@@ -59,6 +59,7 @@ def parse():
                    help="comma-separated subset of: self,llama,gpt2,probe,next,cpu (default all); "
                         "'none' runs the timed region only")
     p.add_argument("--gram-variant", type=int, default=None)
+    p.add_argument("--gram-job-order", type=int, default=None)
     p.add_argument("--stream-blocks-per-cu", type=int, default=None)
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run three plain 1 GiB device copies (untimed) so that a counter profile of "
@@ -525,6 +526,8 @@ def main():
     ctx = A.Context(0)
     if args.gram_variant is not None:
         ctx.set_tuning("gram_variant", args.gram_variant)
+    if args.gram_job_order is not None:
+        ctx.set_tuning("gram_job_order", args.gram_job_order)
     if args.stream_blocks_per_cu is not None:
         ctx.set_tuning("stream_blocks_per_cu", args.stream_blocks_per_cu)
     ctx.set_tuning("profile", 1)

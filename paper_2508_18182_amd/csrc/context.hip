@@ -171,6 +171,10 @@ extern "C" int adloco_set_tuning(adloco_ctx* ctx, const char* name, int value) {
   if (!ctx || !name) return ADLOCO_EINVAL;
   std::string n(name);
   if (n == "gram_variant") ctx->gram_variant = value;
+  else if (n == "gram_job_order") {
+    ctx->gram_job_order = value;
+    ctx->job_tab_nt = -1;
+  }
   else if (n == "wgrad_variant") ctx->wgrad_variant = value;
   else if (n == "stream_blocks_per_cu") {
     if (value < 0 || value > 64) return fail(ctx, ADLOCO_EINVAL, "stream_blocks_per_cu out of range");

@@ -355,7 +355,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   if (dual) {
     if (ctx->job_tab_nt != int(nt)) {
       ++ctx->table_builds;
-      std::vector<GramJob> jobs = make_gram_jobs(int(nt));
+      std::vector<GramJob> jobs = make_gram_jobs(int(nt), ctx->gram_job_order >= 0 ? ctx->gram_job_order : (nt >= 6 ? 0 : 1));
       rc = ensure_scratch(ctx, ctx->job_tab, jobs.size() * sizeof(GramJob));
       if (rc) return rc;
       ctx->job_tab_nt = -1;

@@ -242,6 +242,33 @@ __device__ __forceinline__ void wg_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// What one wave of a group of four does on a 128 x 128 tile pair: the 32-row fragments it reads per
+// k-step (frag_block: which 32-row block of the tile; from_b: of the pair's column side) and the
+// 32 x 32 blocks it accumulates, block b = fragment fa(b) (rows) x fragment fb(b) (columns).
+struct GramShapeOff {        // off-diagonal pair: wave (wq / 2, wq % 2) owns 2 x 2 blocks
+  static constexpr int NF = 4, NB = 4;
+  __device__ static constexpr bool from_b(int f) { return f >= 2; }
+  __device__ static constexpr int frag_block(int f, int wq) { return f < 2 ? (wq >> 1) * 2 + f : (wq & 1) * 2 + (f - 2); }
+  __device__ static constexpr int fa(int b) { return b >> 1; }
+  __device__ static constexpr int fb(int b) { return 2 + (b & 1); }
+  __device__ static constexpr int row_block(int b, int wq) { return (wq >> 1) * 2 + (b >> 1); }
+  __device__ static constexpr int col_block(int b, int wq) { return (wq & 1) * 2 + (b & 1); }
+  __device__ static constexpr float weight(int) { return 1.f; }
+};
+// Pair on the diagonal, upper blocks (i <= j) of the 4 x 4 block grid:
+//   wave 0: (0,0) (0,1) (1,1)   wave 1: (0,2) (1,2) (2,2)   wave 2: (0,3) (1,3) (2,3)   wave 3: (3,3)
+template <int W> struct GramShapeDiag {
+  static constexpr int NF = W == 0 ? 2 : W == 1 ? 3 : W == 2 ? 4 : 1;
+  static constexpr int NB = W == 3 ? 1 : 3;
+  __device__ static constexpr bool from_b(int) { return false; }
+  __device__ static constexpr int frag_block(int f, int) { return W == 3 ? 3 : f; }
+  __device__ static constexpr int row_block(int b, int) { return W == 0 ? (b == 2 ? 1 : 0) : W == 3 ? 3 : b; }
+  __device__ static constexpr int col_block(int b, int) { return W == 0 ? (b == 0 ? 0 : 1) : W == 3 ? 3 : W + 1; }
+  __device__ static constexpr int fa(int b) { return W == 3 ? 0 : row_block(b, 0); }
+  __device__ static constexpr int fb(int b) { return W == 3 ? 0 : col_block(b, 0); }
+  __device__ static constexpr float weight(int b) { return row_block(b, 0) == col_block(b, 0) ? 1.f : 2.f; }
+};
+
 template <bool F16>
 __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -260,7 +287,6 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int grp = wave >> 2;                         // which tile pair of the job
-  const int wm = (wave >> 1) & 1, wn = wave & 1;     // 2x2 waves over the 128x128 tile
   const int slot_a = grp ? J.sa[1] : J.sa[0];
   const int slot_b = grp ? J.sb[1] : J.sb[0];
   const int nka = L.d_in / kKc, nk = nka + L.d_out / kKc;
@@ -326,36 +352,15 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
 
   // ---- fragment addressing
   const int r32 = lane & 31, kg = lane >> 5;
-  // byte offset within a stage of this lane's 16 bytes for every (k-step, fragment): computed once,
-  // so that a k-step spends one vector add per fragment on addresses
-  unsigned pre_a[4][2], pre_b[4][2];
-#pragma unroll
-  for (int m = 0; m < 2; ++m) {
-    const int ra = slot_a * kTile + wm * 64 + m * 32 + r32;
-    const int rb = slot_b * kTile + wn * 64 + m * 32 + r32;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      pre_a[ks][m] = unsigned(ra * ROWB + ((ks * 2 + kg) ^ swz(ra, 0)) * 16);
-      pre_b[ks][m] = unsigned(rb * ROWB + ((ks * 2 + kg) ^ swz(rb, 0)) * 16);
-    }
-  }
+  const bool diag = slot_a == slot_b;       // both sides of the tile pair are the same row block
+  const int wq = wave & 3;                  // this wave's place in its group of four
   typedef __attribute__((address_space(3))) const u32x4* lds_v4;
-  auto read_frags = [&](int st, int ks, bf16x8 (&fa)[2], bf16x8 (&fb)[2]) {
-    const unsigned stage = lds_base + unsigned(st) * st_bytes;
-#pragma unroll
-    for (int m = 0; m < 2; ++m) {
-      fa[m] = __builtin_bit_cast(bf16x8, *(lds_v4)(size_t)(stage + pre_a[ks][m]));
-      fb[m] = __builtin_bit_cast(bf16x8, *(lds_v4)(size_t)(stage + pre_b[ks][m]));
-    }
-  };
 
-  f32x16 acc_a[2][2], acc_d[2][2];
+  f32x16 acc_a[4], acc_d[4];
 #pragma unroll
-  for (int m = 0; m < 2; ++m)
+  for (int b = 0; b < 4; ++b)
 #pragma unroll
-    for (int n = 0; n < 2; ++n)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) { acc_a[m][n][j] = 0.f; acc_d[m][n][j] = 0.f; }
+    for (int j = 0; j < 16; ++j) { acc_a[b][j] = 0.f; acc_d[b][j] = 0.f; }
 
   // ---- prologue: chunks 0 .. n_st-2 in flight, chunk 0 landed for everybody (a wave issues
   // 2 * nblk loads per chunk)
@@ -370,116 +375,110 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
     if (nk > 2) wait_vmcnt<4>(); else if (nk > 1) wait_vmcnt<2>(); else wait_vmcnt<0>();
   }
   wg_barrier();
-  bf16x8 fa[2][2], fb[2][2];
-  read_frags(0, 0, fa[0], fb[0]);
 
-  // SYM: this wave's 64x64 tile lies on the diagonal of the Gram matrix, its 32x32 block (1, 0)
-  // mirrors (0, 1) and is left out
-  auto mfma4 = [&](auto sym, const bf16x8 (&a)[2], const bf16x8 (&b)[2], f32x16 (&acc)[2][2]) {
+  float s = 0.f;
+  const int blk_a = J.blk[slot_a], blk_b = J.blk[slot_b];
+  const bool whole = (blk_a + 1) * kTile <= T && (blk_b + 1) * kTile <= T;
+  // One wave's share of a tile pair.  `shape` (a GramShape) lists the 32-row fragments the wave reads
+  // per k-step and the 32 x 32 blocks it accumulates from them; every wave of the workgroup passes
+  // the same waits, barriers and loads whatever its shape.
+  auto run = [&](auto shape) {
+    typedef decltype(shape) S;
+    constexpr int NF = S::NF, NB = S::NB;
+    // byte offset within a stage of this lane's 16 bytes for every (k-step, fragment): computed
+    // once, so that a k-step spends no vector instruction on addresses
+    unsigned pre[4][NF];
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+    for (int f = 0; f < NF; ++f) {
+      const int row = (S::from_b(f) ? slot_b : slot_a) * kTile + S::frag_block(f, wq) * 32 + r32;
 #pragma unroll
-      for (int n = 0; n < 2; ++n)
-        if (!(decltype(sym)::value && m == 1 && n == 0))
-          acc[m][n] = mfma_32x32x16<F16>(a[m], b[n], acc[m][n]);
-    // issue order: MFMA, LDS read, MFMA, LDS read, ...
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      for (int ks = 0; ks < 4; ++ks) pre[ks][f] = unsigned(row * ROWB + ((ks * 2 + kg) ^ swz(row, 0)) * 16);
     }
-  };
-  int st_cur = 0, st_prev = n_st - 1;            // stages of chunk c and of chunk c-1
-  const int ahead = n_st - 1;                    // the chunk requested at chunk c's barrier is c + ahead
-  auto chunk_step = [&](auto sym, int c, f32x16 (&acc)[2][2]) {
-    const int st_next = st_cur + 1 == n_st ? 0 : st_cur + 1;
-    // k-step 0
-    read_frags(st_cur, 1, fa[1], fb[1]);
-    mfma4(sym, fa[0], fb[0], acc);
-    // k-step 1, with the barrier of this chunk in front of it
-    if (c + 1 < nk) {
-      // my share of chunk c+1 has landed (with four stages chunk c+2 may still be in flight) ...
-      if (n_st == 4 && c + 2 < nk) {
-        if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
-      } else {
-        wait_vmcnt<0>();
+    auto read_frags = [&](int st, int ks, bf16x8 (&f)[NF]) {
+      const unsigned stage = lds_base + unsigned(st) * st_bytes;
+#pragma unroll
+      for (int i = 0; i < NF; ++i) f[i] = __builtin_bit_cast(bf16x8, *(lds_v4)(size_t)(stage + pre[ks][i]));
+    };
+    auto mfmas = [&](const bf16x8 (&f)[NF], f32x16 (&acc)[4]) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) acc[b] = mfma_32x32x16<F16>(f[S::fa(b)], f[S::fb(b)], acc[b]);
+      // issue order: MFMA, LDS read, MFMA, LDS read, ...
+#pragma unroll
+      for (int i = 0; i < (NB < NF ? NB : NF); ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
-      wg_barrier();           // ... and so has everybody's; the stage of chunk c-1 is free
-      if (c + ahead < nk) issue_loads(c + ahead, st_prev);
-    }
-    read_frags(st_cur, 2, fa[0], fb[0]);
-    mfma4(sym, fa[1], fb[1], acc);
-    // k-step 2
-    read_frags(st_cur, 3, fa[1], fb[1]);
-    mfma4(sym, fa[0], fb[0], acc);
-    // k-step 3: fragments of the next chunk's first k-step (after the last chunk: a harmless
-    // re-read of this chunk, so that the reads stay interleaved with the MFMAs)
-    read_frags(c + 1 < nk ? st_next : st_cur, 0, fa[0], fb[0]);
-    mfma4(sym, fa[1], fb[1], acc);
-    st_prev = st_cur;
-    st_cur = st_next;
-  };
-  // A tile pair on the diagonal (both sides the same row block) is symmetric: its wave tile (1, 0)
-  // mirrors (0, 1), which counts twice instead.  The mirror wave only takes part in the loads and
-  // barriers.
-  const bool diag = slot_a == slot_b;
-  const bool mirror = diag && wm == 1 && wn == 0;
-  if (mirror) {
-    for (int c = 0; c < nk; ++c) {
+      if (NF > NB) __builtin_amdgcn_sched_group_barrier(0x100, NF - NB, 0);
+      if (NB > NF) __builtin_amdgcn_sched_group_barrier(0x008, NB - NF, 0);
+    };
+    bf16x8 fr[2][NF];
+    read_frags(0, 0, fr[0]);
+    int st_cur = 0, st_prev = n_st - 1;            // stages of chunk c and of chunk c-1
+    const int ahead = n_st - 1;                    // the chunk requested at chunk c's barrier is c + ahead
+    auto chunk_step = [&](int c, f32x16 (&acc)[4]) {
+      const int st_next = st_cur + 1 == n_st ? 0 : st_cur + 1;
+      // k-step 0
+      read_frags(st_cur, 1, fr[1]);
+      mfmas(fr[0], acc);
+      // k-step 1, with the barrier of this chunk in front of it
       if (c + 1 < nk) {
+        // my share of chunk c+1 has landed (with four stages chunk c+2 may still be in flight) ...
         if (n_st == 4 && c + 2 < nk) {
           if (nblk == 2) wait_vmcnt<4>(); else wait_vmcnt<2>();
         } else {
           wait_vmcnt<0>();
         }
-        wg_barrier();
+        wg_barrier();           // ... and so has everybody's; the stage of chunk c-1 is free
         if (c + ahead < nk) issue_loads(c + ahead, st_prev);
       }
+      read_frags(st_cur, 2, fr[0]);
+      mfmas(fr[1], acc);
+      // k-step 2
+      read_frags(st_cur, 3, fr[1]);
+      mfmas(fr[0], acc);
+      // k-step 3: fragments of the next chunk's first k-step (after the last chunk: a harmless
+      // re-read of this chunk, so that the reads stay interleaved with the MFMAs)
+      read_frags(c + 1 < nk ? st_next : st_cur, 0, fr[0]);
+      mfmas(fr[1], acc);
       st_prev = st_cur;
-      st_cur = st_cur + 1 == n_st ? 0 : st_cur + 1;
-    }
-  } else if (diag && wm == wn) {
+      st_cur = st_next;
+    };
     int c = 0;
-    for (; c < nka; ++c) chunk_step(std::true_type{}, c, acc_a);
-    for (; c < nk; ++c) chunk_step(std::true_type{}, c, acc_d);
-  } else {
-    int c = 0;
-    for (; c < nka; ++c) chunk_step(std::false_type{}, c, acc_a);
-    for (; c < nk; ++c) chunk_step(std::false_type{}, c, acc_d);
-  }
+    for (; c < nka; ++c) chunk_step(c, acc_a);
+    for (; c < nk; ++c) chunk_step(c, acc_d);
 
-  // ---- epilogue: < A A^T , D D^T > over this wave's 64x64 part, masked beyond T
-  const float w = (grp ? J.w[1] : J.w[0]) * ((diag && wm == 0 && wn == 1) ? 2.f : 1.f);
-  float s = 0.f;
-  const int blk_a = J.blk[slot_a], blk_b = J.blk[slot_b];
-  // in a wave tile on the diagonal block (0, 1) stands for (1, 0) as well (whose accumulators stayed 0)
-  const float w01 = (diag && wm == wn) ? 2.f : 1.f;
-  if ((blk_a + 1) * kTile <= T && (blk_b + 1) * kTile <= T) {
+    // ---- < A A^T , D D^T > over this wave's blocks, masked beyond T
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+    for (int b = 0; b < NB; ++b) {
+      float sb = 0.f;
+      if (whole) {
 #pragma unroll
-      for (int n = 0; n < 2; ++n) {
-        float sb = 0.f;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) sb += acc_a[m][n][j] * acc_d[m][n][j];
-        s += (m == 0 && n == 1) ? sb * w01 : sb;
-      }
-  } else {
-#pragma unroll
-    for (int m = 0; m < 2; ++m)
-#pragma unroll
-      for (int n = 0; n < 2; ++n) {
-        const int col = blk_b * kTile + wn * 64 + n * 32 + r32;
-        float sb = 0.f;
+        for (int j = 0; j < 16; ++j) sb += acc_a[b][j] * acc_d[b][j];
+      } else {
+        const int col = blk_b * kTile + S::col_block(b, wq) * 32 + r32;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-          const int row = blk_a * kTile + wm * 64 + m * 32 + (j >> 2) * 8 + kg * 4 + (j & 3);
-          if (row < T && col < T) sb += acc_a[m][n][j] * acc_d[m][n][j];
+          const int row = blk_a * kTile + S::row_block(b, wq) * 32 + (j >> 2) * 8 + kg * 4 + (j & 3);
+          if (row < T && col < T) sb += acc_a[b][j] * acc_d[b][j];
         }
-        s += (m == 0 && n == 1) ? sb * w01 : sb;
       }
+      s += sb * S::weight(b);
+    }
+  };
+  // An off-diagonal tile pair: 2 x 2 waves of 64 x 64.  A tile pair on the diagonal is symmetric: its
+  // ten upper 32 x 32 blocks (i <= j) are dealt 3, 3, 3, 1 to the four waves, blocks off the diagonal
+  // count twice.
+  if (!diag) {
+    run(GramShapeOff{});
+  } else {
+    switch (wq) {
+      case 0: run(GramShapeDiag<0>{}); break;
+      case 1: run(GramShapeDiag<1>{}); break;
+      case 2: run(GramShapeDiag<2>{}); break;
+      default: run(GramShapeDiag<3>{}); break;
+    }
   }
-  s = wave_sum_f32(s) * w;
+  s = wave_sum_f32(s) * (grp ? J.w[1] : J.w[0]);
   __syncthreads();                                    // all fragment reads are over
   float* red = reinterpret_cast<float*>(lds);
   if (lane == 0) red[wave] = s;
@@ -586,11 +585,13 @@ hipError_t launch_gram_bf16(const GramLaunch& l, int /*variant*/, hipStream_t st
   return hipGetLastError();
 }
 
-// Jobs of the dual-tile kernel for nt row blocks: tile pairs (p,q), p <= q, taken two at a time
-// so that the two share a block.  Along a row p consecutive pairs (p,q),(p,q+1) share block p;
-// a row's leftover (p, nt-1) is combined with another row's leftover, which shares block nt-1.
-std::vector<GramJob> make_gram_jobs(int nt) {
-  std::vector<GramJob> jobs;
+// Jobs of the dual-tile kernel for nt row blocks: tile pairs (p,q), p <= q, taken two at a time.
+// A pair on the diagonal costs three MFMAs per wave and k-step, any other four, and a job lasts as
+// long as its slower pair: so diagonal pairs go together, (p,p) with (p+1,p+1) (two blocks to
+// stage).  Off the diagonal, consecutive pairs (p,q),(p,q+1) of a row share block p; a row's
+// leftover (p, nt-1) is combined with another row's leftover, which shares block nt-1.
+std::vector<GramJob> make_gram_jobs(int nt, int order) {
+  std::vector<GramJob> jobs, diag_jobs;
   auto make = [&](int p0, int q0, int p1, int q1) {
     GramJob j{};
     int blocks[4] = {p0, q0, p1 < 0 ? p0 : p1, q1 < 0 ? q0 : q1};
@@ -610,16 +611,40 @@ std::vector<GramJob> make_gram_jobs(int nt) {
     j.w[1] = p1 < 0 ? 0.f : (p1 == q1 ? 1.f : 2.f);
     jobs.push_back(j);
   };
+  for (int d0 = 0; d0 + 1 < nt; d0 += 2) make(d0, d0, d0 + 1, d0 + 1);
+  diag_jobs.swap(jobs);
   std::vector<int> left;
   for (int p = 0; p < nt; ++p) {
-    int q = p;
+    int q = p + 1;
     for (; q + 1 < nt; q += 2) make(p, q, p, q + 1);
     if (q == nt - 1) left.push_back(p);
   }
   size_t i = 0;
   for (; i + 1 < left.size(); i += 2) make(left[i], nt - 1, left[i + 1], nt - 1);
-  if (i < left.size()) make(left[i], nt - 1, -1, -1);
-  return jobs;
+  if (i < left.size()) {
+    // one off-diagonal pair is left: it takes the last diagonal pair along when their number is odd
+    if (nt % 2) make(left[i], nt - 1, nt - 1, nt - 1); else make(left[i], nt - 1, -1, -1);
+  } else if (nt % 2) {
+    make(nt - 1, nt - 1, -1, -1);
+  }
+  // where the (shorter) jobs of two diagonal pairs go among the others
+  std::vector<GramJob> out;
+  if (order == 1) {                       // last
+    out = jobs;
+    out.insert(out.end(), diag_jobs.begin(), diag_jobs.end());
+  } else if (order == 2) {                // spread evenly
+    const size_t n = jobs.size(), m = diag_jobs.size();
+    size_t di = 0;
+    for (size_t i = 0; i < n; ++i) {
+      while (di < m && di * n <= i * m) out.push_back(diag_jobs[di++]);
+      out.push_back(jobs[i]);
+    }
+    while (di < m) out.push_back(diag_jobs[di++]);
+  } else {                                // first
+    out = diag_jobs;
+    out.insert(out.end(), jobs.begin(), jobs.end());
+  }
+  return out;
 }
 
 hipError_t launch_gram_bf16_dual(const GramLaunch& l, const GramJob* jobs, int n_jobs,
