@@ -10,6 +10,8 @@
 // tile of D D^T over d_out in two sets of MFMA accumulators that share one register layout,
 // multiplies them element-wise in registers and reduces to one float.
 #include "common.h"
+#include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 namespace adloco {
@@ -627,7 +629,9 @@ std::vector<GramJob> make_gram_jobs(int nt, int order) {
   } else if (nt % 2) {
     make(nt - 1, nt - 1, -1, -1);
   }
-  // where the (shorter) jobs of two diagonal pairs go among the others
+  // Where the (shorter) jobs of two diagonal pairs go among the others.  First: they run a little
+  // ahead of the unit's other jobs and touch all of its row blocks, which the others then find in
+  // the cache (the order of the off-diagonal jobs among themselves made no difference).
   std::vector<GramJob> out;
   if (order == 1) {                       // last
     out = jobs;
