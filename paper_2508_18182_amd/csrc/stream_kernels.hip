@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void inner_step_scalar_kernel(InnerArgs a, siz
 // Outer model and momentum stay fp32.  Eight parameters per thread: two 16-byte loads of every fp32
 // stream, one of every drift.
 // ---------------------------------------------------------------------------------------
-typedef unsigned short __attribute__((ext_vector_type(8))) u16x8;
+typedef unsigned short __attribute__((ext_vector_type(4))) u16x4;
 
 // fp32 -> bf16, round to nearest, ties to even (NaN keeps a quiet bit)
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
@@ -235,27 +235,36 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
 __device__ __forceinline__ double bf16_to_f64(unsigned short h) {
   return double(__uint_as_float(unsigned(h) << 16));
 }
+// A wave handles 512 consecutive parameters as two halves of 256: lane l takes elements 4 l .. 4 l + 3
+// of each half, so that every load and store instruction of the wave covers one contiguous run (1 KiB
+// of an fp32 vector, 512 bytes of a bf16 one) and no cache line is written in pieces.
+__device__ __forceinline__ size_t drift_elem0(size_t v, int half) {
+  return (v >> 6) * 512 + size_t(half) * 256 + (v & 63) * 4;
+}
 
 struct PackArgs {
   const float* theta;
   const float* inst;
   unsigned short* out;
-  size_t n_grp, n;      // groups of eight handled by the vector kernel; total elements
+  size_t n_grp, n;      // groups of eight handled by the vector kernel (a multiple of 64); total elements
 };
 
 __global__ __launch_bounds__(kStreamThreads) void pack_drift_vec_kernel(PackArgs a) {
   const size_t v = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
   if (v >= a.n_grp) return;
-  const size_t e = v * 8;
-  const f32x4 t0 = ld_stream(a.theta + e), t1 = ld_stream(a.theta + e + 4);
-  const f32x4 x0 = ld_stream(a.inst + e), x1 = ld_stream(a.inst + e + 4);
-  u16x8 o;
+  f32x4 t[2], x[2];
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    o[c] = f32_to_bf16_rne(t0[c] - x0[c]);        // the fp32 difference, then one rounding to bf16
-    o[4 + c] = f32_to_bf16_rne(t1[c] - x1[c]);
+  for (int h = 0; h < 2; ++h) {
+    t[h] = ld_stream(a.theta + drift_elem0(v, h));
+    x[h] = ld_stream(a.inst + drift_elem0(v, h));
   }
-  __builtin_nontemporal_store(o, reinterpret_cast<u16x8*>(a.out + e));
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    u16x4 o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o[c] = f32_to_bf16_rne(t[h][c] - x[h][c]);   // fp32 difference, one rounding
+    __builtin_nontemporal_store(o, reinterpret_cast<u16x4*>(a.out + drift_elem0(v, h)));
+  }
 }
 __global__ __launch_bounds__(256) void pack_drift_scalar_kernel(PackArgs a, size_t first) {
   const size_t stride = size_t(gridDim.x) * blockDim.x;
@@ -290,39 +299,39 @@ template <int M>
 __global__ __launch_bounds__(kStreamThreads) void outer_step_drift_vec_kernel(OuterDriftArgs a) {
   const size_t v = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
   if (v >= a.n_grp) return;
-  const size_t e = v * 8;
   f32x4 th[2], bf[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  th[0] = ld_stream(a.theta + e);
-  th[1] = ld_stream(a.theta + e + 4);
-  if (a.mom) {
-    bf[0] = ld_stream(a.mom + e);
-    bf[1] = ld_stream(a.mom + e + 4);
-  }
-  u16x8 ds[M];
+  u16x4 ds[2][M];
 #pragma unroll
-  for (int m = 0; m < M; ++m) ds[m] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(a.drift[m] + e));
-  f32x4 th_o[2], bf_o[2], pg_o[2];
+  for (int h = 0; h < 2; ++h) {
+    const size_t e = drift_elem0(v, h);
+    th[h] = ld_stream(a.theta + e);
+    if (a.mom) bf[h] = ld_stream(a.mom + e);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    double d[M];
-#pragma unroll
-    for (int m = 0; m < M; ++m) d[m] = bf16_to_f64(ds[m][c]);
-    double tn, bn, dl;
-    outer_drift_elem<M>(a, double(th[c >> 2][c & 3]), double(bf[c >> 2][c & 3]), d, tn, bn, dl);
-    th_o[c >> 2][c & 3] = float(tn);
-    bf_o[c >> 2][c & 3] = float(bn);
-    pg_o[c >> 2][c & 3] = float(dl);
+    for (int m = 0; m < M; ++m) ds[h][m] = __builtin_nontemporal_load(reinterpret_cast<const u16x4*>(a.drift[m] + e));
   }
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    __builtin_nontemporal_store(th_o[h], reinterpret_cast<f32x4*>(a.theta + e + 4 * h));
-    if (a.mom) __builtin_nontemporal_store(bf_o[h], reinterpret_cast<f32x4*>(a.mom + e + 4 * h));
-    if (a.pg) __builtin_nontemporal_store(pg_o[h], reinterpret_cast<f32x4*>(a.pg + e + 4 * h));
-  }
-  if (a.broadcast) {          // worker reset x_m <- x: every drift is zero again
-    const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    const size_t e = drift_elem0(v, h);
+    f32x4 th_o, bf_o, pg_o;
 #pragma unroll
-    for (int m = 0; m < M; ++m) __builtin_nontemporal_store(z, reinterpret_cast<u16x8*>(a.drift[m] + e));
+    for (int c = 0; c < 4; ++c) {
+      double d[M];
+#pragma unroll
+      for (int m = 0; m < M; ++m) d[m] = bf16_to_f64(ds[h][m][c]);
+      double tn, bn, dl;
+      outer_drift_elem<M>(a, double(th[h][c]), double(bf[h][c]), d, tn, bn, dl);
+      th_o[c] = float(tn);
+      bf_o[c] = float(bn);
+      pg_o[c] = float(dl);
+    }
+    __builtin_nontemporal_store(th_o, reinterpret_cast<f32x4*>(a.theta + e));
+    if (a.mom) __builtin_nontemporal_store(bf_o, reinterpret_cast<f32x4*>(a.mom + e));
+    if (a.pg) __builtin_nontemporal_store(pg_o, reinterpret_cast<f32x4*>(a.pg + e));
+    if (a.broadcast) {          // worker reset x_m <- x: every drift is zero again
+      const u16x4 z = {0, 0, 0, 0};
+#pragma unroll
+      for (int m = 0; m < M; ++m) __builtin_nontemporal_store(z, reinterpret_cast<u16x4*>(a.drift[m] + e));
+    }
   }
 }
 
@@ -357,24 +366,28 @@ template <int S>
 __global__ __launch_bounds__(kStreamThreads) void merge_drift_vec_kernel(MergeDriftArgs a) {
   const size_t v = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
   if (v >= a.n_grp) return;
-  const size_t e = v * 8;
   f32x4 x[2];
-  x[0] = ld_stream(a.x_rep + e);
-  x[1] = ld_stream(a.x_rep + e + 4);
-  u16x8 ds[S];
+  u16x4 ds[2][S];
 #pragma unroll
-  for (int j = 0; j < S; ++j) ds[j] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(a.drift[j] + e));
-  f32x4 o[2];
+  for (int h = 0; h < 2; ++h) {
+    const size_t e = drift_elem0(v, h);
+    x[h] = ld_stream(a.x_rep + e);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    // x_merge = x_r - sum_{j != r} b_j d_j / sum_j b_j
-    double s = 0.0;
-#pragma unroll
-    for (int j = 0; j < S; ++j) s += a.w[j] * bf16_to_f64(ds[j][c]);
-    o[c >> 2][c & 3] = float(double(x[c >> 2][c & 3]) - s * a.inv_wsum);
+    for (int j = 0; j < S; ++j) ds[h][j] = __builtin_nontemporal_load(reinterpret_cast<const u16x4*>(a.drift[j] + e));
   }
-  __builtin_nontemporal_store(o[0], reinterpret_cast<f32x4*>(a.x_rep + e));
-  __builtin_nontemporal_store(o[1], reinterpret_cast<f32x4*>(a.x_rep + e + 4));
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    f32x4 o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      // x_merge = x_r - sum_{j != r} b_j d_j / sum_j b_j
+      double s = 0.0;
+#pragma unroll
+      for (int j = 0; j < S; ++j) s += a.w[j] * bf16_to_f64(ds[h][j][c]);
+      o[c] = float(double(x[h][c]) - s * a.inv_wsum);
+    }
+    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(a.x_rep + drift_elem0(v, h)));
+  }
 }
 
 template <int S>
@@ -677,7 +690,7 @@ extern "C" int adloco_pack_drift(adloco_ctx* ctx, const float* theta_outer, cons
   if (N / 8 > kMaxVecPerLaunch)
     return fail(ctx, ADLOCO_EUNSUPPORTED, "pack_drift: N = %zu exceeds one launch", N);
   const bool vec = aligned16(theta_outer) && aligned16(theta_m) && aligned16(drift_out);
-  PackArgs a{theta_outer, theta_m, drift_out, vec ? N / 8 : 0, N};
+  PackArgs a{theta_outer, theta_m, drift_out, vec ? N / 512 * 64 : 0, N};
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (vec) {
     if (a.n_grp > 0)
@@ -731,7 +744,7 @@ extern "C" int adloco_outer_step_drift(adloco_ctx* ctx, float* theta_outer, uint
   if (N / 8 > kMaxVecPerLaunch)
     return fail(ctx, ADLOCO_EUNSUPPORTED, "outer_step_drift: N = %zu exceeds one launch", N);
   a.n = N;
-  a.n_grp = vec ? N / 8 : 0;
+  a.n_grp = vec ? N / 512 * 64 : 0;     // whole waves of 512 parameters; the rest goes to the scalar kernel
   a.lr = lr;
   a.mu = mu;
   a.inv_m = 1.0 / double(M);
@@ -780,7 +793,7 @@ extern "C" int adloco_merge_drift(adloco_ctx* ctx, float* x_rep, const uint16_t*
   a.x_rep = x_rep;
   a.inv_wsum = 1.0 / wsum;
   a.n = N;
-  a.n_grp = vec ? N / 8 : 0;
+  a.n_grp = vec ? N / 512 * 64 : 0;
   hipError_t e;
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipEvent_t ev = prof_begin(ctx, st);
