@@ -150,6 +150,9 @@ typedef struct {
  * bf16 and fp16 inputs are multiplied exactly and accumulated in fp32 (MFMA); fp32 inputs in
  * fp32.  16-bit rows must be 2-byte aligned; 16-byte aligned rows with d % 8 == 0 take the fast
  * path, anything else a slower guarded path (same results).
+ * Linear blocks that are handed the SAME activation tensor (same address, stride and d_in) with the same
+ * d_out -- q / k / v or gate / up of a transformer block -- share their a_i a_i^T: the Gram kernel forms
+ * it once for the group (same results up to fp32 summation order).
  * Two routes give the norms of the linear blocks.  With ADLOCO_GRAD_PROVIDED (the framework's
  * backward already holds the weight gradient) only the Gram contractions run.  When grad_sum
  * is formed here for every linear block and all of them are 16-byte aligned bf16 / fp16 with

@@ -69,6 +69,8 @@ struct LayerDev {
   int sq_blk_start;        // first workgroup of this layer in the squared-norm launch
   int kind;                // ADLOCO_KIND_* (0: linear weight)
   int delta_twin;          // vector blocks: first earlier vector block reading the same delta rows, or -1
+  int a_twin;              // linear blocks: first earlier linear block reading the same activation rows
+                           // (same a, stride, d_in) with the same d_out and delta stride, or -1
 };
 
 // One vector (bias / gain) or embedding-table block in the launches of its kernels.
@@ -101,6 +103,14 @@ __device__ __forceinline__ void direct_load_lds16_s(unsigned lane_off, const voi
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(lane_off), "s"(base), "s"(lds_addr) : "m0");
 }
+// A wave-uniform pointer that the compiler may hold in vector registers, moved to scalar registers
+// (the direct loads above take their base address there).
+template <typename P> __device__ __forceinline__ const P* uniform_ptr(const P* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane(unsigned(v));
+  const unsigned hi = __builtin_amdgcn_readfirstlane(unsigned(v >> 32));
+  return reinterpret_cast<const P*>((unsigned long long)hi << 32 | lo);
+}
 // LDS byte address of a pointer into the workgroup's dynamic shared memory, as a scalar.
 __device__ __forceinline__ unsigned lds_address(const void* p) {
   return __builtin_amdgcn_readfirstlane(
@@ -123,6 +133,10 @@ struct adloco_ctx {
   adloco::Scratch red_f64;     // double partial sums of the streaming reductions
   adloco::Scratch sample_f64;  // double [B] per-sample totals
   adloco::Scratch order_tab;   // int [n_layers] launch order (heaviest first)
+  adloco::Scratch group_tab;   // GramGroup[n_groups], int[n_groups] launch order of the groups; then, at
+                               // single_off, the same with every linear layer in a group of its own
+  int n_groups = 0;
+  size_t single_off = 0;
   std::vector<adloco::LayerDev> layer_tab_host;  // last uploaded copy
   std::vector<int> order_host;
   adloco::Scratch job_tab;     // GramJob[] of the dual-tile Gram kernel
@@ -225,6 +239,14 @@ struct GramLaunch {
   int tile;                 // T-tile edge used by the kernel
   int dtype = ADLOCO_BF16;  // element type of a and delta
 };
+// Linear layers that read the same activation tensor (q / k / v, gate / up of a transformer block):
+// their A A^T is one and the same, so the dual-tile Gram kernel forms it once per group and runs the
+// members' delta delta^T contractions against it one after the other.
+constexpr int kGramGroupMax = 4;
+struct GramGroup {
+  int n;                      // members, 1 .. kGramGroupMax
+  int layer[kGramGroupMax];   // indices into the layer table; all share a, d_in, d_out and the strides
+};
 // One workgroup of the dual-tile Gram kernel: up to two 128x128 tile pairs (A-block, B-block)
 // drawn from at most three distinct 128-row blocks.
 struct GramJob {
@@ -235,8 +257,11 @@ struct GramJob {
 };
 std::vector<GramJob> make_gram_jobs(int nt, int order);
 int gram_tile_edge(int dtype, int variant);
-hipError_t launch_gram_bf16_dual(const GramLaunch& g, const GramJob* jobs, int n_jobs,
-                                 int variant, hipStream_t st);
+// g.order: launch order of GROUP indices; g.n_layers: number of groups; g.n_pairs: partial sums per
+// (layer, sample) = gram_dual_parts(n_jobs)
+hipError_t launch_gram_bf16_dual(const GramLaunch& g, const GramGroup* groups, const GramJob* jobs,
+                                 int n_jobs, int variant, hipStream_t st);
+int gram_dual_parts(int n_jobs);
 hipError_t launch_gram_bf16(const GramLaunch& g, int variant, hipStream_t st);
 hipError_t launch_gram_f32(const GramLaunch& g, hipStream_t st);
 int wgrad_tile_edge(int dtype);

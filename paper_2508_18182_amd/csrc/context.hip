@@ -141,7 +141,7 @@ extern "C" int adloco_destroy(adloco_ctx* ctx) {
   (void)hipSetDevice(ctx->device);
   (void)hipDeviceSynchronize();
   Scratch* all[] = {&ctx->partials, &ctx->layer_tab, &ctx->red_f64, &ctx->sample_f64,
-                    &ctx->order_tab, &ctx->job_tab, &ctx->wgx_tab,
+                    &ctx->order_tab, &ctx->group_tab, &ctx->job_tab, &ctx->wgx_tab,
                     &ctx->wgx_split, &ctx->wgx_part, &ctx->vec_tab, &ctx->emb_tab,
                     &ctx->aux_vec, &ctx->aux_perm, &ctx->aux_part, &ctx->ip_tab, &ctx->ip_tile_out,
                     &ctx->ip_dot, &ctx->ip_sq, &ctx->ip_part, &ctx->ip_flags, &ctx->ts_tab,

@@ -63,7 +63,7 @@ int upload_pointers(adloco_ctx* ctx, const std::vector<LayerDev>& tab, int which
 bool same_shape(const LayerDev& x, const LayerDev& y) {
   return x.a_stride == y.a_stride && x.delta_stride == y.delta_stride && x.d_in == y.d_in &&
          x.d_out == y.d_out && x.fast == y.fast && x.provided == y.provided && x.kind == y.kind &&
-         x.wg_blk_start == y.wg_blk_start && x.sq_blk_start == y.sq_blk_start && x.delta_twin == y.delta_twin &&
+         x.wg_blk_start == y.wg_blk_start && x.sq_blk_start == y.sq_blk_start && x.delta_twin == y.delta_twin && x.a_twin == y.a_twin &&
          (x.a == nullptr) == (y.a == nullptr) && (x.delta == nullptr) == (y.delta == nullptr) &&
          (x.grad_sum == nullptr) == (y.grad_sum == nullptr);
 }
@@ -129,6 +129,14 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
     }
     if (d.grad_sum && (reinterpret_cast<uintptr_t>(d.grad_sum) % 4))
       return fail(ctx, ADLOCO_EINVAL, "layer %d: grad_sum not 4-byte aligned", l);
+    L.a_twin = -1;
+    if (need_inputs && kind == ADLOCO_KIND_LINEAR && d.a)
+      for (int j = 0; j < l; ++j)
+        if (tab[j].kind == ADLOCO_KIND_LINEAR && tab[j].a == L.a && tab[j].a_stride == L.a_stride &&
+            tab[j].d_in == L.d_in && tab[j].d_out == L.d_out && tab[j].delta_stride == L.delta_stride) {
+          L.a_twin = j;
+          break;
+        }
     L.delta_twin = -1;
     if (need_inputs && kind == ADLOCO_KIND_VECTOR)
       for (int j = 0; j < l; ++j)
@@ -189,6 +197,60 @@ int prepare_tables(adloco_ctx* ctx, const adloco_linear_desc* layers, int n_laye
     if (L.kind == ADLOCO_KIND_LINEAR) fast = fast && (L.provided || L.fast);
   ctx->all_fast = fast;
   ctx->n_linear = int(order.size());
+  {
+    // groups of linear layers that read the same activation tensor, for the dual-tile Gram kernel
+    std::vector<GramGroup> groups;
+    std::vector<int> group_of(tab.size(), -1);
+    for (int l = 0; l < n_layers; ++l) {
+      if (tab[l].kind != ADLOCO_KIND_LINEAR) continue;
+      const int t = tab[l].a_twin;
+      if (t >= 0 && group_of[t] >= 0 && groups[group_of[t]].n < kGramGroupMax && tab[t].fast == tab[l].fast) {
+        GramGroup& G = groups[group_of[t]];
+        G.layer[G.n++] = l;
+        group_of[l] = group_of[t];
+      } else {
+        GramGroup G{};
+        G.n = 1;
+        G.layer[0] = l;
+        group_of[l] = int(groups.size());
+        groups.push_back(G);
+      }
+    }
+    // a second table with every layer in a group of its own, for sequences with a ragged last tile
+    std::vector<GramGroup> single;
+    for (int l : order) {
+      GramGroup G{};
+      G.n = 1;
+      G.layer[0] = l;
+      single.push_back(G);
+    }
+    std::vector<int> gorder(groups.size()), sorder(single.size());
+    std::iota(gorder.begin(), gorder.end(), 0);
+    std::iota(sorder.begin(), sorder.end(), 0);       // `order` is sorted already
+    auto weight = [&](int gi) {
+      const GramGroup& G = groups[gi];
+      return (long long)tab[G.layer[0]].d_in + (long long)G.n * tab[G.layer[0]].d_out;
+    };
+    std::stable_sort(gorder.begin(), gorder.end(), [&](int x, int y) { return weight(x) > weight(y); });
+    // layout: groups | their order | singleton groups | their order
+    std::vector<char> blob;
+    auto append = [&](const void* p, size_t n) {
+      const char* c = static_cast<const char*>(p);
+      blob.insert(blob.end(), c, c + n);
+    };
+    append(groups.data(), groups.size() * sizeof(GramGroup));
+    append(gorder.data(), gorder.size() * sizeof(int));
+    ctx->single_off = blob.size();
+    append(single.data(), single.size() * sizeof(GramGroup));
+    append(sorder.data(), sorder.size() * sizeof(int));
+    rc = ensure_scratch(ctx, ctx->group_tab, std::max<size_t>(blob.size(), 16));
+    if (rc) return rc;
+    if (!blob.empty()) {
+      ADLOCO_HIP_CHECK(ctx, hipMemcpyAsync(ctx->group_tab.ptr, blob.data(), blob.size(), hipMemcpyHostToDevice, st));
+      ADLOCO_HIP_CHECK(ctx, hipStreamSynchronize(st));
+    }
+    ctx->n_groups = int(groups.size());
+  }
   ctx->aux_B = ctx->aux_T = -1;         // the vector / table descriptor lists follow the table
   ctx->ip_B = ctx->ip_T = -1;           // and so does the inner-product tile table
   ctx->ts_B = -1;                       // and the statistics tile table
@@ -365,7 +427,7 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
       ctx->job_tab_nt = int(nt);
       ctx->job_tab_n = int(jobs.size());
     }
-    n_pairs = ctx->job_tab_n;
+    n_pairs = gram_dual_parts(ctx->job_tab_n);
   }
   const long long n_part = (long long)n_layers * B * n_pairs;
   if (n_pairs > 0x7fffffffLL || n_part > (1LL << 40))
@@ -487,9 +549,18 @@ extern "C" int adloco_grad_stats(adloco_ctx* ctx, const adloco_linear_desc* laye
   ev = (!tile_form && !sum_only && ctx->n_linear > 0) ? prof_begin(ctx, st) : nullptr;
   if (tile_form || sum_only || ctx->n_linear == 0)
     ;
-  else if (dual)
-    e = launch_gram_bf16_dual(g, static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n,
-                              ctx->gram_variant, st);
+  else if (dual) {
+    // the dual-tile kernel walks groups of layers that share their activations (A A^T once per group)
+    // when some do and no tile is ragged, else every layer by itself
+    GramLaunch gd = g;
+    const bool grouped = ctx->n_groups < ctx->n_linear && T % tile == 0;
+    const char* base = static_cast<const char*>(ctx->group_tab.ptr) + (grouped ? 0 : ctx->single_off);
+    gd.n_layers = grouped ? ctx->n_groups : ctx->n_linear;
+    gd.order = reinterpret_cast<const int*>(base + size_t(gd.n_layers) * sizeof(GramGroup));
+    e = launch_gram_bf16_dual(gd, reinterpret_cast<const GramGroup*>(base),
+                              static_cast<const GramJob*>(ctx->job_tab.ptr), ctx->job_tab_n,
+                              grouped ? kGramGroupMax : 1, st);
+  }
   else if (is_16bit(dtype))
     e = launch_gram_bf16(g, ctx->gram_variant, st);
   else

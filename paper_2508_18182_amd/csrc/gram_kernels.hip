@@ -228,10 +228,11 @@ constexpr int kDualLds = kDualStages * kDualStage;            // 144 KiB
 
 struct GramDualArgs {
   const LayerDev* layers;
-  const int* order;
+  const GramGroup* groups;
+  const int* order;         // launch order of group indices
   const GramJob* jobs;
-  float* partials;
-  int n_layers, B, T, n_jobs, units_padded;
+  float* partials;          // [layer][sample][n_jobs * 8]: one partial sum per job and wave
+  int n_groups, B, T, n_jobs, units_padded;
 };
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
@@ -271,7 +272,8 @@ template <int W> struct GramShapeDiag {
   __device__ static constexpr float weight(int b) { return row_block(b, 0) == col_block(b, 0) ? 1.f : 2.f; }
 };
 
-template <bool F16>
+// MAXM: the largest group of layers sharing their activation tensor in the launch (1: none share)
+template <bool F16, int MAXM>
 __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int bid = blockIdx.x;
@@ -279,10 +281,13 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   const int slot = bid / kNumXcd;
   const int job = slot % g.n_jobs;
   const int u = (slot / g.n_jobs) * kNumXcd + xcd;
-  if (u >= g.n_layers * g.B) return;
-  const int layer = g.order[u / g.B];
+  if (u >= g.n_groups * g.B) return;
+  // the unit: one sample of a group of layers that share their activation tensor (mostly a group of one)
+  const int gi = __builtin_amdgcn_readfirstlane(g.order[u / g.B]);
+  const GramGroup G = g.groups[gi];
+  const int n_mem = MAXM == 1 ? 1 : __builtin_amdgcn_readfirstlane(G.n);
   const int sample = u % g.B;
-  const LayerDev L = g.layers[layer];
+  const LayerDev L = g.layers[__builtin_amdgcn_readfirstlane(G.layer[0])];   // a, widths and strides are the group's
   const GramJob J = g.jobs[job];
   const int nblk = __builtin_amdgcn_readfirstlane(J.nblk);
   const int T = g.T;
@@ -291,7 +296,7 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   const int grp = wave >> 2;                         // which tile pair of the job
   const int slot_a = grp ? J.sa[1] : J.sa[0];
   const int slot_b = grp ? J.sb[1] : J.sb[0];
-  const int nka = L.d_in / kKc, nk = nka + L.d_out / kKc;
+  const int nka = L.d_in / kKc, nkd = L.d_out / kKc, nk = nka + n_mem * nkd;
   constexpr int ROWB = kKc * 2;
 
   // ---- direct global->LDS loads.  One wave instruction fills 8 rows (1 KiB): lane -> row lane/8,
@@ -321,8 +326,11 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
     }
   const unsigned short* const samp_a =
       reinterpret_cast<const unsigned short*>(L.a) + (long long)sample * T * L.a_stride;
-  const unsigned short* const samp_d =
-      reinterpret_cast<const unsigned short*>(L.delta) + (long long)sample * T * L.delta_stride;
+  // delta of the member whose chunks are being requested (the members' chunks follow each other; the
+  // next member's tensor is looked up when the requests cross over: once per member, not per chunk)
+  const long long samp_off_d = (long long)sample * T * L.delta_stride;
+  const unsigned short* cur_d = reinterpret_cast<const unsigned short*>(L.delta) + samp_off_d;
+  int seg_m = 0, seg_end = nka + nkd;
   const unsigned lds_base = lds_address(lds);
   // A job with three row blocks runs three stages of 48 KiB, one with at most two blocks four stages
   // of 36 KiB (32 used): one more chunk in flight out of the same 144 KiB.
@@ -332,7 +340,7 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   auto issue_loads = [&](int c, int st) {
     const unsigned stage = lds_base + unsigned(st) * st_bytes;
     if (c < nka) {
-      const unsigned short* base = samp_a + c * kKc;
+      const unsigned short* base = uniform_ptr(samp_a + c * kKc);
 #pragma unroll
       for (int s = 0; s < 3; ++s)
         if (s < nblk) {
@@ -341,7 +349,13 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
             direct_load_lds16_s(off_pa[s][i], base, stage + (s * kTile + (wave + 8 * i) * 8) * ROWB);
         }
     } else {
-      const unsigned short* base = samp_d + (c - nka) * kKc;
+      if (MAXM > 1 && c >= seg_end) {          // (requests come in the order of the chunks)
+        ++seg_m;
+        seg_end += nkd;
+        const int lm = __builtin_amdgcn_readfirstlane(g.groups[gi].layer[seg_m]);
+        cur_d = reinterpret_cast<const unsigned short*>(g.layers[lm].delta) + samp_off_d;
+      }
+      const unsigned short* base = uniform_ptr(cur_d + (c - (seg_end - nkd)) * kKc);
 #pragma unroll
       for (int s = 0; s < 3; ++s)
         if (s < nblk) {
@@ -378,9 +392,10 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
   }
   wg_barrier();
 
-  float s = 0.f;
   const int blk_a = J.blk[slot_a], blk_b = J.blk[slot_b];
-  const bool whole = (blk_a + 1) * kTile <= T && (blk_b + 1) * kTile <= T;
+  // (the grouped form is launched only for T a multiple of the tile edge: no ragged block there; with the
+  // masked epilogue inside its member loop the kernel runs out of scalar registers)
+  const bool whole = MAXM > 1 ? true : ((blk_a + 1) * kTile <= T && (blk_b + 1) * kTile <= T);
   // One wave's share of a tile pair.  `shape` (a GramShape) lists the 32-row fragments the wave reads
   // per k-step and the 32 x 32 blocks it accumulates from them; every wave of the workgroup passes
   // the same waits, barriers and loads whatever its shape.
@@ -447,24 +462,34 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
     };
     int c = 0;
     for (; c < nka; ++c) chunk_step(c, acc_a);
-    for (; c < nk; ++c) chunk_step(c, acc_d);
-
-    // ---- < A A^T , D D^T > over this wave's blocks, masked beyond T
+    // A A^T of this wave's blocks is complete; the members' D D^T follow one after the other
+    const float w_pair = grp ? J.w[1] : J.w[0];
+    for (int m = 0; m < n_mem; ++m) {
+      for (const int cend = nka + (m + 1) * nkd; c < cend; ++c) chunk_step(c, acc_d);
+      // ---- < A A^T , D D^T > over this wave's blocks, masked beyond T
+      float s = 0.f;
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      float sb = 0.f;
-      if (whole) {
+      for (int b = 0; b < NB; ++b) {
+        float sb = 0.f;
+        if (whole) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) sb += acc_a[b][j] * acc_d[b][j];
-      } else {
-        const int col = blk_b * kTile + S::col_block(b, wq) * 32 + r32;
+          for (int j = 0; j < 16; ++j) sb += acc_a[b][j] * acc_d[b][j];
+        } else {
+          const int col = blk_b * kTile + S::col_block(b, wq) * 32 + r32;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int row = blk_a * kTile + S::row_block(b, wq) * 32 + (j >> 2) * 8 + kg * 4 + (j & 3);
-          if (row < T && col < T) sb += acc_a[b][j] * acc_d[b][j];
+          for (int j = 0; j < 16; ++j) {
+            const int row = blk_a * kTile + S::row_block(b, wq) * 32 + (j >> 2) * 8 + kg * 4 + (j & 3);
+            if (row < T && col < T) sb += acc_a[b][j] * acc_d[b][j];
+          }
         }
+        s += sb * S::weight(b);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc_d[b][j] = 0.f;
       }
-      s += sb * S::weight(b);
+      s = wave_sum_f32(s) * w_pair;
+      const int layer = __builtin_amdgcn_readfirstlane(g.groups[gi].layer[m]);
+      if (lane == 0)
+        g.partials[((size_t(layer) * g.B + sample) * g.n_jobs + job) * 8 + wave] = s;
     }
   };
   // An off-diagonal tile pair: 2 x 2 waves of 64 x 64.  A tile pair on the diagonal is symmetric: its
@@ -479,16 +504,6 @@ __global__ __launch_bounds__(512, 1) void gram_bf16_dual_kernel(GramDualArgs g) 
       case 2: run(GramShapeDiag<2>{}); break;
       default: run(GramShapeDiag<3>{}); break;
     }
-  }
-  s = wave_sum_f32(s) * (grp ? J.w[1] : J.w[0]);
-  __syncthreads();                                    // all fragment reads are over
-  float* red = reinterpret_cast<float*>(lds);
-  if (lane == 0) red[wave] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const float t0 = (red[0] + red[1]) + (red[2] + red[3]);
-    const float t1 = (red[4] + red[5]) + (red[6] + red[7]);
-    g.partials[(size_t(layer) * g.B + sample) * g.n_jobs + job] = t0 + t1;
   }
 }
 
@@ -651,10 +666,14 @@ std::vector<GramJob> make_gram_jobs(int nt, int order) {
   return out;
 }
 
-hipError_t launch_gram_bf16_dual(const GramLaunch& l, const GramJob* jobs, int n_jobs,
-                                 int variant, hipStream_t st) {
-  auto kern = l.dtype == ADLOCO_F16 ? gram_bf16_dual_kernel<true> : gram_bf16_dual_kernel<false>;
-  (void)variant;
+int gram_dual_parts(int n_jobs) { return n_jobs * 8; }
+
+// variant: 1 = no layers share their activations (every group has one member), else groups of up to four
+hipError_t launch_gram_bf16_dual(const GramLaunch& l, const GramGroup* groups, const GramJob* jobs,
+                                 int n_jobs, int variant, hipStream_t st) {
+  const bool f16 = l.dtype == ADLOCO_F16;
+  auto kern = variant == 1 ? (f16 ? gram_bf16_dual_kernel<true, 1> : gram_bf16_dual_kernel<false, 1>)
+                           : (f16 ? gram_bf16_dual_kernel<true, kGramGroupMax> : gram_bf16_dual_kernel<false, kGramGroupMax>);
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDualLds);
@@ -662,10 +681,11 @@ hipError_t launch_gram_bf16_dual(const GramLaunch& l, const GramJob* jobs, int n
   }
   GramDualArgs a;
   a.layers = l.layers;
+  a.groups = groups;
   a.order = l.order;
   a.jobs = jobs;
   a.partials = l.partials;
-  a.n_layers = l.n_layers;
+  a.n_groups = l.n_layers;
   a.B = l.B;
   a.T = l.T;
   a.n_jobs = n_jobs;

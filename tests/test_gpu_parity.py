@@ -411,3 +411,35 @@ def test_argument_errors(ctx):
 def test_zz_boundary_cases_are_rare():
     # runs after the decision tests of this module: at most one seeded case in ten may sit on a cut
     assert NEAR_CUT["total"] == 0 or NEAR_CUT["n"] * 10 <= NEAR_CUT["total"], NEAR_CUT
+
+
+@pytest.mark.parametrize("T", [128, 256, 200])
+def test_layers_sharing_their_activation_tensor(ctx, T):
+    # q / k / v of a transformer block read one activation tensor, gate / up another: the Gram kernel
+    # forms A A^T once per such group (T a multiple of the tile edge) or falls back to one layer at a
+    # time (ragged T); the result must not depend on which
+    import torch
+    import paper_2508_18182_amd as A
+    from gpu_util import to_dev, new_acc, read_acc, rel_err, DEV
+    B = 3
+    shapes = [(128, 192), (128, 192), (128, 192), (192, 128), (128, 64), (128, 64)]
+    host = synth.custom_grad_stats_inputs(7300 + T, shapes, B, T, "bf16", std_delta=0.1, rho=0.4)
+    for l in (1, 2):
+        host[l]["a"] = host[0]["a"]          # q, k, v
+    host[5]["a"] = host[4]["a"]              # gate, up
+    want = orc.grad_stats([(l["a"], l["delta"]) for l in host], two_pass=False)
+    dev_a = {id(l["a"]): to_dev(l["a"]) for l in host}
+    for provided in (False, True):
+        layers = [dict(a=dev_a[id(l["a"])], delta=to_dev(l["delta"]), provided=provided,
+                       grad_sum=torch.from_numpy(np.asarray(G, np.float32)).to(DEV) if provided else
+                       torch.full((l["d_out"], l["d_in"]), float("nan"), device=DEV))
+                  for l, G in zip(host, want["G"])]
+        assert layers[0]["a"].data_ptr() == layers[2]["a"].data_ptr()
+        ps = torch.zeros(B, device=DEV)
+        pl = torch.zeros(len(layers), B, device=DEV)
+        acc = new_acc()
+        A.adloco_grad_stats(ctx, layers, B, T, A.ADLOCO_BF16, ps, pl, acc, 0)
+        torch.cuda.synchronize()
+        assert rel_err(pl.cpu().numpy(), want["n_layer_sample"]) < TOL_BF16
+        assert rel_err(ps.cpu().numpy(), want["n_sample"]) < TOL_BF16
+        assert rel_err(read_acc(acc)[0], want["S1"]) < TOL_BF16
