@@ -450,7 +450,7 @@ static hipError_t launch_outer_drift_m(const OuterDriftArgs& a, bool vec, int bp
     if (a.n_grp > 0)
       hipLaunchKernelGGL(outer_step_drift_vec_kernel<M>,
                          dim3(unsigned((a.n_grp + kStreamThreads - 1) / kStreamThreads)),
-                         dim3(kStreamThreads), stream_lds_bytes(bpc, M + (a.mom ? 4 : 2)), st, a);
+                         dim3(kStreamThreads), stream_lds_bytes(bpc, M + (a.mom ? 2 : 1)), st, a);   // measured best: 7 per CU at M = 8
     if (a.n_grp * 8 < a.n)
       hipLaunchKernelGGL(outer_step_drift_scalar_kernel<M>, dim3(1), dim3(256), 0, st, a, a.n_grp * 8);
   } else {
@@ -466,7 +466,7 @@ static hipError_t launch_merge_drift_s(const MergeDriftArgs& a, bool vec, int bp
     if (a.n_grp > 0)
       hipLaunchKernelGGL(merge_drift_vec_kernel<S>,
                          dim3(unsigned((a.n_grp + kStreamThreads - 1) / kStreamThreads)),
-                         dim3(kStreamThreads), stream_lds_bytes(bpc, S + 2), st, a);
+                         dim3(kStreamThreads), stream_lds_bytes(bpc, S + 4), st, a);   // measured best: 6 per CU at S = 8
     if (a.n_grp * 8 < a.n)
       hipLaunchKernelGGL(merge_drift_scalar_kernel<S>, dim3(1), dim3(256), 0, st, a, a.n_grp * 8);
   } else {
