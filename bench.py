@@ -99,7 +99,7 @@ def source_hash():
 def measured_traffic(name):
     """HBM bytes per launch of kernel `name` from the rocprofv3 counter summary committed under
     profiles/ -- only if that summary carries the hash of the kernel sources of this build."""
-    path = os.path.join(ROOT, "profiles", "bench_round350m_hbm_traffic.md")
+    path = os.path.join(ROOT, "profiles", "bench_adloco350m_hbm_traffic.md")
     try:
         txt = open(path).read()
     except OSError:
@@ -110,7 +110,7 @@ def measured_traffic(name):
     for ln in txt.splitlines():
         parts = [p.strip() for p in ln.split("|")]
         if len(parts) >= 5 and parts[1] == name:
-            return float(parts[2]) + float(parts[3]), "profiles/bench_round350m_hbm_traffic.md (same kernel sources)"
+            return float(parts[2]) + float(parts[3]), "profiles/bench_adloco350m_hbm_traffic.md (same kernel sources)"
     return None, "kernel not in the counter summary"
 
 
