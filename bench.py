@@ -170,6 +170,13 @@ def build_round(torch, synth, A, ctx, args, dev, DT):
     N, M = ocfg["N"], ocfg["M"]
     fixed = (M + 2) * 4 * N + 5 * 4 * sum(di * do for _, di, do in shapes) + (6 << 30)
     n_sets = 8 if free - fixed > 8 * per_set_bytes else 4
+    while n_blocks > 1 and free - fixed < n_sets * per_set_bytes:
+        # a card with less free memory than four sets of the whole model: hold fewer transformer blocks
+        # (config.workload says how many)
+        n_blocks -= 1
+        linears = range(4 * n_blocks)
+        shapes = synth.linear_shapes(5)[:4 * n_blocks]
+        per_set_bytes = sum(2 * b_max * T * (di + do) for _, di, do in shapes)
     rhos_sched = synth.round_rho_schedule(eta, B_SCHEDULE, STAT_TARGETS)
     # which sets each outer step of the schedule accumulates, and the correlation they are drawn with:
     # step 0 -> set 0, step 1 -> sets 1, 2, step 2 -> sets 3..6, step 3 -> all eight (set 7 with its own)
