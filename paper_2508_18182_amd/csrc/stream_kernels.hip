@@ -655,7 +655,7 @@ extern "C" int adloco_inner_step(adloco_ctx* ctx, float* theta, float* exp_avg, 
     if (a.n_vec > 0)
       hipLaunchKernelGGL(inner_step_vec_kernel,
                          dim3(unsigned((a.n_vec + kStreamThreads - 1) / kStreamThreads)),
-                         dim3(kStreamThreads), stream_lds_bytes(ctx->stream_blocks_per_cu, 4), st, a);
+                         dim3(kStreamThreads), stream_lds_bytes(ctx->stream_blocks_per_cu, 5), st, a);   // measured best: 10-12 per CU
     if (a.n_vec * 4 < a.n)
       hipLaunchKernelGGL(inner_step_scalar_kernel, dim3(1), dim3(256), 0, st, a, a.n_vec * 4);
   } else {
